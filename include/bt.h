@@ -1,0 +1,176 @@
+/*
+ * bt.h -- C ABI of the padding-free BERT encoder forward for variable-length
+ * batches on AMD MI355X (gfx950).
+ *
+ * Conventions shared by every entry point
+ *   - Pointers named d_* are DEVICE pointers, h_* are HOST pointers.  The caller
+ *     owns all memory; the library never allocates, frees or keeps a pointer.
+ *   - fp16 tensors are passed as `const bt_half*` (IEEE binary16 bit patterns),
+ *     row-major, innermost dimension contiguous, base address 16-byte aligned.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  All
+ *     work is enqueued on it and nothing synchronises, with the one exception
+ *     stated at bt_build_offsets.
+ *   - Errors are return codes only.  Argument checks happen on the host before
+ *     any launch: a call that returns BT_ERR_INVALID_ARG / BT_ERR_UNSUPPORTED /
+ *     BT_ERR_WORKSPACE has enqueued nothing.  A failed launch gives BT_ERR_HIP.
+ *   - T == 0 or B == 0 is a valid no-op (BT_OK, no launch).  A sequence of
+ *     length 0 is allowed and contributes nothing.
+ *   - Weight matrices are [out_features, in_features] row-major (the reduction
+ *     dimension is contiguous), so y = x W^T + b.
+ *   - The calls are re-entrant: no global state.
+ */
+#ifndef BT_H_
+#define BT_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef uint16_t bt_half;   /* IEEE binary16 bit pattern */
+typedef void*    bt_stream; /* hipStream_t */
+
+typedef enum {
+  BT_OK = 0,
+  BT_ERR_INVALID_ARG = 1, /* null / misaligned pointer, negative size, bad length */
+  BT_ERR_UNSUPPORTED = 2, /* shape outside what the kernels are built for */
+  BT_ERR_WORKSPACE = 3,   /* workspace missing or too small */
+  BT_ERR_HIP = 4          /* a HIP runtime call or kernel launch failed */
+} bt_status;
+
+/* Static, never-NULL description of a status code. */
+const char* bt_status_string(bt_status s);
+
+/* Limits the kernels are built for. */
+#define BT_MAX_SEQ 4096  /* largest S accepted by bt_build_offsets */
+#define BT_HEAD_DIM 64   /* the only head size (standard BERT, Sec. III-B) */
+
+/*
+ * Zero-padding algorithm, Sec. III-D / Fig. 4: prefix sum of the mask matrix and
+ * the position array that maps packed tokens to the padded tensor.
+ *
+ * Exactly one of d_mask (int32 [B,S], entries 0 or 1, 1 = valid token) and
+ * d_lengths (int32 [B], sequence b has tokens 0..L_b-1 valid) is non-NULL.
+ * Outputs:
+ *   d_cu_seqlens int32 [B+1]  exclusive prefix sum of the per-sequence valid counts
+ *   d_token_idx  int32 [B*S]  capacity; the first T entries are written:
+ *                             token_idx[i] = b*S + t of the i-th valid token in
+ *                             row-major order
+ *   h_total      host int32   T = number of valid tokens
+ * This is the one call that synchronises: it waits for `stream` once so that
+ * *h_total is valid on return.  A length outside [0,S] or a mask entry outside
+ * {0,1} is detected on the device and reported as BT_ERR_INVALID_ARG after that
+ * wait (the outputs are then unspecified).  Requires 1 <= S <= BT_MAX_SEQ,
+ * B*S < 2^31.
+ */
+bt_status bt_build_offsets(const int32_t* d_mask, const int32_t* d_lengths, int B, int S,
+                           int32_t* d_cu_seqlens, int32_t* d_token_idx, int32_t* h_total,
+                           bt_stream stream);
+
+/*
+ * Pack (remove padding), Sec. III-D: d_packed[i,:] = d_padded[token_idx[i],:]
+ * for i < T.  d_padded is fp16 [B*S,H], d_packed fp16 [T,H]; H % 8 == 0.
+ * Bit-exact copy.  The two buffers must not overlap.
+ */
+bt_status bt_pack(const bt_half* d_padded, const int32_t* d_token_idx, int T, int H,
+                  bt_half* d_packed, bt_stream stream);
+
+/*
+ * Unpack (rebuild padding), Sec. III-D: d_padded[token_idx[i],:] = d_packed[i,:],
+ * every other row of d_padded [B*S,H] is written as zero.  token_idx must be
+ * strictly increasing (as bt_build_offsets writes it).  T <= B*S, H % 8 == 0.
+ */
+bt_status bt_unpack(const bt_half* d_packed, const int32_t* d_token_idx, int T, int B, int S, int H,
+                    bt_half* d_padded, bt_stream stream);
+
+/*
+ * Fused variable-length multi-head attention, eq. (1) and Sec. III-E: for every
+ * sequence b and head j,  O = softmax((Q+bq)(K+bk)^T * scale) (V+bv)  over the
+ * L_b = cu_seqlens[b+1]-cu_seqlens[b] tokens of that sequence only -- no padded
+ * row or column is ever read or computed.
+ *
+ * d_q, d_k, d_v point at token 0, head 0 of each operand; token i's head j starts
+ * at ptr + i*row_stride + j*head_dim (elements).  row_stride = 3*heads*head_dim
+ * with d_k = d_q + heads*head_dim, d_v = d_q + 2*heads*head_dim reads the fused
+ * [T, q|k|v] buffer GEMM #0 writes; row_stride = heads*head_dim reads three
+ * separate tensors.  row_stride % 8 == 0.
+ * d_bq/d_bk/d_bv: optional fp16 [heads*head_dim] biases (NULL = none), added in
+ * fp32 while the operands are loaded, as Alg. 1 fuses them.
+ * d_out: fp16 [T, heads*head_dim], heads concatenated inside a row.
+ * max_len: an upper bound on every L_b (sizes the grid; a longer sequence is an
+ * error the host cannot see: its extra rows are NOT computed).
+ * head_dim must be BT_HEAD_DIM.  d_ws/ws_bytes: reserved, may be NULL/0.
+ * Logits, softmax statistics and accumulators are fp32; the probabilities enter
+ * the second contraction as fp16.
+ */
+bt_status bt_varlen_mha(const bt_half* d_q, const bt_half* d_k, const bt_half* d_v, int64_t row_stride,
+                        const bt_half* d_bq, const bt_half* d_bk, const bt_half* d_bv,
+                        const int32_t* d_cu_seqlens, int B, int T, int max_len, int heads, int head_dim,
+                        float scale, bt_half* d_out, void* d_ws, size_t ws_bytes, bt_stream stream);
+
+/*
+ * Packed GEMM with fused epilogue, Sec. III-C2: C = act(A W^T + bias).
+ * A fp16 [M,K], W fp16 [N,K], bias fp16 [N] or NULL, C fp16 [M,N]; fp32
+ * accumulation; the bias and the activation are applied to the fp32 accumulators
+ * before the single rounding to fp16.  K % 8 == 0, N % 8 == 0.
+ */
+typedef enum { BT_ACT_NONE = 0, BT_ACT_GELU_ERF = 1, BT_ACT_GELU_TANH = 2 } bt_act;
+bt_status bt_gemm_bias_act(const bt_half* d_A, const bt_half* d_W, const bt_half* d_bias, int M, int N, int K,
+                           bt_act act, bt_half* d_C, bt_stream stream);
+
+/*
+ * Fused add-bias + residual + LayerNorm, Sec. III-C1:
+ *   y[i,:] = LN(x[i,:] + bias + residual[i,:]) * gamma + beta,   one pass over memory.
+ * x, residual, y fp16 [T,H]; bias, gamma, beta fp16 [H]; bias may be NULL.
+ * Statistics in fp32, biased variance, eps inside the square root.
+ * H % 8 == 0, H <= 8192.  y may alias x or residual.
+ */
+bt_status bt_add_bias_residual_layernorm(const bt_half* d_x, const bt_half* d_bias, const bt_half* d_residual,
+                                         const bt_half* d_gamma, const bt_half* d_beta, float eps, int T, int H,
+                                         bt_half* d_y, bt_stream stream);
+
+/*
+ * One encoder layer's parameters (device pointers, fp16).  Shapes:
+ *   w_qkv [3H,H]  rows 0..H-1 produce Q, H..2H-1 K, 2H..3H-1 V;   b_qkv [3H]
+ *   w_o [H,H], b_o [H];  ln0_g, ln0_b [H]
+ *   w_1 [F,H], b_1 [F];  w_2 [H,F], b_2 [H];  ln1_g, ln1_b [H]
+ * gelu_kind: 0 = exact (erf), 1 = tanh approximation.
+ */
+typedef struct {
+  int H, heads, head_dim, F;
+  float ln_eps;
+  int gelu_kind;
+  const bt_half *w_qkv, *b_qkv, *w_o, *b_o, *ln0_g, *ln0_b, *w_1, *b_1, *w_2, *b_2, *ln1_g, *ln1_b;
+} bt_layer;
+
+/* Bytes of workspace bt_encoder_layer_fwd / bt_encoder_fwd need for T tokens. */
+size_t bt_layer_workspace_bytes(const bt_layer* layer, int T, int B, int max_len);
+
+/*
+ * One padding-free post-LN BERT encoder layer on packed tokens, Fig. 2(c):
+ *   QKV = x W_qkv^T + b_qkv;  A = varlen MHA(QKV);  y1 = LN(A W_o^T + b_o + x);
+ *   y  = LN(GELU(y1 W_1^T + b_1) W_2^T + b_2 + y1).
+ * d_x, d_y fp16 [T,H] (must not alias); d_ws 256-byte aligned, at least
+ * bt_layer_workspace_bytes() bytes.  H == heads*head_dim, head_dim == BT_HEAD_DIM.
+ */
+bt_status bt_encoder_layer_fwd(const bt_layer* layer, const bt_half* d_x, const int32_t* d_cu_seqlens,
+                               int B, int T, int max_len, bt_half* d_y, void* d_ws, size_t ws_bytes,
+                               bt_stream stream);
+
+/*
+ * A stack of n_layers encoder layers (Sec. IV-E): layer i+1 reads layer i's
+ * output.  `layers` is a HOST array of n_layers descriptors with identical
+ * H/heads/F.  The workspace (sized by bt_layer_workspace_bytes) also holds the
+ * ping-pong buffer between layers; d_x is not modified; d_y receives the last
+ * layer's output.
+ */
+bt_status bt_encoder_fwd(const bt_layer* layers, int n_layers, const bt_half* d_x,
+                         const int32_t* d_cu_seqlens, int B, int T, int max_len, bt_half* d_y,
+                         void* d_ws, size_t ws_bytes, bt_stream stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* BT_H_ */

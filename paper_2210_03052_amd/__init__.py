@@ -1,0 +1,283 @@
+"""Thin ctypes binding of libbt.so, the C-ABI HIP library (see include/bt.h).
+
+Argument marshalling only: every function checks dtypes / devices, allocates
+the output tensors with torch (device memory and streams are torch's), and
+passes raw device pointers plus the current HIP stream to the entry point of
+the same name.  No step of the path is computed here, and there is no
+fallback: if the library is not built, ``load_library`` raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "libbt.so")
+
+BT_OK = 0
+ACT_NONE, ACT_GELU_ERF, ACT_GELU_TANH = 0, 1, 2
+_c = ctypes
+_lib = None
+
+
+class BtError(RuntimeError):
+    def __init__(self, code, where):
+        self.code = int(code)
+        msg = _lib.bt_status_string(code).decode() if _lib is not None else str(code)
+        super().__init__(f"{where}: {msg} (status {int(code)})")
+
+
+class bt_layer(_c.Structure):
+    _fields_ = [("H", _c.c_int), ("heads", _c.c_int), ("head_dim", _c.c_int), ("F", _c.c_int),
+                ("ln_eps", _c.c_float), ("gelu_kind", _c.c_int)] + [
+        (n, _c.c_void_p) for n in ("w_qkv", "b_qkv", "w_o", "b_o", "ln0_g", "ln0_b",
+                                   "w_1", "b_1", "w_2", "b_2", "ln1_g", "ln1_b")]
+
+
+PARAM_NAMES = ("w_qkv", "b_qkv", "w_o", "b_o", "ln0_g", "ln0_b", "w_1", "b_1", "w_2", "b_2", "ln1_g", "ln1_b")
+
+_SIGNATURES = {
+    "bt_status_string": (_c.c_char_p, [_c.c_int]),
+    "bt_build_offsets": (_c.c_int, [_c.c_void_p, _c.c_void_p, _c.c_int, _c.c_int, _c.c_void_p, _c.c_void_p,
+                                    _c.POINTER(_c.c_int32), _c.c_void_p]),
+    "bt_pack": (_c.c_int, [_c.c_void_p, _c.c_void_p, _c.c_int, _c.c_int, _c.c_void_p, _c.c_void_p]),
+    "bt_unpack": (_c.c_int, [_c.c_void_p, _c.c_void_p, _c.c_int, _c.c_int, _c.c_int, _c.c_int, _c.c_void_p,
+                             _c.c_void_p]),
+    "bt_varlen_mha": (_c.c_int, [_c.c_void_p, _c.c_void_p, _c.c_void_p, _c.c_int64, _c.c_void_p, _c.c_void_p,
+                                 _c.c_void_p, _c.c_void_p, _c.c_int, _c.c_int, _c.c_int, _c.c_int, _c.c_int,
+                                 _c.c_float, _c.c_void_p, _c.c_void_p, _c.c_size_t, _c.c_void_p]),
+    "bt_gemm_bias_act": (_c.c_int, [_c.c_void_p, _c.c_void_p, _c.c_void_p, _c.c_int, _c.c_int, _c.c_int, _c.c_int,
+                                    _c.c_void_p, _c.c_void_p]),
+    "bt_add_bias_residual_layernorm": (_c.c_int, [_c.c_void_p, _c.c_void_p, _c.c_void_p, _c.c_void_p, _c.c_void_p,
+                                                  _c.c_float, _c.c_int, _c.c_int, _c.c_void_p, _c.c_void_p]),
+    "bt_layer_workspace_bytes": (_c.c_size_t, [_c.POINTER(bt_layer), _c.c_int, _c.c_int, _c.c_int]),
+    "bt_encoder_layer_fwd": (_c.c_int, [_c.POINTER(bt_layer), _c.c_void_p, _c.c_void_p, _c.c_int, _c.c_int,
+                                        _c.c_int, _c.c_void_p, _c.c_void_p, _c.c_size_t, _c.c_void_p]),
+    "bt_encoder_fwd": (_c.c_int, [_c.POINTER(bt_layer), _c.c_int, _c.c_void_p, _c.c_void_p, _c.c_int, _c.c_int,
+                                  _c.c_int, _c.c_void_p, _c.c_void_p, _c.c_size_t, _c.c_void_p]),
+}
+EXPORTED = tuple(_SIGNATURES)
+
+
+def load_library(path: str | None = None):
+    """dlopen libbt.so and declare the prototypes.  Raises if it is missing."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    path = path or LIB_PATH
+    if not os.path.exists(path):
+        raise RuntimeError(f"{path} is not built: run `python -m paper_2210_03052_amd.build` "
+                           "(there is no CPU fallback)")
+    lib = _c.CDLL(path)
+    for name, (res, args) in _SIGNATURES.items():
+        fn = getattr(lib, name)
+        fn.restype, fn.argtypes = res, args
+    _lib = lib
+    return lib
+
+
+# ------------------------------------------------------------------ helpers
+def _torch():
+    import torch
+    return torch
+
+
+def _stream():
+    return _c.c_void_p(_torch().cuda.current_stream().cuda_stream)
+
+
+def _ptr(t):
+    return _c.c_void_p(t.data_ptr()) if t is not None else _c.c_void_p(0)
+
+
+def _chk(t, dtype, name, ndim=None):
+    torch = _torch()
+    if not isinstance(t, torch.Tensor) or not t.is_cuda or t.dtype != dtype or not t.is_contiguous():
+        raise TypeError(f"{name}: expected a contiguous CUDA tensor of dtype {dtype}")
+    if ndim is not None and t.dim() != ndim:
+        raise TypeError(f"{name}: expected {ndim} dimensions, got {t.dim()}")
+
+
+def _call(name, *args):
+    lib = load_library()
+    st = getattr(lib, name)(*args)
+    if st != BT_OK:
+        raise BtError(st, name)
+
+
+# ------------------------------------------------------------------ entry points
+def build_offsets(mask=None, lengths=None, S=None):
+    """bt_build_offsets.  Returns (cu_seqlens int32[B+1], token_idx int32[T], T)."""
+    torch = _torch()
+    if (mask is None) == (lengths is None):
+        raise ValueError("give exactly one of mask / lengths")
+    if mask is not None:
+        _chk(mask, torch.int32, "mask", 2)
+        B, S = mask.shape
+        dev = mask.device
+    else:
+        _chk(lengths, torch.int32, "lengths", 1)
+        if S is None:
+            raise ValueError("S is required with lengths")
+        B, dev = lengths.shape[0], lengths.device
+    cu = torch.empty(B + 1, dtype=torch.int32, device=dev)
+    tok = torch.empty(max(1, B * S), dtype=torch.int32, device=dev)
+    total = _c.c_int32(-1)
+    _call("bt_build_offsets", _ptr(mask), _ptr(lengths), B, int(S), _ptr(cu), _ptr(tok), _c.byref(total), _stream())
+    T = int(total.value)
+    return cu, tok[:T], T
+
+
+def pack(padded, token_idx, out=None):
+    """bt_pack: padded fp16 [B,S,H] or [B*S,H] -> packed fp16 [T,H]."""
+    torch = _torch()
+    _chk(padded, torch.float16, "padded")
+    _chk(token_idx, torch.int32, "token_idx", 1)
+    H, T = padded.shape[-1], token_idx.shape[0]
+    if out is None:
+        out = torch.empty((T, H), dtype=torch.float16, device=padded.device)
+    _call("bt_pack", _ptr(padded), _ptr(token_idx), T, H, _ptr(out), _stream())
+    return out
+
+
+def unpack(packed, token_idx, B, S, out=None):
+    """bt_unpack: packed fp16 [T,H] -> padded fp16 [B,S,H], pads zero."""
+    torch = _torch()
+    _chk(packed, torch.float16, "packed", 2)
+    _chk(token_idx, torch.int32, "token_idx", 1)
+    T, H = packed.shape
+    if out is None:
+        out = torch.empty((B, S, H), dtype=torch.float16, device=packed.device)
+    _call("bt_unpack", _ptr(packed), _ptr(token_idx), T, B, S, H, _ptr(out), _stream())
+    return out
+
+
+def varlen_mha(qkv, cu_seqlens, max_len, heads, head_dim=64, scale=None, bq=None, bk=None, bv=None, out=None):
+    """bt_varlen_mha on the fused packed buffer qkv fp16 [T, 3*heads*head_dim]."""
+    torch = _torch()
+    _chk(qkv, torch.float16, "qkv", 2)
+    _chk(cu_seqlens, torch.int32, "cu_seqlens", 1)
+    HD = heads * head_dim
+    T, B = qkv.shape[0], cu_seqlens.shape[0] - 1
+    if qkv.shape[1] != 3 * HD:
+        raise ValueError("qkv must be [T, 3*heads*head_dim]")
+    for b_, n in ((bq, "bq"), (bk, "bk"), (bv, "bv")):
+        if b_ is not None:
+            _chk(b_, torch.float16, n, 1)
+    if scale is None:
+        scale = head_dim ** -0.5
+    if out is None:
+        out = torch.empty((T, HD), dtype=torch.float16, device=qkv.device)
+    base, es = qkv.data_ptr(), qkv.element_size()
+    _call("bt_varlen_mha", _c.c_void_p(base), _c.c_void_p(base + HD * es), _c.c_void_p(base + 2 * HD * es),
+          3 * HD, _ptr(bq), _ptr(bk), _ptr(bv), _ptr(cu_seqlens), B, T, int(max_len), heads, head_dim,
+          float(scale), _ptr(out), _c.c_void_p(0), 0, _stream())
+    return out
+
+
+def varlen_mha_separate(q, k, v, cu_seqlens, max_len, heads, head_dim=64, scale=None, out=None):
+    """bt_varlen_mha on three separate packed tensors fp16 [T, heads*head_dim]."""
+    torch = _torch()
+    for t, n in ((q, "q"), (k, "k"), (v, "v")):
+        _chk(t, torch.float16, n, 2)
+    _chk(cu_seqlens, torch.int32, "cu_seqlens", 1)
+    HD = heads * head_dim
+    T, B = q.shape[0], cu_seqlens.shape[0] - 1
+    if scale is None:
+        scale = head_dim ** -0.5
+    if out is None:
+        out = torch.empty((T, HD), dtype=torch.float16, device=q.device)
+    _call("bt_varlen_mha", _ptr(q), _ptr(k), _ptr(v), HD, None, None, None, _ptr(cu_seqlens), B, T, int(max_len),
+          heads, head_dim, float(scale), _ptr(out), _c.c_void_p(0), 0, _stream())
+    return out
+
+
+def gemm_bias_act(a, w, bias=None, act=ACT_NONE, out=None):
+    """bt_gemm_bias_act: act(a [M,K] @ w[N,K]^T + bias) -> fp16 [M,N]."""
+    torch = _torch()
+    _chk(a, torch.float16, "a", 2)
+    _chk(w, torch.float16, "w", 2)
+    if bias is not None:
+        _chk(bias, torch.float16, "bias", 1)
+    M, K = a.shape
+    N = w.shape[0]
+    if w.shape[1] != K:
+        raise ValueError("w must be [N,K]")
+    if out is None:
+        out = torch.empty((M, N), dtype=torch.float16, device=a.device)
+    _call("bt_gemm_bias_act", _ptr(a), _ptr(w), _ptr(bias), M, N, K, int(act), _ptr(out), _stream())
+    return out
+
+
+def add_bias_residual_layernorm(x, bias, residual, gamma, beta, eps, out=None):
+    """bt_add_bias_residual_layernorm on fp16 [T,H]."""
+    torch = _torch()
+    _chk(x, torch.float16, "x", 2)
+    _chk(residual, torch.float16, "residual", 2)
+    T, H = x.shape
+    if out is None:
+        out = torch.empty_like(x)
+    _call("bt_add_bias_residual_layernorm", _ptr(x), _ptr(bias), _ptr(residual), _ptr(gamma), _ptr(beta),
+          float(eps), T, H, _ptr(out), _stream())
+    return out
+
+
+class Layer:
+    """Device copies of one layer's parameters plus the C descriptor."""
+
+    def __init__(self, params: dict, device="cuda:0", gelu_kind=0):
+        torch = _torch()
+        self.tensors = {}
+        for n in PARAM_NAMES:
+            t = params[n]
+            if not isinstance(t, torch.Tensor):
+                t = torch.from_numpy(t)
+            self.tensors[n] = t.to(device=device, dtype=torch.float16).contiguous()
+        self.H = int(self.tensors["w_o"].shape[0])
+        self.F = int(self.tensors["w_1"].shape[0])
+        self.heads = int(params["heads"])
+        self.head_dim = int(params.get("head_dim", self.H // self.heads))
+        self.eps = float(params.get("eps", 1e-12))
+        self.desc = bt_layer(self.H, self.heads, self.head_dim, self.F, self.eps, int(gelu_kind),
+                             *[self.tensors[n].data_ptr() for n in PARAM_NAMES])
+
+
+def layer_workspace_bytes(layer: Layer, T, B, max_len):
+    return int(load_library().bt_layer_workspace_bytes(_c.byref(layer.desc), T, B, max_len))
+
+
+def _workspace(layer, T, B, max_len, device):
+    torch = _torch()
+    n = layer_workspace_bytes(layer, T, B, max_len)
+    return torch.empty(max(n, 256), dtype=torch.uint8, device=device), n
+
+
+def encoder_layer_fwd(layer: Layer, x, cu_seqlens, max_len, out=None, ws=None):
+    """bt_encoder_layer_fwd: packed fp16 [T,H] -> packed fp16 [T,H]."""
+    torch = _torch()
+    _chk(x, torch.float16, "x", 2)
+    _chk(cu_seqlens, torch.int32, "cu_seqlens", 1)
+    T, B = x.shape[0], cu_seqlens.shape[0] - 1
+    if out is None:
+        out = torch.empty_like(x)
+    if ws is None:
+        ws, _ = _workspace(layer, T, B, max_len, x.device)
+    _call("bt_encoder_layer_fwd", _c.byref(layer.desc), _ptr(x), _ptr(cu_seqlens), B, T, int(max_len), _ptr(out),
+          _ptr(ws), ws.numel(), _stream())
+    return out
+
+
+def encoder_fwd(layers, x, cu_seqlens, max_len, out=None, ws=None):
+    """bt_encoder_fwd: the stack of layers on packed fp16 [T,H]."""
+    torch = _torch()
+    _chk(x, torch.float16, "x", 2)
+    _chk(cu_seqlens, torch.int32, "cu_seqlens", 1)
+    T, B = x.shape[0], cu_seqlens.shape[0] - 1
+    if out is None:
+        out = torch.empty_like(x)
+    if ws is None:
+        ws, _ = _workspace(layers[0], T, B, max_len, x.device)
+    arr = (bt_layer * len(layers))(*[l.desc for l in layers])
+    _call("bt_encoder_fwd", arr, len(layers), _ptr(x), _ptr(cu_seqlens), B, T, int(max_len), _ptr(out), _ptr(ws),
+          ws.numel(), _stream())
+    return out

@@ -1,0 +1,106 @@
+// Fused add-bias + residual + LayerNorm (Sec. III-C1): one trip over memory.
+// One wavefront owns one token row; the row lives in registers between the
+// single 128-bit load and the single 128-bit store.  Mean and variance are fp32,
+// two-pass over the registers (no E[x^2]-E[x]^2 cancellation).
+#include "common.h"
+
+namespace bt {
+
+// CPL = 16-byte chunks per lane; a row has H/8 chunks, chunk c = lane + 64*i.
+template <int CPL>
+__global__ __launch_bounds__(256) void bias_residual_ln_kernel(const half_t* x,
+                                                               const half_t* __restrict__ bias,
+                                                               const half_t* residual,
+                                                               const half_t* __restrict__ gamma,
+                                                               const half_t* __restrict__ beta, float eps, int T,
+                                                               int H, half_t* y) {
+  const int lane = threadIdx.x & 63;
+  const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (row >= T) return;
+  const int chunks = H >> 3;
+  const size_t base = (size_t)row * H;
+
+  float v[CPL][8];
+  float sum = 0.f;
+#pragma unroll
+  for (int i = 0; i < CPL; ++i) {
+    const int c = lane + i * kWave;
+    if (c < chunks) {
+      const half8_t a = *reinterpret_cast<const half8_t*>(x + base + c * 8);
+      const half8_t r = *reinterpret_cast<const half8_t*>(residual + base + c * 8);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) v[i][e] = (float)a[e] + (float)r[e];
+      if (bias) {
+        const half8_t b = *reinterpret_cast<const half8_t*>(bias + c * 8);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) v[i][e] += (float)b[e];
+      }
+#pragma unroll
+      for (int e = 0; e < 8; ++e) sum += v[i][e];
+    } else {
+#pragma unroll
+      for (int e = 0; e < 8; ++e) v[i][e] = 0.f;
+    }
+  }
+  const float inv_h = 1.0f / (float)H;
+  const float mean = wave_sum(sum) * inv_h;
+  float sq = 0.f;
+#pragma unroll
+  for (int i = 0; i < CPL; ++i) {
+    if (lane + i * kWave < chunks) {
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        const float d = v[i][e] - mean;
+        sq += d * d;
+      }
+    }
+  }
+  const float rstd = rsqrtf(wave_sum(sq) * inv_h + eps);
+#pragma unroll
+  for (int i = 0; i < CPL; ++i) {
+    const int c = lane + i * kWave;
+    if (c < chunks) {
+      const half8_t g = *reinterpret_cast<const half8_t*>(gamma + c * 8);
+      const half8_t b = *reinterpret_cast<const half8_t*>(beta + c * 8);
+      half8_t o;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) o[e] = (half_t)((v[i][e] - mean) * rstd * (float)g[e] + (float)b[e]);
+      *reinterpret_cast<half8_t*>(y + base + c * 8) = o;
+    }
+  }
+}
+
+bt_status layernorm_dispatch(const bt_half* x, const bt_half* bias, const bt_half* residual, const bt_half* gamma,
+                             const bt_half* beta, float eps, int T, int H, bt_half* y, hipStream_t st) {
+  const half_t* px = reinterpret_cast<const half_t*>(x);
+  const half_t* pb = reinterpret_cast<const half_t*>(bias);
+  const half_t* pr = reinterpret_cast<const half_t*>(residual);
+  const half_t* pg = reinterpret_cast<const half_t*>(gamma);
+  const half_t* pe = reinterpret_cast<const half_t*>(beta);
+  half_t* py = reinterpret_cast<half_t*>(y);
+  const int chunks = H / 8;
+  dim3 grid((T + 3) / 4), block(256);
+  if (chunks <= 64) bias_residual_ln_kernel<1><<<grid, block, 0, st>>>(px, pb, pr, pg, pe, eps, T, H, py);
+  else if (chunks <= 128) bias_residual_ln_kernel<2><<<grid, block, 0, st>>>(px, pb, pr, pg, pe, eps, T, H, py);
+  else if (chunks <= 256) bias_residual_ln_kernel<4><<<grid, block, 0, st>>>(px, pb, pr, pg, pe, eps, T, H, py);
+  else if (chunks <= 512) bias_residual_ln_kernel<8><<<grid, block, 0, st>>>(px, pb, pr, pg, pe, eps, T, H, py);
+  else bias_residual_ln_kernel<16><<<grid, block, 0, st>>>(px, pb, pr, pg, pe, eps, T, H, py);
+  return launch_status();
+}
+
+}  // namespace bt
+
+extern "C" bt_status bt_add_bias_residual_layernorm(const bt_half* d_x, const bt_half* d_bias,
+                                                    const bt_half* d_residual, const bt_half* d_gamma,
+                                                    const bt_half* d_beta, float eps, int T, int H, bt_half* d_y,
+                                                    bt_stream stream) {
+  if (T < 0 || H < 8 || (H % 8) != 0 || !(eps >= 0.f)) return BT_ERR_INVALID_ARG;
+  if (H > 8192) return BT_ERR_UNSUPPORTED;
+  if (T == 0) return BT_OK;
+  if (!d_x || !d_residual || !d_gamma || !d_beta || !d_y) return BT_ERR_INVALID_ARG;
+  if (!bt::aligned16(d_x) || !bt::aligned16(d_residual) || !bt::aligned16(d_gamma) || !bt::aligned16(d_beta) ||
+      !bt::aligned16(d_y) || (d_bias && !bt::aligned16(d_bias)))
+    return BT_ERR_INVALID_ARG;
+  return bt::layernorm_dispatch(d_x, d_bias, d_residual, d_gamma, d_beta, eps, T, H, d_y,
+                                static_cast<hipStream_t>(stream));
+}

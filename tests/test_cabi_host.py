@@ -1,0 +1,107 @@
+"""Host-side checks of the C-ABI library that need no GPU: it loads, exports
+every symbol the header declares, and rejects bad arguments before any launch."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2210_03052_amd as bt
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(bt.LIB_PATH):
+        from paper_2210_03052_amd.build import build_library
+        build_library(verbose=False)
+    return bt.load_library()
+
+
+def _declared_symbols():
+    text = open(os.path.join(ROOT, "include", "bt.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(bt_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_header_symbols_exported(lib):
+    names = _declared_symbols()
+    assert "bt_varlen_mha" in names and "bt_encoder_layer_fwd" in names and len(names) >= 10
+    for n in names:
+        assert hasattr(lib, n), f"{n} declared in bt.h but not exported"
+    assert set(names) == set(bt.EXPORTED)
+
+
+def test_status_strings(lib):
+    seen = {lib.bt_status_string(i) for i in range(5)}
+    assert len(seen) == 5 and all(s for s in seen)
+    assert lib.bt_status_string(99)
+
+
+def test_argument_errors_before_launch(lib):
+    one = ctypes.c_void_p(16)      # non-null, aligned, never dereferenced: calls fail before any launch
+    odd = ctypes.c_void_p(24)
+    tot = ctypes.c_int32(0)
+    # build_offsets: both or neither of mask/lengths, bad sizes
+    assert lib.bt_build_offsets(None, None, 2, 8, one, one, ctypes.byref(tot), None) == 1
+    assert lib.bt_build_offsets(one, one, 2, 8, one, one, ctypes.byref(tot), None) == 1
+    assert lib.bt_build_offsets(one, None, 2, 0, one, one, ctypes.byref(tot), None) == 1
+    assert lib.bt_build_offsets(one, None, 2, 1 << 20, one, one, ctypes.byref(tot), None) == 2
+    # pack / unpack
+    assert lib.bt_pack(one, one, 4, 7, one, None) == 1
+    assert lib.bt_pack(one, one, -1, 8, one, None) == 1
+    assert lib.bt_pack(one, one, 0, 8, one, None) == 0          # T == 0: no-op
+    assert lib.bt_pack(odd, one, 4, 8, one, None) == 1          # misaligned
+    assert lib.bt_unpack(one, one, 100, 2, 8, 8, one, None) == 1  # T > B*S
+    assert lib.bt_unpack(one, one, 0, 0, 8, 8, one, None) == 0
+    # mha
+    f = ctypes.c_float(0.125)
+    assert lib.bt_varlen_mha(one, one, one, 2304, None, None, None, one, 2, 10, 8, 12, 32, f, one, None, 0, None) == 2
+    assert lib.bt_varlen_mha(one, one, one, 100, None, None, None, one, 2, 10, 8, 12, 64, f, one, None, 0, None) == 1
+    assert lib.bt_varlen_mha(one, one, one, 2304, None, None, None, one, 2, 100, 8, 12, 64, f, one, None, 0, None) == 1
+    assert lib.bt_varlen_mha(one, one, one, 2304, None, None, None, one, 0, 0, 8, 12, 64, f, one, None, 0, None) == 0
+    assert lib.bt_varlen_mha(one, one, one, 2304, None, None, None, one, 2, 10, 8, 12, 64, ctypes.c_float(-1.0),
+                             one, None, 0, None) == 1
+    # gemm / layernorm
+    assert lib.bt_gemm_bias_act(one, one, None, 4, 12, 64, 0, one, None) == 1   # N % 8
+    assert lib.bt_gemm_bias_act(one, one, None, 4, 16, 60, 0, one, None) == 1   # K % 8
+    assert lib.bt_gemm_bias_act(one, one, None, 4, 16, 64, 7, one, None) == 1   # bad activation
+    assert lib.bt_gemm_bias_act(one, one, None, 0, 16, 64, 0, one, None) == 0
+    assert lib.bt_add_bias_residual_layernorm(one, None, one, one, one, ctypes.c_float(1e-12), 4, 12, one, None) == 1
+    assert lib.bt_add_bias_residual_layernorm(one, None, one, one, one, ctypes.c_float(1e-12), 4, 16384, one,
+                                              None) == 2
+
+
+def test_layer_checks(lib):
+    one = 256
+    good = bt.bt_layer(768, 12, 64, 3072, 1e-12, 0, *[one] * 12)
+    n = lib.bt_layer_workspace_bytes(ctypes.byref(good), 100, 4, 64)
+    # qkv + attn + proj + y1 + g + ping + pong, each 256-byte aligned
+    assert n >= 2 * 100 * (3 * 768 + 5 * 768 + 3072) and n % 256 == 0
+    assert lib.bt_layer_workspace_bytes(ctypes.byref(good), 0, 4, 64) == 0
+    x, y, cu, ws = ctypes.c_void_p(256), ctypes.c_void_p(512), ctypes.c_void_p(768), ctypes.c_void_p(1024)
+    call = lambda L, T=100, ws_=ws, nbytes=n, y_=y: lib.bt_encoder_layer_fwd(
+        ctypes.byref(L), x, cu, 4, T, 64, y_, ws_, nbytes, None)
+    assert call(good, nbytes=n - 1) == 3                       # workspace too small
+    assert call(good, ws_=None) == 3
+    assert call(good, y_=x) == 1                               # in-place not allowed
+    assert call(good, T=0) == 0
+    assert call(good, T=4 * 64 + 1) == 1                       # more tokens than B*max_len
+    assert call(bt.bt_layer(768, 12, 32, 3072, 1e-12, 0, *[one] * 12)) == 2      # head_dim
+    assert call(bt.bt_layer(768, 10, 64, 3072, 1e-12, 0, *[one] * 12)) == 2      # H != heads*d
+    assert call(bt.bt_layer(768, 12, 64, 3072, 1e-12, 5, *[one] * 12)) == 1      # gelu kind
+    assert call(bt.bt_layer(768, 12, 64, 3072, 1e-12, 0, *([one] * 11 + [0]))) == 1  # null parameter
+    arr = (bt.bt_layer * 2)(good, bt.bt_layer(1024, 16, 64, 4096, 1e-12, 0, *[one] * 12))
+    assert lib.bt_encoder_fwd(arr, 2, x, cu, 4, 100, 64, y, ws, n, None) == 1  # mixed shapes
+    assert lib.bt_encoder_fwd(arr, 0, x, cu, 4, 100, 64, y, ws, n, None) == 1
+
+
+def test_no_fallback_when_library_missing(tmp_path):
+    import importlib
+    mod = importlib.reload(bt)
+    try:
+        with pytest.raises(RuntimeError, match="not built"):
+            mod.load_library(str(tmp_path / "missing.so"))
+    finally:
+        importlib.reload(bt)

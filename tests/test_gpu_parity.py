@@ -1,0 +1,311 @@
+"""GPU parity tests: the HIP path (through the C ABI) against the fp64 CPU oracle
+on the same seeded inputs.  Integer / byte work is bit-exact; fp16 outputs are
+within max-abs 1e-2 per layer and 5e-2 after 12 layers (1e-1 after 24)."""
+import numpy as np
+import pytest
+
+from oracle import bt_oracle as O
+from paper_2210_03052_amd import inputs as I
+
+pytestmark = pytest.mark.gpu
+
+TOL_LAYER = 1e-2
+TOL_12 = 5e-2
+TOL_24 = 1e-1
+
+
+def dev(a):
+    import torch
+    return torch.from_numpy(np.ascontiguousarray(a)).to("cuda:0")
+
+
+def host(t):
+    return t.detach().cpu().numpy()
+
+
+def oracle_layers(wl, n, stress=False):
+    return [O.LayerWeights(**I.make_layer_params(wl, i, stress)) for i in range(n)]
+
+
+# ------------------------------------------------------------------ offsets / pack / unpack
+def test_offsets_fig4(bt):
+    mask = O.lengths_to_mask([5, 2, 4], 5)
+    cu, tok, T = bt.build_offsets(mask=dev(mask))
+    rcu, rtok, rT = O.build_offsets(mask)
+    assert T == rT == 11
+    assert np.array_equal(host(cu), rcu) and np.array_equal(host(tok), rtok)
+
+
+@pytest.mark.parametrize("B,S,p", [(1, 1, 1.0), (3, 64, 0.5), (16, 256, 0.6), (17, 65, 0.3), (70, 100, 0.7),
+                                   (200, 33, 0.5), (4, 1000, 0.9), (2, 4096, 0.5), (5, 40, 0.0)])
+def test_offsets_any_mask(bt, B, S, p):
+    rng = np.random.default_rng(B * 1000 + S)
+    mask = (rng.random((B, S)) < p).astype(np.int32)
+    cu, tok, T = bt.build_offsets(mask=dev(mask))
+    rcu, rtok, rT = O.build_offsets(mask)
+    assert T == rT
+    assert np.array_equal(host(cu), rcu) and np.array_equal(host(tok), rtok)
+
+
+@pytest.mark.parametrize("name", list(I.WORKLOADS))
+def test_offsets_from_lengths_workloads(bt, name):
+    wl = I.WORKLOADS[name]
+    L = I.draw_lengths(wl)
+    cu, tok, T = bt.build_offsets(lengths=dev(L), S=wl.S)
+    rcu, rtok, rT = O.build_offsets(O.lengths_to_mask(L, wl.S))
+    assert T == rT == int(L.sum())
+    assert np.array_equal(host(cu), rcu) and np.array_equal(host(tok), rtok)
+
+
+def test_offsets_lengths_edge_cases(bt):
+    for L, S in (([0, 0, 0], 8), ([8, 0, 8], 8), ([64] * 20, 64), ([1] * 130, 3), ([0, 5, 0, 1, 128], 128)):
+        L = np.array(L, np.int32)
+        cu, tok, T = bt.build_offsets(lengths=dev(L), S=S)
+        rcu, rtok, rT = O.build_offsets(O.lengths_to_mask(L, S))
+        assert T == rT and np.array_equal(host(cu), rcu) and np.array_equal(host(tok), rtok)
+    with pytest.raises(bt.BtError) as e:
+        bt.build_offsets(lengths=dev(np.array([3, 9], np.int32)), S=8)      # length > S
+    assert e.value.code == 1
+    with pytest.raises(bt.BtError):
+        bt.build_offsets(mask=dev(np.array([[1, 2, 0]], np.int32)))         # mask entry not 0/1
+
+
+@pytest.mark.parametrize("B,S,H", [(3, 5, 8), (4, 64, 768), (16, 256, 768), (7, 100, 1024), (2, 33, 72)])
+def test_pack_unpack_bit_exact(bt, B, S, H):
+    import torch
+    rng = np.random.default_rng(B + S + H)
+    mask = (rng.random((B, S)) < 0.6).astype(np.int32)
+    x = rng.normal(size=(B, S, H)).astype(np.float16)
+    cu, tok, T = bt.build_offsets(mask=dev(mask))
+    _, rtok, _ = O.build_offsets(mask)
+    packed = bt.pack(dev(x), tok)
+    ref = O.pack(x, rtok)
+    assert np.array_equal(host(packed).view(np.uint16), ref.view(np.uint16))
+    out = torch.full((B, S, H), 7.0, dtype=torch.float16, device="cuda:0")   # stale contents must vanish
+    bt.unpack(packed, tok, B, S, out=out)
+    assert np.array_equal(host(out).view(np.uint16), O.unpack(ref, rtok, B, S).view(np.uint16))
+
+
+def test_unpack_all_padding(bt):
+    import torch
+    tok = torch.empty(0, dtype=torch.int32, device="cuda:0")
+    packed = torch.empty((0, 16), dtype=torch.float16, device="cuda:0")
+    out = torch.ones((2, 3, 16), dtype=torch.float16, device="cuda:0")
+    bt.unpack(packed, tok, 2, 3, out=out)
+    assert float(out.abs().sum()) == 0.0
+
+
+# ------------------------------------------------------------------ GEMM + epilogue
+def _gelu_tanh64(x):
+    return 0.5 * x * (1 + np.tanh(np.sqrt(2 / np.pi) * (x + 0.044715 * x ** 3)))
+
+
+@pytest.mark.parametrize("M,N,K,act,bias", [
+    (1, 8, 8, 0, False), (5, 16, 40, 0, True), (77, 72, 200, 1, True), (150, 2304, 768, 0, True),
+    (129, 768, 3072, 0, False), (300, 3072, 768, 1, True), (2456, 768, 768, 0, True), (2456, 3072, 768, 2, True),
+    (1000, 1024, 4096, 0, True), (4710, 4096, 1024, 1, True)])
+def test_gemm_bias_act(bt, M, N, K, act, bias):
+    rng = np.random.default_rng(M + N + K)
+    a = rng.normal(0, 1, (M, K)).astype(np.float16)
+    w = rng.normal(0, 0.03, (N, K)).astype(np.float16)
+    b = rng.normal(0, 0.5, N).astype(np.float16) if bias else None
+    got = host(bt.gemm_bias_act(dev(a), dev(w), dev(b) if bias else None, act)).astype(np.float64)
+    ref = a.astype(np.float64) @ w.astype(np.float64).T
+    if bias:
+        ref = ref + b.astype(np.float64)
+    if act == 1:
+        ref = O.gelu(ref)
+    elif act == 2:
+        ref = _gelu_tanh64(ref)
+    err = np.abs(got - ref)
+    assert err.max() <= 2e-3 + 1e-3 * np.abs(ref).max(), err.max()
+    assert (err <= 1e-3 + 2 ** -10 * np.abs(ref)).mean() > 0.999
+
+
+# ------------------------------------------------------------------ bias + residual + LayerNorm
+@pytest.mark.parametrize("T,H,bias", [(1, 8, True), (5, 64, True), (150, 768, True), (2456, 768, False),
+                                      (333, 1024, True), (9, 4096, True), (3, 8192, True), (7, 520, True)])
+def test_bias_residual_layernorm(bt, T, H, bias):
+    rng = np.random.default_rng(T + H)
+    x = rng.normal(0, 1, (T, H)).astype(np.float16)
+    r = rng.normal(0, 1, (T, H)).astype(np.float16)
+    b = rng.normal(0, 0.5, H).astype(np.float16)
+    g = rng.normal(1, 0.2, H).astype(np.float16)
+    be = rng.normal(0, 0.2, H).astype(np.float16)
+    got = host(bt.add_bias_residual_layernorm(dev(x), dev(b) if bias else None, dev(r), dev(g), dev(be), 1e-12))
+    pre = x.astype(np.float64) + r.astype(np.float64) + (b.astype(np.float64) if bias else 0.0)
+    ref = O.layer_norm(pre, g, be, 1e-12)
+    assert np.abs(got.astype(np.float64) - ref).max() <= 4e-3
+
+
+# ------------------------------------------------------------------ variable-length MHA
+def _mha_case(bt, lengths, heads, seed, with_bias=False, max_len=None):
+    lengths = np.asarray(lengths, np.int32)
+    d = 64
+    T = int(lengths.sum())
+    rng = np.random.default_rng(seed)
+    qkv = rng.normal(0, 1, (T, 3 * heads * d)).astype(np.float16)
+    cu = np.concatenate([[0], np.cumsum(lengths)]).astype(np.int32)
+    biases = [rng.normal(0, 0.5, heads * d).astype(np.float16) for _ in range(3)] if with_bias else [None] * 3
+    got = host(bt.varlen_mha(dev(qkv), dev(cu), int(max_len or max(1, lengths.max())), heads,
+                             bq=dev(biases[0]) if with_bias else None, bk=dev(biases[1]) if with_bias else None,
+                             bv=dev(biases[2]) if with_bias else None)).astype(np.float64)
+    ref = O.varlen_mha_packed(qkv, cu, heads, d, bq=biases[0], bk=biases[1], bv=biases[2])
+    return np.abs(got - ref).max() if T else 0.0
+
+
+@pytest.mark.parametrize("lengths", [[1], [2, 1, 3], [32], [33], [63, 64, 65], [127, 128, 129, 1], [256, 7],
+                                     [0, 5, 0, 70], [300, 31, 200], [1024, 513], [40] * 70])
+@pytest.mark.parametrize("heads", [1, 12])
+def test_varlen_mha_shapes(bt, lengths, heads):
+    if heads == 12 and sum(lengths) > 1600:
+        pytest.skip("large case is covered with one head")
+    assert _mha_case(bt, lengths, heads, seed=sum(lengths) + heads) <= 4e-3
+
+
+def test_varlen_mha_bias_and_loose_max_len(bt):
+    assert _mha_case(bt, [50, 3, 129], 4, seed=5, with_bias=True) <= 4e-3
+    assert _mha_case(bt, [50, 3, 129], 4, seed=6, max_len=512) <= 4e-3
+
+
+def test_varlen_mha_separate_tensors_and_scale(bt):
+    rng = np.random.default_rng(3)
+    lengths = np.array([70, 9], np.int32)
+    heads, d, T = 2, 64, 79
+    q, k, v = (rng.normal(0, 1, (T, heads * d)).astype(np.float16) for _ in range(3))
+    cu = np.array([0, 70, 79], np.int32)
+    got = host(bt.varlen_mha_separate(dev(q), dev(k), dev(v), dev(cu), 70, heads, scale=0.3)).astype(np.float64)
+    ref = O.varlen_mha_packed(np.concatenate([q, k, v], axis=1), cu, heads, d, scale=0.3)
+    assert np.abs(got - ref).max() <= 4e-3
+
+
+def test_varlen_mha_workload_mha_b16_s256(bt):
+    """Attention alone: batch 16, max 256, 12 heads x 64, lengths U[1,256]."""
+    wl = I.WORKLOADS["mha_b16_s256"]
+    L = I.draw_lengths(wl)
+    T = int(L.sum())
+    qkv = I.make_qkv_packed(wl, T)
+    cu = np.concatenate([[0], np.cumsum(L)]).astype(np.int32)
+    got = host(bt.varlen_mha(dev(qkv), dev(cu), wl.S, wl.heads)).astype(np.float64)
+    ref = O.varlen_mha_packed(qkv, cu, wl.heads, wl.head_dim)
+    assert np.abs(got - ref).max() <= 4e-3
+
+
+def test_varlen_mha_ignores_other_sequences(bt):
+    """Pads do not exist in the packed layout; neighbours must not leak in."""
+    import torch
+    rng = np.random.default_rng(11)
+    lengths = np.array([37, 100, 5], np.int32)
+    cu = np.concatenate([[0], np.cumsum(lengths)]).astype(np.int32)
+    qkv = rng.normal(0, 1, (142, 3 * 2 * 64)).astype(np.float16)
+    a = bt.varlen_mha(dev(qkv), dev(cu), 100, 2)
+    qkv2 = qkv.copy()
+    qkv2[37:137] = 100.0                              # overwrite the middle sequence
+    b = bt.varlen_mha(dev(qkv2), dev(cu), 100, 2)
+    assert torch.equal(a[:37], b[:37]) and torch.equal(a[137:], b[137:])
+
+
+# ------------------------------------------------------------------ encoder layer / stack
+def _run_stack(bt, wl, n_layers, stress=False, seqs=None):
+    """Returns (gpu outputs per layer as fp64 packed, lengths, packed input)."""
+    L = I.draw_lengths(wl)
+    T = int(L.sum())
+    x = I.make_hidden_packed(wl, T)
+    cu, tok, T2 = bt.build_offsets(lengths=dev(L), S=wl.S)
+    assert T2 == T
+    layers = [bt.Layer(I.make_layer_params(wl, i, stress)) for i in range(n_layers)]
+    return layers, L, x, cu
+
+
+def _oracle_on(wl, L, x_packed, layers, seqs):
+    """Oracle stack on the chosen sequences only (sequences are independent)."""
+    cu = np.concatenate([[0], np.cumsum(L)])
+    Ls = L[seqs]
+    S = int(Ls.max())
+    xp = np.zeros((len(seqs), S, wl.H))
+    for i, b in enumerate(seqs):
+        xp[i, : L[b]] = x_packed[cu[b]: cu[b + 1]]
+    mask = O.lengths_to_mask(Ls, S)
+    y = O.encoder_stack(xp, mask, layers)
+    return [y[i, : L[b]] for i, b in enumerate(seqs)], cu
+
+
+@pytest.mark.parametrize("stress", [False, True])
+def test_layer_b4_s64(bt, stress):
+    """One BERT-base layer, batch 4, max 64, lengths U[8,64]."""
+    wl = I.WORKLOADS["layer_b4_s64"]
+    layers, L, x, cu = _run_stack(bt, wl, 1, stress)
+    got = host(bt.encoder_layer_fwd(layers[0], dev(x), cu, wl.S)).astype(np.float64)
+    ref, cuh = _oracle_on(wl, L, x, oracle_layers(wl, 1, stress), list(range(wl.B)))
+    err = max(np.abs(got[cuh[b]: cuh[b + 1]] - ref[b]).max() for b in range(wl.B))
+    assert err <= TOL_LAYER, err
+    # the stack entry point with one layer is the same computation
+    got2 = host(bt.encoder_fwd(layers, dev(x), cu, wl.S)).astype(np.float64)
+    assert np.array_equal(got, got2)
+
+
+def test_layer_zero_length_sequences(bt):
+    wl = I.WORKLOADS["layer_b4_s64"]
+    L = np.array([0, 17, 0, 64], np.int32)
+    x = I.make_hidden_packed(wl, int(L.sum()))
+    cu, tok, T = bt.build_offsets(lengths=dev(L), S=wl.S)
+    layer = bt.Layer(I.make_layer_params(wl, 0, True))
+    got = host(bt.encoder_layer_fwd(layer, dev(x), cu, wl.S)).astype(np.float64)
+    ref, cuh = _oracle_on(wl, L, x, oracle_layers(wl, 1, True), [1, 3])
+    assert np.abs(got[:17] - ref[0]).max() <= TOL_LAYER and np.abs(got[17:] - ref[1]).max() <= TOL_LAYER
+
+
+def test_stack_bert_base_b16_s256(bt):
+    """12 layers, batch 16, max 256: end-to-end <= 5e-2; each layer alone <= 1e-2
+    (GPU layer i against the oracle applied to the GPU's own layer i-1 output)."""
+    wl = I.WORKLOADS["bert_base_b16_s256"]
+    layers, L, x, cu = _run_stack(bt, wl, wl.layers)
+    ow = oracle_layers(wl, wl.layers)
+    seqs = list(range(wl.B))
+    cur = dev(x)
+    prev_host = x
+    worst_layer = 0.0
+    for i in range(wl.layers):
+        nxt = bt.encoder_layer_fwd(layers[i], cur, cu, wl.S)
+        g = host(nxt)
+        if i in (0, 5, 11):
+            ref, cuh = _oracle_on(wl, L, prev_host, [ow[i]], seqs)
+            e = max(np.abs(g[cuh[b]: cuh[b + 1]].astype(np.float64) - ref[b]).max() for b in seqs)
+            worst_layer = max(worst_layer, e)
+        cur, prev_host = nxt, g
+    assert worst_layer <= TOL_LAYER, worst_layer
+    full = host(bt.encoder_fwd(layers, dev(x), cu, wl.S))
+    assert np.array_equal(full, prev_host)               # stack == layer-by-layer, bit for bit
+    ref, cuh = _oracle_on(wl, L, x, ow, seqs)
+    err = max(np.abs(full[cuh[b]: cuh[b + 1]].astype(np.float64) - ref[b]).max() for b in seqs)
+    assert err <= TOL_12, err
+
+
+def _sampled_stack(bt, name, tol_mid, tol_end):
+    wl = I.WORKLOADS[name]
+    layers, L, x, cu = _run_stack(bt, wl, wl.layers)
+    order = np.argsort(L)
+    seqs = sorted({int(order[0]), int(order[len(order) // 2]), int(order[-1])})
+    full = host(bt.encoder_fwd(layers, dev(x), cu, wl.S)).astype(np.float64)
+    ow = oracle_layers(wl, wl.layers)
+    ref, cuh = _oracle_on(wl, L, x, ow, seqs)
+    err = max(np.abs(full[cuh[b]: cuh[b + 1]] - ref[i]).max() for i, b in enumerate(seqs))
+    assert err <= tol_end, err
+    if wl.layers > 12:
+        mid = host(bt.encoder_fwd(layers[:12], dev(x), cu, wl.S)).astype(np.float64)
+        refm, _ = _oracle_on(wl, L, x, ow[:12], seqs)
+        errm = max(np.abs(mid[cuh[b]: cuh[b + 1]] - refm[i]).max() for i, b in enumerate(seqs))
+        assert errm <= tol_mid, errm
+    # LayerNorm with gamma=1, beta=0: every output row has mean 0 and variance 1 (property, all rows)
+    assert np.abs(full.mean(axis=1)).max() < 5e-3 and np.abs(full.var(axis=1) - 1).max() < 2e-2
+
+
+def test_stack_bert_base_b16_s1024_sampled(bt):
+    """12 layers, batch 16, max 1024: shortest / median / longest sequence through
+    the fp64 oracle (sequences are independent), plus a property on all rows."""
+    _sampled_stack(bt, "bert_base_b16_s1024", TOL_12, TOL_12)
+
+
+def test_stack_bert_large_b32_s512_sampled(bt):
+    """24 layers of the large shape, skewed lengths: 5e-2 at layer 12, 1e-1 at 24."""
+    _sampled_stack(bt, "bert_large_b32_s512", TOL_12, TOL_24)
