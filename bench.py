@@ -1,0 +1,196 @@
+#!/usr/bin/env python3
+"""Benchmark of the padding-free BERT encoder forward on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME]
+
+A step is one pass of the whole hot path over one synthetic batch that is
+already resident in HBM: bt_build_offsets (with its one host sync) -> bt_pack ->
+bt_encoder_fwd (all layers) -> bt_unpack.  Prints ONE JSON line:
+sequences/s (whole job), plus
+  "roofline"     the dominant kernel's achieved rate against MI355X's published
+                 peak, from HIP-event timing of that kernel in this process,
+  "kernels"      the same figures for every kernel of the layer,
+  "cpu_baseline" the fp64 numpy oracle timed on this machine's host cores.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_MFMA_F16 = 2500.0   # TFLOP/s, dense fp16 MFMA, published
+PEAK_HBM = 8000.0        # GB/s, published
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="bert_base_b16_s256")
+    ap.add_argument("--kernel-iters", type=int, default=200, help="launches per kernel for the roofline timing")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-kernels", action="store_true", help="skip the per-kernel timing pass")
+    return ap.parse_args()
+
+
+def time_launches(torch, fn, iters, warm=10):
+    """Average duration of one launch: `iters` back-to-back launches between two
+    HIP events on the launch stream (includes the inter-launch gap)."""
+    for _ in range(warm):
+        fn()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(iters):
+        fn()
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) * 1e3 / iters      # microseconds
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (sequences are independent, so more GPUs would be "
+              "plain data parallelism with no collectives); run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+    import torch
+
+    import paper_2210_03052_amd as bt
+    from paper_2210_03052_amd import inputs as I
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    bt.load_library()                      # raises if libbt.so is not built: no fallback
+    torch.cuda.set_device(0)
+    wl = I.WORKLOADS[args.workload]
+    if wl.layers < 1:
+        print("bench.py: pick an encoder workload", file=sys.stderr)
+        sys.exit(2)
+
+    # ---------------- synthetic batch, resident in HBM before timing starts
+    L = I.draw_lengths(wl)
+    T = int(L.sum())
+    sum_l2 = int((L.astype(np.int64) ** 2).sum())
+    H, F, nl = wl.H, wl.F, wl.layers
+    dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to("cuda:0")
+    x_packed_h = I.make_hidden_packed(wl, T)
+    x_padded = dev(I.pad_rows(x_packed_h, L, wl.S))
+    lengths_d = dev(L)
+    params = [I.make_layer_params(wl, i) for i in range(nl)]
+    layers = [bt.Layer(p) for p in params]
+    ws = torch.empty(bt.layer_workspace_bytes(layers[0], wl.B * wl.S, wl.B, wl.S), dtype=torch.uint8, device="cuda:0")
+    x_packed = torch.empty((wl.B * wl.S, H), dtype=torch.float16, device="cuda:0")
+    y_packed = torch.empty((wl.B * wl.S, H), dtype=torch.float16, device="cuda:0")
+    y_padded = torch.empty((wl.B, wl.S, H), dtype=torch.float16, device="cuda:0")
+
+    def step():
+        cu, tok, t = bt.build_offsets(lengths=lengths_d, S=wl.S)
+        xp = bt.pack(x_padded, tok, out=x_packed[:t])
+        yp = bt.encoder_fwd(layers, xp, cu, wl.S, out=y_packed[:t], ws=ws)
+        bt.unpack(yp, tok, wl.B, wl.S, out=y_padded)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ms_per_step = dt * 1e3 / args.steps
+    seq_per_s = wl.B * args.steps / dt
+    flops_step = nl * (24.0 * T * H * H + 4.0 * sum_l2 * H)
+
+    out = {
+        "metric": "sequences/s BERT-base fp16 varlen (b16, max256)" if args.workload == "bert_base_b16_s256"
+                  else f"sequences/s {args.workload} fp16 varlen",
+        "value": round(seq_per_s, 1), "unit": "sequences/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f16", "data": "synthetic",
+        "config": {"workload": args.workload, "batch": wl.B, "max_seq": wl.S, "hidden": H, "heads": wl.heads,
+                   "ffn": F, "layers": nl, "length_law": wl.length_law, "valid_tokens": T, "sum_len_sq": sum_l2,
+                   "step": "build_offsets+pack+encoder_fwd+unpack"},
+        "useful_tflops_per_s": round(flops_step / (ms_per_step * 1e-3) / 1e12, 2),
+    }
+
+    # ---------------- per-kernel timing (HIP events on the launch stream)
+    if not args.no_kernels:
+        cu, tok, _ = bt.build_offsets(lengths=lengths_d, S=wl.S)
+        xp = bt.pack(x_padded, tok)
+        ly = layers[0]
+        P = ly.tensors
+        qkv = torch.empty((T, 3 * H), dtype=torch.float16, device="cuda:0")
+        attn = torch.empty((T, H), dtype=torch.float16, device="cuda:0")
+        proj = torch.empty((T, H), dtype=torch.float16, device="cuda:0")
+        y1 = torch.empty((T, H), dtype=torch.float16, device="cuda:0")
+        g = torch.empty((T, F), dtype=torch.float16, device="cuda:0")
+        y2 = torch.empty((T, H), dtype=torch.float16, device="cuda:0")
+        steps = [
+            ("gemm0_qkv_bias", "mfma", 6.0 * T * H * H,
+             lambda: bt.gemm_bias_act(xp, P["w_qkv"], P["b_qkv"], bt.ACT_NONE, out=qkv)),
+            ("varlen_mha", "mfma", 4.0 * sum_l2 * H, lambda: bt.varlen_mha(qkv, cu, wl.S, wl.heads, out=attn)),
+            ("gemm1_proj", "mfma", 2.0 * T * H * H, lambda: bt.gemm_bias_act(attn, P["w_o"], None, bt.ACT_NONE, out=proj)),
+            ("bias_residual_ln0", "hbm", 6.0 * T * H,
+             lambda: bt.add_bias_residual_layernorm(proj, P["b_o"], xp, P["ln0_g"], P["ln0_b"], ly.eps, out=y1)),
+            ("gemm2_bias_gelu", "mfma", 2.0 * T * H * F,
+             lambda: bt.gemm_bias_act(y1, P["w_1"], P["b_1"], bt.ACT_GELU_ERF, out=g)),
+            ("gemm3_ffn_down", "mfma", 2.0 * T * H * F, lambda: bt.gemm_bias_act(g, P["w_2"], None, bt.ACT_NONE, out=proj)),
+            ("bias_residual_ln1", "hbm", 6.0 * T * H,
+             lambda: bt.add_bias_residual_layernorm(proj, P["b_2"], y1, P["ln1_g"], P["ln1_b"], ly.eps, out=y2)),
+            ("pack", "hbm", 4.0 * T * H, lambda: bt.pack(x_padded, tok, out=x_packed[:T])),
+            ("unpack", "hbm", 2.0 * T * H + 2.0 * wl.B * wl.S * H, lambda: bt.unpack(y2, tok, wl.B, wl.S, out=y_padded)),
+        ]
+        kernels = []
+        for name, bound, work, fn in steps:
+            us = time_launches(torch, fn, args.kernel_iters)
+            per_step = nl if name not in ("pack", "unpack") else 1
+            if bound == "mfma":
+                ach, peak, unit = work / us / 1e6, PEAK_MFMA_F16, "TFLOP/s"
+            else:
+                ach, peak, unit = work / us / 1e3, PEAK_HBM, "GB/s"
+            kernels.append({"kernel": name, "bound": bound, "us": round(us, 2), "launches_per_step": per_step,
+                            "achieved": round(ach, 2), "peak": peak, "unit": unit, "frac": round(ach / peak, 4),
+                            "work_per_launch": work})
+        dom = max(kernels, key=lambda k: k["us"] * k["launches_per_step"])
+        out["roofline"] = {"kernel": dom["kernel"], "bound": dom["bound"], "achieved": dom["achieved"],
+                           "peak": dom["peak"], "unit": dom["unit"], "frac": dom["frac"], "traffic": None,
+                           "us_per_launch": dom["us"], "work_per_launch": dom["work_per_launch"]}
+        out["kernels"] = kernels
+        out["kernel_time_sum_ms_per_step"] = round(sum(k["us"] * k["launches_per_step"] for k in kernels) / 1e3, 4)
+
+    # ---------------- CPU baseline: the oracle as it stands, on this machine's cores
+    if not args.no_cpu_baseline:
+        from oracle import bt_oracle as O
+        cores = len(os.sched_getaffinity(0))
+        try:                                                   # threads the BLAS behind numpy really uses
+            from threadpoolctl import threadpool_info
+            cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [cores])
+        except Exception:
+            pass
+        mask = O.lengths_to_mask(L, wl.S)
+        xh = I.pad_rows(x_packed_h, L, wl.S).astype(np.float64)
+        ow = [O.LayerWeights(**p) for p in params]
+        n_base = min(nl, 12)
+        O.encoder_layer(xh[:2], mask[:2], ow[0])            # warm the BLAS threads
+        t0 = time.perf_counter()
+        O.encoder_stack(xh, mask, ow[:n_base])
+        cpu_s = (time.perf_counter() - t0) * nl / n_base
+        out["cpu_baseline"] = {"value": round(wl.B / cpu_s, 3), "unit": "sequences/s", "cores": cores,
+                               "kind": "oracle",
+                               "sample": f"whole batch, {n_base} of {nl} layers timed once (scaled to {nl}), "
+                                         f"numpy fp64 padded semantics", "seconds": round(cpu_s, 2)}
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -2,84 +2,181 @@
 // A [M,K] and W [N,K] are both K-contiguous, which is exactly the operand order
 // the gfx950 MFMA wants: every lane feeds 8 consecutive K values of one row.
 //
-// Tiling: 256 threads = 4 wavefronts in a 2x2 grid; block tile BM x BN x 64,
-// wave tile (BM/2) x (BN/2) made of 32x32x16 fp16 MFMA blocks with fp32
-// accumulators.  Operand tiles are staged in LDS (double-buffered, rows padded
-// by 16 bytes so that 128-bit reads of 16 consecutive rows hit 64 distinct
-// banks); the next K-slab is fetched from global memory into registers while the
-// current one is multiplied.  The product is computed transposed (W is the MFMA
-// A operand), so each lane ends up with 4 consecutive output columns of one row
-// and stores them with one 8-byte write after bias/activation in fp32.
+// Main kernel (K % BK == 0): 256 threads = 4 wavefronts in a 2x2 grid, block
+// tile BM x BN x BK, wave tile (BM/2) x (BN/2) of 32x32x16 fp16 MFMA blocks with
+// fp32 accumulators.  Operand slabs travel global memory -> LDS directly
+// (global_load_lds_dwordx4: no register staging), NS slabs deep, so that NS-1
+// slabs are in flight while one is multiplied; each wave waits only for its own
+// oldest slab (s_waitcnt vmcnt) and one s_barrier per slab publishes it.
+// LDS rows are unpadded (a DMA instruction fills 1 KB contiguously) and
+// XOR-swizzled at 16-byte granularity on the *global* side, so the 128-bit
+// operand reads of 16 consecutive rows still hit 64 distinct banks.
+// The product is computed transposed (W is the MFMA A operand): each lane ends
+// up with 4 consecutive output columns of one row and stores them with one
+// 8-byte write after bias/activation in fp32.
+//
+// Fallback kernel (any K % 8 == 0): register-staged, zero-fills the K tail.
+#include <type_traits>
+
 #include "common.h"
 
 namespace bt {
 
-constexpr int kGemmThreads = 256;
-constexpr int kBK = 64;            // K-slab per stage (halves)
-constexpr int kLdsStride = kBK + 8;  // halves; 144-byte rows
+constexpr int kGemmThreads = 256;  // fallback kernel
 
-__device__ __forceinline__ float gelu_erf(float x) { return 0.5f * x * (1.0f + erff(x * 0.70710678118654752f)); }
+#define BT_AS1 __attribute__((address_space(1)))
+#define BT_AS3 __attribute__((address_space(3)))
+
+// erf by the rational/exponential fit of Abramowitz & Stegun 7.1.26 (|error| <= 1.5e-7, far below
+// the fp16 rounding of the result); an order of magnitude fewer instructions than libm's erff,
+// which matters because the epilogue runs once per output element.
+__device__ __forceinline__ float erf_as(float x) {
+  const float ax = fabsf(x);
+  const float t = __builtin_amdgcn_rcpf(1.0f + 0.3275911f * ax);
+  const float poly = t * (0.254829592f + t * (-0.284496736f + t * (1.421413741f + t * (-1.453152027f + t * 1.061405429f))));
+  const float e = __builtin_amdgcn_exp2f(-1.4426950408889634f * ax * ax);
+  return copysignf(1.0f - poly * e, x);
+}
+__device__ __forceinline__ float gelu_erf(float x) { return 0.5f * x * (1.0f + erf_as(x * 0.70710678118654752f)); }
 __device__ __forceinline__ float gelu_tanh(float x) {
   const float u = 0.7978845608028654f * (x + 0.044715f * x * x * x);
   return 0.5f * x * (1.0f + tanhf(u));
 }
 
-template <int BM, int BN, int ACT>
-__global__ __launch_bounds__(kGemmThreads) void gemm_kernel(const half_t* __restrict__ A,
-                                                            const half_t* __restrict__ W,
-                                                            const half_t* __restrict__ bias, half_t* __restrict__ C,
-                                                            int M, int N, int K, int tiles_n, int n_tiles) {
-  constexpr int WM = BM / 2, WN = BN / 2;      // wave tile
-  constexpr int MI = WM / 32, NI = WN / 32;    // 32x32 blocks per wave
-  constexpr int A_CH = BM * (kBK / 8) / kGemmThreads;  // 16-byte chunks per thread
-  constexpr int B_CH = BN * (kBK / 8) / kGemmThreads;
-  static_assert(A_CH >= 1 && B_CH >= 1, "tile too small for 256 threads");
+// One 16-byte-per-lane DMA from global memory straight into LDS: lane i's 16 bytes land at
+// lds_base + 16*i (lds_base is wave-uniform and travels in M0).  Issued through inline assembly so
+// that the compiler does not serialise later LDS reads behind every outstanding DMA; completion is
+// tracked by hand with s_waitcnt vmcnt + s_barrier.  The s_nop covers the M0-write -> LDS-DMA hazard.
+__device__ __forceinline__ void dma16(const void* gptr, uint32_t lds_base) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_base), "v"(gptr)
+               : "memory", "m0");
+}
+__device__ __forceinline__ uint32_t lds_addr(const void* p) {
+  return (uint32_t)(uintptr_t)(BT_AS3 const void*)p;
+}
 
-  __shared__ __attribute__((aligned(16))) half_t sA[2][BM * kLdsStride];
-  __shared__ __attribute__((aligned(16))) half_t sB[2][BN * kLdsStride];
+// s_waitcnt vmcnt(n), other counters untouched (gfx9 encoding: vmcnt = [15:14|3:0]).
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {
+  static_assert(N >= 0 && N < 64, "vmcnt is 6 bits");
+  __builtin_amdgcn_s_waitcnt((N & 15) | ((N >> 4) << 14) | (7 << 4) | (15 << 8));
+}
 
-  const int tile = xcd_remap(blockIdx.x, n_tiles);
-  const int tm = tile / tiles_n, tn = tile - tm * tiles_n;
+// Shared epilogue.  acc[i][j][4g+t] = C[m][n] with m = m_base + i*32 + l32, n = n_base + j*32 + 8g + 4hf + t.
+// Bias and activation are applied to the fp32 accumulators; the fp16 tile of this wave is then
+// transposed through a private LDS region (rows padded to WN+8 halves) so that global memory is
+// written with 16-byte-per-lane stores, 8 lanes covering 128 contiguous bytes of an output row.
+template <int MI, int NI, int ACT>
+__device__ __forceinline__ void store_tile(const float16_t (&acc)[MI][NI], const half_t* __restrict__ bias,
+                                           half_t* __restrict__ C, int M, int N, int m_base, int n_base, int lane,
+                                           half_t* stage /* this wave's LDS region: MI*32 x (NI*32+8) halves */) {
+  constexpr int WN = NI * 32, LD = WN + 8;
+  const int l32 = lane & 31, hf = lane >> 5;
+#pragma unroll
+  for (int j = 0; j < NI; ++j) {
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+      const int nl = j * 32 + 8 * g + 4 * hf;
+      const int n = n_base + nl;
+      float bv[4] = {0.f, 0.f, 0.f, 0.f};
+      if (bias && n < N) {  // N % 8 == 0: the 4 columns are all in or all out
+        const half4_t b4 = *reinterpret_cast<const half4_t*>(bias + n);
+#pragma unroll
+        for (int t = 0; t < 4; ++t) bv[t] = (float)b4[t];
+      }
+#pragma unroll
+      for (int i = 0; i < MI; ++i) {
+        half4_t o;
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+          float v = acc[i][j][4 * g + t] + bv[t];
+          if (ACT == BT_ACT_GELU_ERF) v = gelu_erf(v);
+          else if (ACT == BT_ACT_GELU_TANH) v = gelu_tanh(v);
+          o[t] = (half_t)v;
+        }
+        *reinterpret_cast<half4_t*>(stage + (i * 32 + l32) * LD + nl) = o;
+      }
+    }
+  }
+  // rows of this wave's tile: WN/8 lanes per row
+  constexpr int LPR = WN / 8, RPP = 64 / LPR;  // lanes per row, rows per pass
+  const int rr = lane / LPR, cc = (lane % LPR) * 8;
+#pragma unroll
+  for (int r0 = 0; r0 < MI * 32; r0 += RPP) {
+    const int m = m_base + r0 + rr, n = n_base + cc;
+    const uint4_t v = *reinterpret_cast<const uint4_t*>(stage + (r0 + rr) * LD + cc);
+    if (m < M && n < N) *reinterpret_cast<uint4_t*>(C + (size_t)m * N + n) = v;
+  }
+}
+
+// ---------------------------------------------------------------------------
+// Pipelined kernel: direct-to-LDS slabs, NS stages, WGM x WGN wavefronts.
+// ---------------------------------------------------------------------------
+template <int BM, int BN, int WGM, int WGN, int NS, int ACT>
+__global__ __launch_bounds__(WGM* WGN * 64) void gemm_pipe_kernel(const half_t* __restrict__ A,
+                                                                  const half_t* __restrict__ W,
+                                                                  const half_t* __restrict__ bias,
+                                                                  half_t* __restrict__ C, int M, int N, int K,
+                                                                  int tiles_n, int n_tiles, int group_m) {
+  constexpr int BK = 64, KS = BK / 16;
+  constexpr int NWAVES = WGM * WGN;
+  constexpr int WM = BM / WGM, WN = BN / WGN;   // wave tile
+  constexpr int MI = WM / 32, NI = WN / 32;     // 32x32 MFMA blocks per wave tile
+  constexpr int CPR = BK / 8;                   // 16-byte chunks per LDS row
+  constexpr int RPI = 64 / CPR;                 // rows one DMA instruction (64 lanes x 16 B) fills
+  constexpr int LA = BM / RPI / NWAVES, LB = BN / RPI / NWAVES;  // DMA instructions per wave per slab
+  constexpr int TOT = LA + LB;
+  static_assert(WM % 32 == 0 && WN % 32 == 0, "wave tile");
+  static_assert(LA * RPI * NWAVES == BM && LB * RPI * NWAVES == BN, "tile rows must split evenly over the waves");
+  static_assert(NS >= 2 && (NS - 1) * TOT < 64, "vmcnt range");
+
+  constexpr int STAGE_HALVES = WM * (WN + 8);  // per-wave epilogue staging
+  constexpr int PIPE_HALVES = NS * (BM + BN) * BK;
+  constexpr int LDS_HALVES = PIPE_HALVES > NWAVES * STAGE_HALVES ? PIPE_HALVES : NWAVES * STAGE_HALVES;
+  __shared__ __attribute__((aligned(1024))) half_t smem[LDS_HALVES];
+  half_t* const sA = smem;                 // [NS][BM*BK]
+  half_t* const sB = smem + NS * BM * BK;  // [NS][BN*BK]
+
+  // Tile order.  Block ids are dealt round-robin to the 8 XCDs; xcd_remap gives every XCD one
+  // contiguous run of the logical order, and the logical order walks strips of `group_m` tile rows
+  // column by column, so the tiles an XCD works on together form a near-square patch of C whose A
+  // and W panels fit its private L2 instead of streaming all of W through every L2.
+  const int lin = xcd_remap(blockIdx.x, n_tiles);
+  const int tiles_m = n_tiles / tiles_n;
+  const int per_group = group_m * tiles_n;
+  const int first_m = (lin / per_group) * group_m;
+  const int rows_here = min(tiles_m - first_m, group_m);
+  const int in_group = lin - (lin / per_group) * per_group;
+  const int tm = first_m + in_group % rows_here, tn = in_group / rows_here;
   const int m0 = tm * BM, n0 = tn * BN;
-
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int wm = wave >> 1, wn = wave & 1;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform: LDS DMA bases live in M0
+  const int wm = wave / WGN, wn = wave % WGN;
   const int l32 = lane & 31, hf = lane >> 5;
 
-  // global -> register staging: chunk c = tid + 256*i covers row c/8, halves (c%8)*8..+7
-  const half_t* a_ptr[A_CH];
-  const half_t* b_ptr[B_CH];
-  int a_lds[A_CH], b_lds[B_CH];
-  const int kc = (tid & 7) * 8;
+  // DMA source pointers.  Instruction q of this wave fills LDS rows [r0, r0+8) of the slab; lane i
+  // lands at row r0 + i/8, physical chunk i%8, and therefore fetches logical chunk
+  // (i%8) ^ ((row>>1)&7) of that row from global memory.
+  const half_t* ga[LA];
+  const half_t* gb[LB];
 #pragma unroll
-  for (int i = 0; i < A_CH; ++i) {
-    const int row = (tid >> 3) + i * (kGemmThreads / 8);
-    const int gr = min(m0 + row, M - 1);  // rows past M are read clamped, never stored
-    a_ptr[i] = A + (size_t)gr * K + kc;
-    a_lds[i] = row * kLdsStride + kc;
+  for (int q = 0; q < LA; ++q) {
+    const int r = (wave * LA + q) * RPI + lane / CPR;
+    const int c = (lane % CPR) ^ ((r >> 1) & (CPR - 1));
+    ga[q] = A + (size_t)min(m0 + r, M - 1) * K + c * 8;  // rows past M: clamped reads, never stored
   }
 #pragma unroll
-  for (int i = 0; i < B_CH; ++i) {
-    const int row = (tid >> 3) + i * (kGemmThreads / 8);
-    const int gr = min(n0 + row, N - 1);
-    b_ptr[i] = W + (size_t)gr * K + kc;
-    b_lds[i] = row * kLdsStride + kc;
+  for (int q = 0; q < LB; ++q) {
+    const int r = (wave * LB + q) * RPI + lane / CPR;
+    const int c = (lane % CPR) ^ ((r >> 1) & (CPR - 1));
+    gb[q] = W + (size_t)min(n0 + r, N - 1) * K + c * 8;
   }
-
-  uint4_t ra[A_CH], rb[B_CH];
-  const uint4_t zero4 = {0u, 0u, 0u, 0u};
-  auto fetch = [&](int k0) {
-    const bool in = (k0 + kc) < K;  // K % 8 == 0: a chunk is entirely inside or outside
-#pragma unroll
-    for (int i = 0; i < A_CH; ++i) ra[i] = in ? *reinterpret_cast<const uint4_t*>(a_ptr[i] + k0) : zero4;
-#pragma unroll
-    for (int i = 0; i < B_CH; ++i) rb[i] = in ? *reinterpret_cast<const uint4_t*>(b_ptr[i] + k0) : zero4;
-  };
-  auto stage = [&](int buf) {
-#pragma unroll
-    for (int i = 0; i < A_CH; ++i) *reinterpret_cast<uint4_t*>(&sA[buf][a_lds[i]]) = ra[i];
-#pragma unroll
-    for (int i = 0; i < B_CH; ++i) *reinterpret_cast<uint4_t*>(&sB[buf][b_lds[i]]) = rb[i];
+  const uint32_t lds_a = lds_addr(sA) + wave * LA * RPI * BK * 2;  // bytes
+  const uint32_t lds_b = lds_addr(sB) + wave * LB * RPI * BK * 2;
+  // DMA instruction q (0 <= q < TOT) of this wave for slab `slab` into stage `stage`: A rows, then W rows.
+  auto issue_one = [&](int q, int slab, int stage) {
+    if (q < LA) dma16(ga[q < LA ? q : 0] + slab * BK, lds_a + stage * (BM * BK * 2) + q * (RPI * BK * 2));
+    else dma16(gb[q >= LA ? q - LA : 0] + slab * BK, lds_b + stage * (BN * BK * 2) + (q - LA) * (RPI * BK * 2));
   };
 
   float16_t acc[MI][NI];
@@ -90,112 +187,217 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_kernel(const half_t* __rest
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-  const int nk = (K + kBK - 1) / kBK;
-  fetch(0);
-  stage(0);
-  __syncthreads();
-
-  const int a_rd = (wm * WM + l32) * kLdsStride + hf * 8;
-  const int b_rd = (wn * WN + l32) * kLdsStride + hf * 8;
-
-  for (int kt = 0; kt < nk; ++kt) {
-    const int buf = kt & 1;
-    if (kt + 1 < nk) fetch((kt + 1) * kBK);
+  const int nk = K / BK;
 #pragma unroll
-    for (int ks = 0; ks < kBK / 16; ++ks) {
-      half8_t fa[MI], fb[NI];
+  for (int s = 0; s < NS - 1; ++s)
+    if (s < nk) {
 #pragma unroll
-      for (int i = 0; i < MI; ++i)
-        fa[i] = *reinterpret_cast<const half8_t*>(&sA[buf][a_rd + i * 32 * kLdsStride + ks * 16]);
+      for (int q = 0; q < TOT; ++q) issue_one(q, s, s);
+    }
+
+  // operand read offsets (halves): row*BK + ((2ks+hf) ^ swz(row))*8 ; swz depends on l32 only
+  const int swz = (l32 >> 1) & (CPR - 1);
+  const int a_row = (wm * WM + l32) * BK, b_row = (wn * WN + l32) * BK;
+  half8_t fa[2][MI], fb[2][NI];
+  auto read_frags = [&](int stage, int ks, int slot) {
+    const int co = ((2 * ks + hf) ^ swz) * 8;
+    const half_t* pa = sA + stage * (BM * BK) + a_row + co;
+    const half_t* pb = sB + stage * (BN * BK) + b_row + co;
+#pragma unroll
+    for (int i = 0; i < MI; ++i) fa[slot][i] = *reinterpret_cast<const half8_t*>(pa + i * 32 * BK);
+#pragma unroll
+    for (int j = 0; j < NI; ++j) fb[slot][j] = *reinterpret_cast<const half8_t*>(pb + j * 32 * BK);
+  };
+  auto mfmas = [&](int slot) {
+#pragma unroll
+    for (int i = 0; i < MI; ++i)
 #pragma unroll
       for (int j = 0; j < NI; ++j)
-        fb[j] = *reinterpret_cast<const half8_t*>(&sB[buf][b_rd + j * 32 * kLdsStride + ks * 16]);
-#pragma unroll
-      for (int i = 0; i < MI; ++i)
-#pragma unroll
-        for (int j = 0; j < NI; ++j)
-          // transposed product: D[n][m] += W[n][k] * A[m][k]
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fb[j], fa[i], acc[i][j], 0, 0, 0);
-    }
-    if (kt + 1 < nk) stage(buf ^ 1);
-    __syncthreads();
-  }
+        // transposed product: D[n][m] += W[n][k] * A[m][k]
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fb[slot][j], fa[slot][i], acc[i][j], 0, 0, 0);
+  };
+  // Wait until this wave's share of slab kt has landed (at most min(nk-1-kt, NS-2) younger slabs of
+  // TOT instructions each may stay in flight), then publish it to the block.  The barrier also
+  // tells everyone that slab kt-1 is no longer being read, so its stage may be refilled.
+  auto acquire = [&](int kt) {
+    const int younger = min(nk - 1 - kt, NS - 2);
+    if (NS >= 4 && younger >= 2) wait_vmcnt<(NS >= 4 ? 2 : 0) * TOT>();
+    else if (NS >= 3 && younger == 1) wait_vmcnt<(NS >= 3 ? 1 : 0) * TOT>();
+    else wait_vmcnt<0>();
+    __builtin_amdgcn_s_barrier();
+  };
 
-  // Epilogue.  acc[i][j][4g+t] = C[m][n] with m = m0 + wm*WM + i*32 + l32,
-  // n = n0 + wn*WN + j*32 + 8g + 4hf + t.
+  // Software pipeline.  The fragments of k-step ks+1 are read from LDS while the MFMAs of k-step ks
+  // run; the hand-over to the next slab (acquire + its first fragment read) sits in front of the
+  // last k-step's MFMAs, so neither the LDS latency nor the DMA issue is exposed at a slab boundary.
+  // The DMA instructions for slab kt+NS-1 are spread over the first KS-1 k-steps: a burst would
+  // stall the wave behind its own address FIFO.
+  acquire(0);
+  read_frags(0, 0, 0);
+  int stage = 0;
+  for (int kt = 0; kt < nk; ++kt) {
+    const bool fetch = kt + NS - 1 < nk;
+    const int fstage = stage == 0 ? NS - 1 : stage - 1;  // (kt + NS - 1) % NS
 #pragma unroll
-  for (int i = 0; i < MI; ++i) {
-    const int m = m0 + wm * WM + i * 32 + l32;
-    if (m >= M) continue;
+    for (int ks = 0; ks < KS - 1; ++ks) {
+      read_frags(stage, ks + 1, (ks + 1) & 1);
+      if (fetch) {
 #pragma unroll
-    for (int j = 0; j < NI; ++j) {
-#pragma unroll
-      for (int g = 0; g < 4; ++g) {
-        const int n = n0 + wn * WN + j * 32 + 8 * g + 4 * hf;
-        if (n >= N) continue;  // N % 8 == 0: the 4 columns are all in or all out
-        float v[4];
-#pragma unroll
-        for (int t = 0; t < 4; ++t) v[t] = acc[i][j][4 * g + t];
-        if (bias) {
-          const half4_t bv = *reinterpret_cast<const half4_t*>(bias + n);
-#pragma unroll
-          for (int t = 0; t < 4; ++t) v[t] += (float)bv[t];
-        }
-        if (ACT == BT_ACT_GELU_ERF) {
-#pragma unroll
-          for (int t = 0; t < 4; ++t) v[t] = gelu_erf(v[t]);
-        } else if (ACT == BT_ACT_GELU_TANH) {
-#pragma unroll
-          for (int t = 0; t < 4; ++t) v[t] = gelu_tanh(v[t]);
-        }
-        half4_t o;
-#pragma unroll
-        for (int t = 0; t < 4; ++t) o[t] = (half_t)v[t];
-        *reinterpret_cast<half4_t*>(C + (size_t)m * N + n) = o;
+        for (int q = ks * TOT / (KS - 1); q < (ks + 1) * TOT / (KS - 1); ++q) issue_one(q, kt + NS - 1, fstage);
       }
+      mfmas(ks & 1);
+      __builtin_amdgcn_sched_barrier(0);
     }
+    const int nstage = stage + 1 == NS ? 0 : stage + 1;
+    if (kt + 1 < nk) {
+      // all of this wave's reads of slab kt are in registers before anyone may refill its stage
+      asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+      acquire(kt + 1);
+      read_frags(nstage, 0, 0);
+    }
+    mfmas((KS - 1) & 1);
+    __builtin_amdgcn_sched_barrier(0);
+    stage = nstage;
   }
+  __builtin_amdgcn_s_barrier();  // every wave is done reading the last slab: LDS becomes staging space
+  store_tile<MI, NI, ACT>(acc, bias, C, M, N, m0 + wm * WM, n0 + wn * WN, lane, smem + wave * STAGE_HALVES);
 }
 
-template <int BM, int BN>
-static bt_status launch_gemm(const half_t* A, const half_t* W, const half_t* bias, half_t* C, int M, int N, int K,
+// ---------------------------------------------------------------------------
+// Fallback kernel: register-staged, 64x64x64 tile, padded LDS rows, K tail zero-filled.
+// ---------------------------------------------------------------------------
+template <int ACT>
+__global__ __launch_bounds__(kGemmThreads) void gemm_simple_kernel(const half_t* __restrict__ A,
+                                                                   const half_t* __restrict__ W,
+                                                                   const half_t* __restrict__ bias,
+                                                                   half_t* __restrict__ C, int M, int N, int K,
+                                                                   int tiles_n) {
+  constexpr int BM = 64, BN = 64, BK = 64, LDS = BK + 8, CH = BM * (BK / 8) / kGemmThreads;
+  __shared__ __attribute__((aligned(16))) half_t sA[BM * LDS];
+  __shared__ __attribute__((aligned(16))) half_t sB[BN * LDS];
+  const int tm = blockIdx.x / tiles_n, tn = blockIdx.x - tm * tiles_n;
+  const int m0 = tm * BM, n0 = tn * BN;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave >> 1, wn = wave & 1, l32 = lane & 31, hf = lane >> 5;
+  const int kc = (tid & 7) * 8;
+  float16_t acc[1][1];
+#pragma unroll
+  for (int r = 0; r < 16; ++r) acc[0][0][r] = 0.f;
+  const uint4_t zero4 = {0u, 0u, 0u, 0u};
+  for (int k0 = 0; k0 < K; k0 += BK) {
+    const bool in = (k0 + kc) < K;  // K % 8 == 0: a chunk is entirely inside or outside
+    uint4_t ra[CH], rb[CH];
+#pragma unroll
+    for (int i = 0; i < CH; ++i) {
+      const int row = (tid >> 3) + i * (kGemmThreads / 8);
+      ra[i] = in ? *reinterpret_cast<const uint4_t*>(A + (size_t)min(m0 + row, M - 1) * K + k0 + kc) : zero4;
+      rb[i] = in ? *reinterpret_cast<const uint4_t*>(W + (size_t)min(n0 + row, N - 1) * K + k0 + kc) : zero4;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < CH; ++i) {
+      const int row = (tid >> 3) + i * (kGemmThreads / 8);
+      *reinterpret_cast<uint4_t*>(&sA[row * LDS + kc]) = ra[i];
+      *reinterpret_cast<uint4_t*>(&sB[row * LDS + kc]) = rb[i];
+    }
+    __syncthreads();
+#pragma unroll
+    for (int ks = 0; ks < BK / 16; ++ks) {
+      const half8_t fa = *reinterpret_cast<const half8_t*>(&sA[(wm * 32 + l32) * LDS + ks * 16 + hf * 8]);
+      const half8_t fb = *reinterpret_cast<const half8_t*>(&sB[(wn * 32 + l32) * LDS + ks * 16 + hf * 8]);
+      acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fb, fa, acc[0][0], 0, 0, 0);
+    }
+  }
+  __syncthreads();  // operand tiles are dead: reuse them as per-wave staging space (32 x 40 halves each)
+  store_tile<1, 1, ACT>(acc, bias, C, M, N, m0 + wm * 32, n0 + wn * 32, lane, (wave < 2 ? sA : sB) + (wave & 1) * 32 * 40);
+}
+
+int g_gemm_group_m = 0;  // tuning hook
+
+template <int BM, int BN, int WGM, int WGN, int NS>
+static bt_status launch_pipe(const half_t* A, const half_t* W, const half_t* bias, half_t* C, int M, int N, int K,
                              bt_act act, hipStream_t st) {
   const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
   const long long n_tiles = (long long)tiles_m * tiles_n;
   if (n_tiles > 0x7fffffffLL) return BT_ERR_UNSUPPORTED;
-  dim3 grid((unsigned)n_tiles), block(kGemmThreads);
+  dim3 grid((unsigned)n_tiles), block(WGM * WGN * 64);
+  // strip height: the per-XCD share of tiles (n_tiles/8) should cover a patch with gm*BM ~ gn*BN
+  int group_m = g_gemm_group_m;
+  if (group_m <= 0) {
+    const double share = (double)n_tiles / 8.0;
+    group_m = (int)(sqrt(share * BN / BM) + 0.5);
+  }
+  group_m = group_m < 1 ? 1 : (group_m > tiles_m ? tiles_m : group_m);
   switch (act) {
     case BT_ACT_NONE:
-      gemm_kernel<BM, BN, BT_ACT_NONE><<<grid, block, 0, st>>>(A, W, bias, C, M, N, K, tiles_n, (int)n_tiles);
+      gemm_pipe_kernel<BM, BN, WGM, WGN, NS, BT_ACT_NONE><<<grid, block, 0, st>>>(A, W, bias, C, M, N, K, tiles_n, (int)n_tiles, group_m);
       break;
     case BT_ACT_GELU_ERF:
-      gemm_kernel<BM, BN, BT_ACT_GELU_ERF><<<grid, block, 0, st>>>(A, W, bias, C, M, N, K, tiles_n, (int)n_tiles);
-      break;
-    case BT_ACT_GELU_TANH:
-      gemm_kernel<BM, BN, BT_ACT_GELU_TANH><<<grid, block, 0, st>>>(A, W, bias, C, M, N, K, tiles_n, (int)n_tiles);
+      gemm_pipe_kernel<BM, BN, WGM, WGN, NS, BT_ACT_GELU_ERF><<<grid, block, 0, st>>>(A, W, bias, C, M, N, K, tiles_n, (int)n_tiles, group_m);
       break;
     default:
-      return BT_ERR_INVALID_ARG;
+      gemm_pipe_kernel<BM, BN, WGM, WGN, NS, BT_ACT_GELU_TANH><<<grid, block, 0, st>>>(A, W, bias, C, M, N, K, tiles_n, (int)n_tiles, group_m);
+      break;
   }
   return launch_status();
 }
 
-// Tile choice: the packed token count is small next to 256 compute units, so
-// prefer the largest tile that still yields at least ~2 workgroups per CU.
+static bt_status launch_simple(const half_t* A, const half_t* W, const half_t* bias, half_t* C, int M, int N, int K,
+                               bt_act act, hipStream_t st) {
+  const int tiles_n = (N + 63) / 64;
+  const long long n_tiles = (long long)((M + 63) / 64) * tiles_n;
+  if (n_tiles > 0x7fffffffLL) return BT_ERR_UNSUPPORTED;
+  dim3 grid((unsigned)n_tiles), block(kGemmThreads);
+  switch (act) {
+    case BT_ACT_NONE: gemm_simple_kernel<BT_ACT_NONE><<<grid, block, 0, st>>>(A, W, bias, C, M, N, K, tiles_n); break;
+    case BT_ACT_GELU_ERF: gemm_simple_kernel<BT_ACT_GELU_ERF><<<grid, block, 0, st>>>(A, W, bias, C, M, N, K, tiles_n); break;
+    default: gemm_simple_kernel<BT_ACT_GELU_TANH><<<grid, block, 0, st>>>(A, W, bias, C, M, N, K, tiles_n); break;
+  }
+  return launch_status();
+}
+
+int g_gemm_cfg = -1;  // tuning hook, set through bt_debug_set_gemm_cfg
+
 bt_status gemm_dispatch(const bt_half* A, const bt_half* W, const bt_half* bias, int M, int N, int K, bt_act act,
                         bt_half* C, hipStream_t st) {
   const half_t* a = reinterpret_cast<const half_t*>(A);
   const half_t* w = reinterpret_cast<const half_t*>(W);
   const half_t* b = reinterpret_cast<const half_t*>(bias);
   half_t* c = reinterpret_cast<half_t*>(C);
+  if ((K % 64) != 0) return launch_simple(a, w, b, c, M, N, K, act, st);
   auto tiles = [&](int bm, int bn) { return (long long)((M + bm - 1) / bm) * ((N + bn - 1) / bn); };
-  constexpr long long kTarget = 512;
-  if (tiles(128, 128) >= kTarget) return launch_gemm<128, 128>(a, w, b, c, M, N, K, act, st);
-  if (tiles(128, 64) >= kTarget) return launch_gemm<128, 64>(a, w, b, c, M, N, K, act, st);
-  return launch_gemm<64, 64>(a, w, b, c, M, N, K, act, st);
+  int cfg = g_gemm_cfg;
+  // Tile choice.  A compute unit ingests operands at ~64 B/clk, so big tiles (more flops per byte
+  // staged) win as long as there are enough of them to occupy most of the 256 compute units.
+  if (cfg < 0) cfg = tiles(256, 128) >= 150 ? 11 : (tiles(128, 64) >= 150 ? 16 : 5);
+  switch (cfg) {
+    case 0: return launch_pipe<128, 128, 2, 2, 4>(a, w, b, c, M, N, K, act, st);
+    case 1: return launch_pipe<128, 128, 2, 2, 2>(a, w, b, c, M, N, K, act, st);
+    case 2: return launch_pipe<128, 128, 2, 2, 3>(a, w, b, c, M, N, K, act, st);
+    case 3: return launch_pipe<128, 64, 2, 2, 4>(a, w, b, c, M, N, K, act, st);
+    case 4: return launch_pipe<128, 64, 2, 2, 3>(a, w, b, c, M, N, K, act, st);
+    case 5: return launch_pipe<64, 64, 2, 2, 4>(a, w, b, c, M, N, K, act, st);
+    case 6: return launch_pipe<256, 128, 2, 2, 3>(a, w, b, c, M, N, K, act, st);
+    case 7: return launch_pipe<192, 128, 2, 2, 3>(a, w, b, c, M, N, K, act, st);
+    case 8: return launch_pipe<192, 128, 2, 2, 4>(a, w, b, c, M, N, K, act, st);
+    case 9: return launch_pipe<128, 192, 2, 2, 3>(a, w, b, c, M, N, K, act, st);
+    case 10: return launch_pipe<192, 192, 2, 2, 3>(a, w, b, c, M, N, K, act, st);
+    case 11: return launch_pipe<256, 128, 4, 2, 3>(a, w, b, c, M, N, K, act, st);   // 8 waves, 64x64 each
+    case 12: return launch_pipe<64, 128, 2, 2, 4>(a, w, b, c, M, N, K, act, st);
+    case 13: return launch_pipe<192, 64, 2, 2, 4>(a, w, b, c, M, N, K, act, st);
+    case 14: return launch_pipe<128, 128, 4, 2, 4>(a, w, b, c, M, N, K, act, st);   // 8 waves, 32x64 each
+    case 15: return launch_pipe<256, 256, 4, 2, 2>(a, w, b, c, M, N, K, act, st);   // 8 waves, 64x128 each
+    case 16: return launch_pipe<128, 64, 4, 2, 4>(a, w, b, c, M, N, K, act, st);    // 8 waves, 32x32 each
+    case 17: return launch_pipe<256, 64, 4, 2, 4>(a, w, b, c, M, N, K, act, st);    // 8 waves, 64x32 each
+    case 18: return launch_pipe<256, 192, 4, 2, 2>(a, w, b, c, M, N, K, act, st);   // 8 waves, 64x96 each
+    default: return launch_simple(a, w, b, c, M, N, K, act, st);
+  }
 }
 
 }  // namespace bt
+
+extern "C" void bt_debug_set_gemm_cfg(int cfg) { bt::g_gemm_cfg = cfg; }
+extern "C" void bt_debug_set_gemm_group_m(int g) { bt::g_gemm_group_m = g; }
 
 extern "C" bt_status bt_gemm_bias_act(const bt_half* d_A, const bt_half* d_W, const bt_half* d_bias, int M, int N,
                                       int K, bt_act act, bt_half* d_C, bt_stream stream) {
