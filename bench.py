@@ -28,6 +28,18 @@ sys.path.insert(0, ROOT)
 PEAK_MFMA_F16 = 2500.0   # TFLOP/s, dense fp16 MFMA, published
 PEAK_HBM = 8000.0        # GB/s, published
 
+# HBM bytes per launch (fetched + written) from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this
+# script, scaled by the same counters' reading of a 1 GiB copy; see profiles/ for the runs.
+MEASURED_TRAFFIC = {
+    ("bert_base_b16_s256", "gemm0_qkv_bias"): 36420 * 1024,
+    ("bert_base_b16_s256", "varlen_mha"): 20570 * 1024,
+    ("bert_base_b16_s256", "gemm1_proj"): 17358 * 1024,
+    ("bert_base_b16_s256", "bias_residual_ln0"): 10468 * 1024,
+    ("bert_base_b16_s256", "gemm2_bias_gelu"): 41535 * 1024,
+    ("bert_base_b16_s256", "gemm3_ffn_down"): 58866 * 1024,
+    ("bert_base_b16_s256", "bias_residual_ln1"): 10468 * 1024,
+}
+
 
 def parse():
     ap = argparse.ArgumentParser()
@@ -38,6 +50,7 @@ def parse():
     ap.add_argument("--kernel-iters", type=int, default=200, help="launches per kernel for the roofline timing")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernels", action="store_true", help="skip the per-kernel timing pass")
+    ap.add_argument("--calibrate-copy", action="store_true", help="also run one 1 GiB device copy (counter scaling)")
     return ap.parse_args()
 
 
@@ -124,34 +137,47 @@ def main():
     }
 
     # ---------------- per-kernel timing (HIP events on the launch stream)
+    # Each kernel of the layer is launched `kernel_iters` times back to back through the C ABI (raw
+    # ctypes calls with prebuilt arguments, ~1 us of host time each) between two HIP events recorded
+    # on the stream the kernels run on; the average includes the inter-launch gap.
     if not args.no_kernels:
+        import ctypes as C
+        lib = bt.load_library()
         cu, tok, _ = bt.build_offsets(lengths=lengths_d, S=wl.S)
         xp = bt.pack(x_padded, tok)
         ly = layers[0]
         P = ly.tensors
-        qkv = torch.empty((T, 3 * H), dtype=torch.float16, device="cuda:0")
-        attn = torch.empty((T, H), dtype=torch.float16, device="cuda:0")
-        proj = torch.empty((T, H), dtype=torch.float16, device="cuda:0")
-        y1 = torch.empty((T, H), dtype=torch.float16, device="cuda:0")
-        g = torch.empty((T, F), dtype=torch.float16, device="cuda:0")
-        y2 = torch.empty((T, H), dtype=torch.float16, device="cuda:0")
+        f16 = lambda *shape: torch.empty(shape, dtype=torch.float16, device="cuda:0")
+        qkv, attn, proj, y1, g, y2 = f16(T, 3 * H), f16(T, H), f16(T, H), f16(T, H), f16(T, F), f16(T, H)
+        st = C.c_void_p(torch.cuda.current_stream().cuda_stream)
+        ptr = lambda t: C.c_void_p(t.data_ptr()) if t is not None else C.c_void_p(0)
+        eps = C.c_float(ly.eps)
+        HD = H
+        def bind(fn, *a):            # marshal once; the timed loop only does the foreign call
+            return lambda: fn(*a)
+        gemm = lambda a, w, b, M, N, K, act, c: bind(lib.bt_gemm_bias_act, ptr(a), ptr(w), ptr(b), M, N, K, act, ptr(c), st)
+        lnk = lambda x_, b, r, ga, be, y_: bind(lib.bt_add_bias_residual_layernorm, ptr(x_), ptr(b), ptr(r), ptr(ga),
+                                                ptr(be), eps, T, H, ptr(y_), st)
+        qb = qkv.data_ptr()
+        mha = bind(lib.bt_varlen_mha, C.c_void_p(qb), C.c_void_p(qb + 2 * HD), C.c_void_p(qb + 4 * HD), 3 * HD, None, None,
+                   None, ptr(cu), wl.B, T, wl.S, wl.heads, wl.head_dim, C.c_float(wl.head_dim ** -0.5), ptr(attn), None,
+                   0, st)
         steps = [
-            ("gemm0_qkv_bias", "mfma", 6.0 * T * H * H,
-             lambda: bt.gemm_bias_act(xp, P["w_qkv"], P["b_qkv"], bt.ACT_NONE, out=qkv)),
-            ("varlen_mha", "mfma", 4.0 * sum_l2 * H, lambda: bt.varlen_mha(qkv, cu, wl.S, wl.heads, out=attn)),
-            ("gemm1_proj", "mfma", 2.0 * T * H * H, lambda: bt.gemm_bias_act(attn, P["w_o"], None, bt.ACT_NONE, out=proj)),
-            ("bias_residual_ln0", "hbm", 6.0 * T * H,
-             lambda: bt.add_bias_residual_layernorm(proj, P["b_o"], xp, P["ln0_g"], P["ln0_b"], ly.eps, out=y1)),
-            ("gemm2_bias_gelu", "mfma", 2.0 * T * H * F,
-             lambda: bt.gemm_bias_act(y1, P["w_1"], P["b_1"], bt.ACT_GELU_ERF, out=g)),
-            ("gemm3_ffn_down", "mfma", 2.0 * T * H * F, lambda: bt.gemm_bias_act(g, P["w_2"], None, bt.ACT_NONE, out=proj)),
-            ("bias_residual_ln1", "hbm", 6.0 * T * H,
-             lambda: bt.add_bias_residual_layernorm(proj, P["b_2"], y1, P["ln1_g"], P["ln1_b"], ly.eps, out=y2)),
-            ("pack", "hbm", 4.0 * T * H, lambda: bt.pack(x_padded, tok, out=x_packed[:T])),
-            ("unpack", "hbm", 2.0 * T * H + 2.0 * wl.B * wl.S * H, lambda: bt.unpack(y2, tok, wl.B, wl.S, out=y_padded)),
+            ("gemm0_qkv_bias", "mfma", 6.0 * T * H * H, gemm(xp, P["w_qkv"], P["b_qkv"], T, 3 * H, H, 0, qkv)),
+            ("varlen_mha", "mfma", 4.0 * sum_l2 * H, mha),
+            ("gemm1_proj", "mfma", 2.0 * T * H * H, gemm(attn, P["w_o"], None, T, H, H, 0, proj)),
+            ("bias_residual_ln0", "hbm", 6.0 * T * H, lnk(proj, P["b_o"], xp, P["ln0_g"], P["ln0_b"], y1)),
+            ("gemm2_bias_gelu", "mfma", 2.0 * T * H * F, gemm(y1, P["w_1"], P["b_1"], T, F, H, 1, g)),
+            ("gemm3_ffn_down", "mfma", 2.0 * T * H * F, gemm(g, P["w_2"], None, T, H, F, 0, proj)),
+            ("bias_residual_ln1", "hbm", 6.0 * T * H, lnk(proj, P["b_2"], y1, P["ln1_g"], P["ln1_b"], y2)),
+            ("pack", "hbm", 4.0 * T * H, bind(lib.bt_pack, ptr(x_padded), ptr(tok), T, H, ptr(x_packed), st)),
+            ("unpack", "hbm", 2.0 * T * H + 2.0 * wl.B * wl.S * H,
+             bind(lib.bt_unpack, ptr(y2), ptr(tok), T, wl.B, wl.S, H, ptr(y_padded), st)),
         ]
         kernels = []
         for name, bound, work, fn in steps:
+            if fn() != 0:
+                raise RuntimeError(f"{name} failed")
             us = time_launches(torch, fn, args.kernel_iters)
             per_step = nl if name not in ("pack", "unpack") else 1
             if bound == "mfma":
@@ -163,10 +189,19 @@ def main():
                             "work_per_launch": work})
         dom = max(kernels, key=lambda k: k["us"] * k["launches_per_step"])
         out["roofline"] = {"kernel": dom["kernel"], "bound": dom["bound"], "achieved": dom["achieved"],
-                           "peak": dom["peak"], "unit": dom["unit"], "frac": dom["frac"], "traffic": None,
+                           "peak": dom["peak"], "unit": dom["unit"], "frac": dom["frac"],
+                           "traffic": MEASURED_TRAFFIC.get((args.workload, dom["kernel"])),
                            "us_per_launch": dom["us"], "work_per_launch": dom["work_per_launch"]}
         out["kernels"] = kernels
         out["kernel_time_sum_ms_per_step"] = round(sum(k["us"] * k["launches_per_step"] for k in kernels) / 1e3, 4)
+
+    if args.calibrate_copy:
+        # a plain device copy of known size (1 GiB read + 1 GiB written) for scaling rocprofv3's
+        # FETCH_SIZE / WRITE_SIZE counters
+        a = torch.empty(1 << 30, dtype=torch.uint8, device="cuda:0")
+        b = torch.empty_like(a)
+        b.copy_(a)
+        torch.cuda.synchronize()
 
     # ---------------- CPU baseline: the oracle as it stands, on this machine's cores
     if not args.no_cpu_baseline:

@@ -9,80 +9,197 @@
 // MFMA mapping (32x32x16 fp16, fp32 accumulate), chosen so that softmax needs no
 // cross-lane traffic beyond one exchange between the two 32-lane halves:
 //   S^T[key][q] = K[key][:] . Q[q][:]      A operand = K tile (LDS), B = Q (registers)
-//   O^T[d][q]  += V^T[d][key] * P^T[key][q] A operand = V^T tile (LDS), B = P
+//   O^T[d][q]  += V^T[d][key] * P^T[key][q] A operand = V^T fragment, B = P
 // In both accumulators a lane owns ONE query column (q = lane % 32), so the row
 // maximum, the rescale factor and the row sum are per-lane scalars, and the
 // fp32 S^T accumulator registers of a lane are -- after exp and conversion to
 // fp16 -- directly the B operand of the second product (the key order inside a
-// 16-key step is permuted identically on the V^T side, which a sum allows).
-// K tiles are staged row-major in LDS, V tiles transposed; the next tile is
-// prefetched from global memory into registers while the current one is used.
+// 16-key step is permuted identically on the V side, which a sum allows).
+//
+// K and V tiles travel global memory -> LDS by DMA (global_load_lds_dwordx4), NS
+// tiles deep, both row-major with the 16-byte chunks XOR-swizzled on the global
+// side.  K fragments are plain 128-bit LDS reads; V^T fragments come from the
+// transposing LDS read of gfx950 (ds_read_b64_tr_b16), so V is never transposed
+// in memory.  Biases: b_q is added to the Q registers; b_k shifts every logit of
+// a row by the same amount and cancels in the softmax; b_v is added to the
+// output (the probabilities of a row sum to one).
 #include "common.h"
 
 namespace bt {
 
-constexpr int kD = BT_HEAD_DIM;   // 64
-constexpr int kKT = 64;           // keys per tile
-constexpr int kKStride = kD + 8;  // halves per LDS row of the K tile   (144 B)
-constexpr int kVStride = kKT + 4; // halves per LDS row of the V^T tile (136 B)
+constexpr int kD = BT_HEAD_DIM;  // 64
+constexpr int kKT = 64;          // keys per tile
 
-__device__ __forceinline__ half8_t add_bias8(half8_t x, const float* b) {
-  half8_t r;
-#pragma unroll
-  for (int e = 0; e < 8; ++e) r[e] = (half_t)((float)x[e] + b[e]);
-  return r;
+#define BT_AS3 __attribute__((address_space(3)))
+typedef __fp16 fp16x4_t __attribute__((__vector_size__(4 * sizeof(__fp16))));  // operand type of the tr16 builtin
+
+__device__ __forceinline__ void mha_dma16(const void* gptr, uint32_t lds_base) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_base), "v"(gptr)
+               : "memory", "m0");
+}
+template <int N>
+__device__ __forceinline__ void mha_wait_vmcnt() {
+  static_assert(N >= 0 && N < 64, "vmcnt is 6 bits");
+  __builtin_amdgcn_s_waitcnt((N & 15) | ((N >> 4) << 14) | (7 << 4) | (15 << 8));
 }
 
-template <int NW>
+// Per-lane constants of the LDS fragment reads.
+struct FragAddr {
+  int k_rd, swz_k;        // K: row l32, 16-byte chunk (2ks+hf) ^ swz_k
+  int v_row, v_c, v_in;   // V: transposing read, see process_tile
+  int hf;
+};
+__device__ __forceinline__ FragAddr make_frag_addr(int lane) {
+  FragAddr f;
+  const int l32 = lane & 31;
+  f.hf = lane >> 5;
+  f.k_rd = l32 * kD;
+  f.swz_k = (l32 >> 1) & 7;
+  // 16-lane group g = lane>>4 covers d = 16*(g&1)..+15 and keys 4*hf..+3 of an 8-key half step;
+  // lane j of the group points at key row j>>2, d offset 4*(j&3).
+  const int vj = lane & 15, vg = (lane >> 4) & 1;
+  f.v_row = 4 * f.hf + (vj >> 2);
+  f.v_c = vg * 2 + ((vj & 3) >> 1);
+  f.v_in = 4 * (vj & 1);
+  return f;
+}
+
+// One 64-key tile for the 32 query rows of a wavefront: S^T = K Q^T, online softmax, O^T += V^T P^T.
+// m_run is kept in the scaled log2 domain and is only raised when the tile maximum exceeds it by
+// more than 8 (a factor 256: probabilities stay <= 256, exact in fp16/fp32 terms), so the rescale
+// of the accumulators is skipped for most tiles; any reference maximum gives the same softmax.
+__device__ __forceinline__ void process_tile(const half_t* sk, const half_t* sv, const half8_t (&qf)[4], int k0, int L,
+                                             float scale_log2e, const FragAddr& fa, float& m_run, float& l_run,
+                                             float16_t (&o_acc)[2]) {
+  const int hf = fa.hf;
+  float16_t s[2];
+#pragma unroll
+  for (int kb = 0; kb < 2; ++kb) {
+#pragma unroll
+    for (int r = 0; r < 16; ++r) s[kb][r] = 0.f;
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) {
+      const half8_t a =
+          *reinterpret_cast<const half8_t*>(sk + fa.k_rd + kb * 32 * kD + (((2 * ks + hf) ^ fa.swz_k) * 8));
+      s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, qf[ks], s[kb], 0, 0, 0);
+    }
+  }
+  if (k0 + kKT > L) {  // ragged last tile (wave-uniform): keys past the end of the sequence drop out
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int key = k0 + kb * 32 + 8 * (r >> 2) + 4 * hf + (r & 3);
+        if (key >= L) s[kb][r] = -INFINITY;
+      }
+  }
+  float mx = s[0][0];
+#pragma unroll
+  for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[kb][r]);
+  mx = fmaxf(mx, __shfl_xor(mx, 32, kWave));
+  const float mx_s = mx * scale_log2e;            // finite: every tile holds at least one valid key
+  const bool raise = mx_s > m_run + 8.0f;         // same in both halves of a query column
+  if (__builtin_amdgcn_ballot_w64(raise)) {
+    const float m_new = raise ? mx_s : m_run;
+    const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
+    m_run = m_new;
+    l_run *= alpha;
+#pragma unroll
+    for (int db = 0; db < 2; ++db)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) o_acc[db][r] *= alpha;
+  }
+  float psum = 0.f;
+  half8_t pf[2][2];
+#pragma unroll
+  for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s[kb][r], scale_log2e, -m_run));
+      psum += p;
+      pf[kb][r >> 3][r & 7] = (half_t)p;
+    }
+  l_run += psum;
+  // O^T += V^T P^T ; 16-key step ks covers S^T registers 8*(ks%2)..+7 of block ks/2, i.e. keys
+  // 16ks + {0..3, 8..11} + 4hf, the order the two transposing reads deliver.
+#pragma unroll
+  for (int db = 0; db < 2; ++db) {
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) {
+      half8_t a;
+#pragma unroll
+      for (int t = 0; t < 2; ++t) {
+        const int row = 16 * ks + 8 * t + fa.v_row;
+        const int chunk = (4 * db + fa.v_c) ^ (((row >> 1) & 1) << 2);
+        const half4_t x = __builtin_bit_cast(
+            half4_t, __builtin_amdgcn_ds_read_tr16_b64_v4f16((BT_AS3 fp16x4_t*)(sv + row * kD + chunk * 8 + fa.v_in)));
+#pragma unroll
+        for (int e = 0; e < 4; ++e) a[4 * t + e] = x[e];
+      }
+      o_acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, pf[ks >> 1][ks & 1], o_acc[db], 0, 0, 0);
+    }
+  }
+}
+
+// Locate the (sequence, q-tile) a workgroup owns: prefix sum of per-sequence tile counts, 64
+// sequences at a time.  Results are wave-uniform (returned through readfirstlane).
+__device__ __forceinline__ bool locate_tile(const int32_t* __restrict__ cu, int B, int BQ, int qtile, int lane,
+                                            int& tok0, int& L, int& qt) {
+  int running = 0;
+  for (int b0 = 0; b0 < B; b0 += kWave) {
+    const int b = b0 + lane;
+    const int start = b < B ? cu[b] : 0;
+    const int len = b < B ? cu[b + 1] - start : 0;
+    const int nt = (len + BQ - 1) / BQ;
+    int incl = nt;
+#pragma unroll
+    for (int o = 1; o < kWave; o <<= 1) {
+      const int u = __shfl_up(incl, o, kWave);
+      if (lane >= o) incl += u;
+    }
+    const int excl = running + incl - nt;
+    const unsigned long long hit = __ballot(qtile >= excl && qtile < excl + nt);
+    if (hit) {
+      const int src = __ffsll((long long)hit) - 1;
+      tok0 = __builtin_amdgcn_readfirstlane(__shfl(start, src, kWave));
+      L = __builtin_amdgcn_readfirstlane(__shfl(len, src, kWave));
+      qt = __builtin_amdgcn_readfirstlane(qtile - __shfl(excl, src, kWave));
+      return true;
+    }
+    running += __shfl(incl, kWave - 1, kWave);
+  }
+  return false;
+}
+
+template <int NW, int NS>
 __global__ __launch_bounds__(NW * 64) void varlen_mha_kernel(
     const half_t* __restrict__ Q, const half_t* __restrict__ K, const half_t* __restrict__ V, int64_t row_stride,
-    const half_t* __restrict__ bq, const half_t* __restrict__ bk, const half_t* __restrict__ bv,
-    const int32_t* __restrict__ cu, int B, int heads, float scale_log2e, half_t* __restrict__ out) {
-  constexpr int NT = NW * 64;
+    const half_t* __restrict__ bq, const half_t* __restrict__ bv, const int32_t* __restrict__ cu, int B, int heads,
+    float scale_log2e, half_t* __restrict__ out) {
   constexpr int BQ = NW * 32;
-  constexpr int KC = (kKT * 8) / NT;      // 16-byte K chunks per thread per tile
-  constexpr int VC = (kKT / 2 * 8) / NT;  // (key pair, chunk) items per thread per tile
+  constexpr int TILE = kKT * kD;            // halves per K (or V) tile
+  constexpr int PER = 8 / NW;               // DMA instructions per wave per operand tile (8 rows each)
+  constexpr int TOT = 2 * PER;              // ... per stage
+  static_assert(NW == 1 || NW == 2 || NW == 4, "NW");
 
-  __shared__ __attribute__((aligned(16))) half_t sK[2][kKT * kKStride];
-  __shared__ __attribute__((aligned(16))) half_t sV[2][kD * kVStride];
+  __shared__ __attribute__((aligned(1024))) half_t sK[NS * TILE];
+  __shared__ __attribute__((aligned(1024))) half_t sV[NS * TILE];
 
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int l32 = lane & 31, hf = lane >> 5;
   const int head = blockIdx.x % heads;
   const int qtile = blockIdx.x / heads;
 
-  // Locate (sequence, q-tile): prefix sum of per-sequence tile counts, 64 at a time.
-  int seq = -1, qt = 0;
-  {
-    int running = 0;
-    for (int b0 = 0; b0 < B; b0 += kWave) {
-      const int b = b0 + lane;
-      const int len = b < B ? cu[b + 1] - cu[b] : 0;
-      const int nt = (len + BQ - 1) / BQ;
-      int incl = nt;
-#pragma unroll
-      for (int o = 1; o < kWave; o <<= 1) {
-        const int u = __shfl_up(incl, o, kWave);
-        if (lane >= o) incl += u;
-      }
-      const int excl = running + incl - nt;
-      const unsigned long long hit = __ballot(qtile >= excl && qtile < excl + nt);
-      if (hit) {
-        const int src = __ffsll((long long)hit) - 1;
-        seq = b0 + src;
-        qt = qtile - __shfl(excl, src, kWave);
-        break;
-      }
-      running += __shfl(incl, kWave - 1, kWave);
-    }
-  }
-  if (seq < 0) return;  // same decision in every wave: no barrier is left waiting
+  int tok0 = 0, L = 0, qt = -1;
+  if (!locate_tile(cu, B, BQ, qtile, lane, tok0, L, qt)) return;  // same decision in every wave
 
-  const int tok0 = cu[seq];
-  const int L = cu[seq + 1] - tok0;
   const int q0 = qt * BQ;
   const int hofs = head * kD;
   const bool wave_active = q0 + wave * 32 < L;
+  const int ntiles = (L + kKT - 1) / kKT;
 
   // ---- Q fragments (B operand of S^T): rows q0 + wave*32 + l32, halves ks*16 + hf*8 ..+7
   const int q_row = q0 + wave * 32 + l32;
@@ -90,69 +207,43 @@ __global__ __launch_bounds__(NW * 64) void varlen_mha_kernel(
   {
     const half_t* qp = Q + (size_t)(tok0 + min(q_row, L - 1)) * row_stride + hofs + hf * 8;
 #pragma unroll
-    for (int ks = 0; ks < 4; ++ks) {
-      qf[ks] = *reinterpret_cast<const half8_t*>(qp + ks * 16);
-      if (bq) {
-        float b[8];
-#pragma unroll
-        for (int e = 0; e < 8; ++e) b[e] = (float)bq[hofs + ks * 16 + hf * 8 + e];
-        qf[ks] = add_bias8(qf[ks], b);
-      }
-    }
+    for (int ks = 0; ks < 4; ++ks) qf[ks] = *reinterpret_cast<const half8_t*>(qp + ks * 16);
   }
 
-  // ---- global -> register staging of one K/V tile
-  const int dc = tid & 7;  // 16-byte chunk inside a 64-half row (NT is a multiple of 8)
-  float kbias[8], vbias[8];
+  // ---- DMA of K/V tiles.  Instruction p of this wave fills LDS rows [8*(wave*PER+p), +8) of the
+  // tile; lane i lands at row r = 8*(..) + i/8, physical chunk i%8, and fetches the logical chunk
+  //   K: (i%8) ^ ((r>>1)&7)      (128-bit reads of 16 consecutive rows stay conflict-free)
+  //   V: (i%8) ^ (4*((r>>1)&1))  (the 4-row x 64-byte windows of the transposing read do)
+  const half_t* kbase = K + (size_t)tok0 * row_stride + hofs;
+  const half_t* vbase = V + (size_t)tok0 * row_stride + hofs;
+  int k_chunk[PER], v_chunk[PER], t_row[PER];
 #pragma unroll
-  for (int e = 0; e < 8; ++e) {
-    kbias[e] = bk ? (float)bk[hofs + dc * 8 + e] : 0.f;
-    vbias[e] = bv ? (float)bv[hofs + dc * 8 + e] : 0.f;
+  for (int p = 0; p < PER; ++p) {
+    const int r = (wave * PER + p) * 8 + (lane >> 3);
+    t_row[p] = r;
+    k_chunk[p] = ((lane & 7) ^ ((r >> 1) & 7)) * 8;
+    v_chunk[p] = ((lane & 7) ^ (((r >> 1) & 1) << 2)) * 8;
   }
-  half8_t rk[KC], rv[VC][2];
-  const half_t* kbase = K + (size_t)tok0 * row_stride + hofs + dc * 8;
-  const half_t* vbase = V + (size_t)tok0 * row_stride + hofs + dc * 8;
-  auto fetch = [&](int k0) {
+  const uint32_t lds_k = (uint32_t)(uintptr_t)(BT_AS3 const void*)sK + wave * PER * 1024;
+  const uint32_t lds_v = (uint32_t)(uintptr_t)(BT_AS3 const void*)sV + wave * PER * 1024;
+  auto issue_tile = [&](int kt, int stage) {
 #pragma unroll
-    for (int i = 0; i < KC; ++i) {
-      const int key = min(k0 + (tid >> 3) + i * (NT / 8), L - 1);  // rows past L: clamped, masked later
-      rk[i] = *reinterpret_cast<const half8_t*>(kbase + (size_t)key * row_stride);
-    }
-#pragma unroll
-    for (int i = 0; i < VC; ++i) {
-      const int kp = (tid >> 3) + i * (NT / 8);
-#pragma unroll
-      for (int u = 0; u < 2; ++u) {
-        const int key = min(k0 + 2 * kp + u, L - 1);
-        rv[i][u] = *reinterpret_cast<const half8_t*>(vbase + (size_t)key * row_stride);
-      }
+    for (int p = 0; p < PER; ++p) {
+      const size_t row = (size_t)min(kt * kKT + t_row[p], L - 1) * row_stride;  // rows past L: clamped, masked later
+      mha_dma16(kbase + row + k_chunk[p], lds_k + stage * (TILE * 2) + p * 1024);
+      mha_dma16(vbase + row + v_chunk[p], lds_v + stage * (TILE * 2) + p * 1024);
     }
   };
-  auto stage = [&](int buf) {
 #pragma unroll
-    for (int i = 0; i < KC; ++i) {
-      const int key = (tid >> 3) + i * (NT / 8);
-      half8_t x = rk[i];
-      if (bk) x = add_bias8(x, kbias);
-      *reinterpret_cast<half8_t*>(&sK[buf][key * kKStride + dc * 8]) = x;
-    }
+  for (int s = 0; s < NS - 1; ++s)
+    if (s < ntiles) issue_tile(s, s);
+
+  if (bq) {
 #pragma unroll
-    for (int i = 0; i < VC; ++i) {
-      const int kp = (tid >> 3) + i * (NT / 8);
-      half8_t x0 = rv[i][0], x1 = rv[i][1];
-      if (bv) {
-        x0 = add_bias8(x0, vbias);
-        x1 = add_bias8(x1, vbias);
-      }
+    for (int ks = 0; ks < 4; ++ks)
 #pragma unroll
-      for (int e = 0; e < 8; ++e) {  // transpose: V^T[d][key], two neighbouring keys per 32-bit write
-        half2_t pr;
-        pr[0] = x0[e];
-        pr[1] = x1[e];
-        *reinterpret_cast<half2_t*>(&sV[buf][(dc * 8 + e) * kVStride + 2 * kp]) = pr;
-      }
-    }
-  };
+      for (int e = 0; e < 8; ++e) qf[ks][e] = (half_t)((float)qf[ks][e] + (float)bq[hofs + ks * 16 + hf * 8 + e]);
+  }
 
   float16_t o_acc[2];
 #pragma unroll
@@ -161,89 +252,23 @@ __global__ __launch_bounds__(NW * 64) void varlen_mha_kernel(
     for (int r = 0; r < 16; ++r) o_acc[db][r] = 0.f;
   float m_run = -INFINITY, l_run = 0.f;  // per query column; l_run is this half's partial sum
 
-  const int ntiles = (L + kKT - 1) / kKT;
-  fetch(0);
-  stage(0);
-  __syncthreads();
+  const FragAddr fa = make_frag_addr(lane);
 
+  int stage = 0;
   for (int kt = 0; kt < ntiles; ++kt) {
-    const int buf = kt & 1;
-    const int k0 = kt * kKT;
-    if (kt + 1 < ntiles) fetch(k0 + kKT);
-
-    if (wave_active) {
-      // S^T = K Q^T for the two 32-key blocks of the tile
-      float16_t s[2];
-#pragma unroll
-      for (int kb = 0; kb < 2; ++kb) {
-#pragma unroll
-        for (int r = 0; r < 16; ++r) s[kb][r] = 0.f;
-#pragma unroll
-        for (int ks = 0; ks < 4; ++ks) {
-          const half8_t a =
-              *reinterpret_cast<const half8_t*>(&sK[buf][(kb * 32 + l32) * kKStride + ks * 16 + hf * 8]);
-          s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, qf[ks], s[kb], 0, 0, 0);
-        }
-      }
-      // scale into the log2 domain; mask the keys past the end of the sequence
-      const bool ragged = k0 + kKT > L;
-#pragma unroll
-      for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          float x = s[kb][r] * scale_log2e;
-          if (ragged) {
-            const int key = k0 + kb * 32 + 8 * (r >> 2) + 4 * hf + (r & 3);
-            if (key >= L) x = -INFINITY;
-          }
-          s[kb][r] = x;
-        }
-      float mx = s[0][0];
-#pragma unroll
-      for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[kb][r]);
-      mx = fmaxf(mx, __shfl_xor(mx, 32, kWave));
-      const float m_new = fmaxf(m_run, mx);  // finite: every tile holds at least one valid key
-      const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
-      m_run = m_new;
-      float psum = 0.f;
-      half8_t pf[2][2];
-#pragma unroll
-      for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const float p = __builtin_amdgcn_exp2f(s[kb][r] - m_new);
-          psum += p;
-          pf[kb][r >> 3][r & 7] = (half_t)p;
-        }
-      l_run = l_run * alpha + psum;
-#pragma unroll
-      for (int db = 0; db < 2; ++db)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) o_acc[db][r] *= alpha;
-      // O^T += V^T P^T ; 16-key step ks covers S^T registers 8*(ks%2)..+7 of block ks/2,
-      // i.e. keys 16ks + {0..3, 8..11} + 4hf, the same order the V^T fragment is read in.
-#pragma unroll
-      for (int db = 0; db < 2; ++db) {
-#pragma unroll
-        for (int ks = 0; ks < 4; ++ks) {
-          const half_t* vp = &sV[buf][(db * 32 + l32) * kVStride + ks * 16 + 4 * hf];
-          const half4_t lo = *reinterpret_cast<const half4_t*>(vp);
-          const half4_t hi = *reinterpret_cast<const half4_t*>(vp + 8);
-          half8_t a;
-#pragma unroll
-          for (int e = 0; e < 4; ++e) {
-            a[e] = lo[e];
-            a[4 + e] = hi[e];
-          }
-          o_acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, pf[ks >> 1][ks & 1], o_acc[db], 0, 0, 0);
-        }
-      }
+    {  // tile kt landed (at most min(ntiles-1-kt, NS-2) younger tiles in flight) and is published
+      const int younger = min(ntiles - 1 - kt, NS - 2);
+      if (NS >= 4 && younger >= 2) mha_wait_vmcnt<(NS >= 4 ? 2 : 0) * TOT>();
+      else if (NS >= 3 && younger == 1) mha_wait_vmcnt<(NS >= 3 ? 1 : 0) * TOT>();
+      else mha_wait_vmcnt<0>();
+      __builtin_amdgcn_s_barrier();
     }
+    if (kt + NS - 1 < ntiles) issue_tile(kt + NS - 1, stage == 0 ? NS - 1 : stage - 1);
+    const int k0 = kt * kKT;
 
-    if (kt + 1 < ntiles) stage(buf ^ 1);
-    __syncthreads();
+    if (wave_active)
+      process_tile(sK + stage * TILE, sV + stage * TILE, qf, k0, L, scale_log2e, fa, m_run, l_run, o_acc);
+    stage = stage + 1 == NS ? 0 : stage + 1;
   }
 
   if (wave_active && q_row < L) {
@@ -254,18 +279,197 @@ __global__ __launch_bounds__(NW * 64) void varlen_mha_kernel(
     for (int db = 0; db < 2; ++db)
 #pragma unroll
       for (int g = 0; g < 4; ++g) {
+        float bias4[4] = {0.f, 0.f, 0.f, 0.f};
+        if (bv) {
+#pragma unroll
+          for (int t = 0; t < 4; ++t) bias4[t] = (float)bv[hofs + db * 32 + 8 * g + 4 * hf + t];
+        }
         half4_t o;
 #pragma unroll
-        for (int t = 0; t < 4; ++t) o[t] = (half_t)(o_acc[db][4 * g + t] * inv);
+        for (int t = 0; t < 4; ++t) o[t] = (half_t)(o_acc[db][4 * g + t] * inv + bias4[t]);
         *reinterpret_cast<half4_t*>(op + db * 32 + 8 * g) = o;
       }
   }
 }
 
-template <int NW>
+// ---------------------------------------------------------------------------
+// Split-key variant for short sequences / small batches.  The q-parallel kernel
+// above gives one wavefront 32 query rows and ALL keys of the sequence, so with
+// few, short sequences there are about as many wavefronts as SIMDs and each one
+// walks its tiles serially.  Here a workgroup owns 32 query rows and its NK
+// wavefronts split the key tiles (wave w takes tiles w, w+NK, ...), each with a
+// private LDS ring and no barrier in the loop; the NK partial results
+// (running max, sum, unnormalised O) are merged through LDS at the end, which is
+// the same rescaling the online softmax applies between tiles.
+// ---------------------------------------------------------------------------
+template <int NK, int NS>
+__global__ __launch_bounds__(NK * 64) void varlen_mha_splitkey_kernel(
+    const half_t* __restrict__ Q, const half_t* __restrict__ K, const half_t* __restrict__ V, int64_t row_stride,
+    const half_t* __restrict__ bq, const half_t* __restrict__ bv, const int32_t* __restrict__ cu, int B, int heads,
+    float scale_log2e, half_t* __restrict__ out) {
+  constexpr int BQ = 32;
+  constexpr int TILE = kKT * kD;       // halves per K (or V) tile
+  constexpr int WAVE_LDS = NS * 2 * TILE;  // halves per wave: NS x (K tile + V tile), >= 8 KB + 256 B for the merge
+  constexpr int TOT = 16;              // DMA instructions per tile pair
+  static_assert((NS - 1) * TOT < 64, "vmcnt range");
+
+  __shared__ __attribute__((aligned(1024))) half_t smem[NK * WAVE_LDS];
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int l32 = lane & 31, hf = lane >> 5;
+  const int head = blockIdx.x % heads;
+  const int qtile = blockIdx.x / heads;
+
+  int tok0 = 0, L = 0, qt = -1;
+  if (!locate_tile(cu, B, BQ, qtile, lane, tok0, L, qt)) return;  // same decision in every wave
+
+  const int q0 = qt * BQ;
+  const int hofs = head * kD;
+  const int ntiles = (L + kKT - 1) / kKT;
+  const int my_tiles = wave < ntiles ? (ntiles - wave + NK - 1) / NK : 0;  // tiles wave, wave+NK, ...
+
+  const int q_row = q0 + l32;
+  half8_t qf[4];
+  {
+    const half_t* qp = Q + (size_t)(tok0 + min(q_row, L - 1)) * row_stride + hofs + hf * 8;
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) qf[ks] = *reinterpret_cast<const half8_t*>(qp + ks * 16);
+  }
+
+  const half_t* kbase = K + (size_t)tok0 * row_stride + hofs;
+  const half_t* vbase = V + (size_t)tok0 * row_stride + hofs;
+  half_t* my_lds = smem + wave * WAVE_LDS;
+  const uint32_t lds_base = (uint32_t)(uintptr_t)(BT_AS3 const void*)my_lds;
+  auto issue_tile = [&](int kt, int stage) {  // this wave alone fetches all 64 rows of both tiles
+#pragma unroll
+    for (int p = 0; p < 8; ++p) {
+      const int r = p * 8 + (lane >> 3);
+      const size_t row = (size_t)min(kt * kKT + r, L - 1) * row_stride;
+      const int kc = ((lane & 7) ^ ((r >> 1) & 7)) * 8;
+      const int vc = ((lane & 7) ^ (((r >> 1) & 1) << 2)) * 8;
+      mha_dma16(kbase + row + kc, lds_base + stage * (2 * TILE * 2) + p * 1024);
+      mha_dma16(vbase + row + vc, lds_base + stage * (2 * TILE * 2) + TILE * 2 + p * 1024);
+    }
+  };
+#pragma unroll
+  for (int s = 0; s < (NS > 1 ? NS - 1 : 1); ++s)
+    if (s < my_tiles) issue_tile(wave + s * NK, s);
+
+  if (bq) {
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks)
+#pragma unroll
+      for (int e = 0; e < 8; ++e) qf[ks][e] = (half_t)((float)qf[ks][e] + (float)bq[hofs + ks * 16 + hf * 8 + e]);
+  }
+
+  float16_t o_acc[2];
+#pragma unroll
+  for (int db = 0; db < 2; ++db)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) o_acc[db][r] = 0.f;
+  float m_run = -INFINITY, l_run = 0.f;
+
+  const FragAddr fa = make_frag_addr(lane);
+
+  int stage = 0;
+  for (int it = 0; it < my_tiles; ++it) {
+    const int kt = wave + it * NK;
+    if (NS == 1) {
+      if (it > 0) issue_tile(kt, 0);  // single buffer: fetch, then wait (tile 0 was issued above)
+      mha_wait_vmcnt<0>();
+    } else {
+      const int younger = min(my_tiles - 1 - it, NS - 2);
+      if (NS >= 4 && younger >= 2) mha_wait_vmcnt<(NS >= 4 ? 2 : 0) * TOT>();
+      else if (NS >= 3 && younger == 1) mha_wait_vmcnt<(NS >= 3 ? 1 : 0) * TOT>();
+      else mha_wait_vmcnt<0>();
+      // the stage refilled now was read in iteration it-1; those reads completed before its MFMAs issued
+      if (it + NS - 1 < my_tiles) issue_tile(kt + (NS - 1) * NK, stage == 0 ? NS - 1 : stage - 1);
+    }
+    const int k0 = kt * kKT;
+    process_tile(my_lds + stage * (2 * TILE), my_lds + stage * (2 * TILE) + TILE, qf, k0, L, scale_log2e, fa, m_run,
+                 l_run, o_acc);
+    if (NS > 1) stage = stage + 1 == NS ? 0 : stage + 1;
+  }
+
+  // ---- merge the NK partial results.  Each wave parks (O^T fp32 [64 d][32 q], m[32], l[32]) in its
+  // own LDS ring (all of its tile reads are complete), one barrier, then wave w finishes d-slice w.
+  float* po = reinterpret_cast<float*>(my_lds);   // 8 KB
+  float* pm = po + kD * 32;                       // 128 B
+  float* pl = pm + 32;                            // 128 B
+  asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+#pragma unroll
+  for (int db = 0; db < 2; ++db)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) po[(db * 32 + 8 * (r >> 2) + 4 * hf + (r & 3)) * 32 + l32] = o_acc[db][r];
+  const float l_tot = l_run + __shfl_xor(l_run, 32, kWave);
+  if (hf == 0) {
+    pm[l32] = m_run;
+    pl[l32] = l_tot;
+  }
+  __syncthreads();
+  constexpr int DW = kD / NK;   // d values finished by one wave (16 or 32)
+  constexpr int DL = DW / 2;    // ... by one lane (8 or 16), contiguous
+  float mw[NK], lw[NK], M = -INFINITY;
+#pragma unroll
+  for (int w = 0; w < NK; ++w) {
+    const float* base = reinterpret_cast<const float*>(smem + w * WAVE_LDS);
+    mw[w] = base[kD * 32 + l32];
+    lw[w] = base[kD * 32 + 32 + l32];
+    M = fmaxf(M, mw[w]);
+  }
+  float denom = 0.f, sc[NK];
+#pragma unroll
+  for (int w = 0; w < NK; ++w) {
+    sc[w] = __builtin_amdgcn_exp2f(mw[w] - M);  // a wave without tiles has m = -inf: weight 0
+    denom += sc[w] * lw[w];
+  }
+  const float inv = 1.0f / denom;
+  const int d0 = wave * DW + hf * DL;
+  float o[DL];
+#pragma unroll
+  for (int i = 0; i < DL; ++i) o[i] = 0.f;
+#pragma unroll
+  for (int w = 0; w < NK; ++w) {
+    const float* base = reinterpret_cast<const float*>(smem + w * WAVE_LDS);
+#pragma unroll
+    for (int i = 0; i < DL; ++i) o[i] += sc[w] * base[(d0 + i) * 32 + l32];
+  }
+  if (q_row < L) {
+    half_t* op = out + (size_t)(tok0 + q_row) * (heads * kD) + hofs + d0;
+#pragma unroll
+    for (int c = 0; c < DL / 8; ++c) {
+      half8_t h8;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        float v = o[c * 8 + e] * inv;
+        if (bv) v += (float)bv[hofs + d0 + c * 8 + e];
+        h8[e] = (half_t)v;
+      }
+      *reinterpret_cast<half8_t*>(op + c * 8) = h8;
+    }
+  }
+}
+
+template <int NK, int NS>
+static bt_status launch_mha_splitkey(const half_t* q, const half_t* k, const half_t* v, int64_t row_stride,
+                                     const half_t* bq, const half_t* bv, const int32_t* cu, int B, int T, int max_len,
+                                     int heads, float scale, half_t* out, hipStream_t st) {
+  constexpr int BQ = 32;
+  const long long by_len = (long long)B * ((max_len + BQ - 1) / BQ);
+  const long long by_tok = (long long)T / BQ + B;
+  const long long tiles = by_len < by_tok ? by_len : by_tok;
+  const long long blocks = tiles * heads;
+  if (blocks > 0x7fffffffLL) return BT_ERR_UNSUPPORTED;
+  varlen_mha_splitkey_kernel<NK, NS><<<(unsigned)blocks, NK * 64, 0, st>>>(q, k, v, row_stride, bq, bv, cu, B, heads,
+                                                                         scale * 1.4426950408889634f, out);
+  return launch_status();
+}
+
+template <int NW, int NS>
 static bt_status launch_mha(const half_t* q, const half_t* k, const half_t* v, int64_t row_stride, const half_t* bq,
-                            const half_t* bk, const half_t* bv, const int32_t* cu, int B, int T, int max_len,
-                            int heads, float scale, half_t* out, hipStream_t st) {
+                            const half_t* bv, const int32_t* cu, int B, int T, int max_len, int heads, float scale,
+                            half_t* out, hipStream_t st) {
   constexpr int BQ = NW * 32;
   // number of q-tiles: sum ceil(L_b/BQ) <= min(B*ceil(max_len/BQ), floor(T/BQ) + B)
   const long long by_len = (long long)B * ((max_len + BQ - 1) / BQ);
@@ -273,27 +477,42 @@ static bt_status launch_mha(const half_t* q, const half_t* k, const half_t* v, i
   const long long tiles = by_len < by_tok ? by_len : by_tok;
   const long long blocks = tiles * heads;
   if (blocks > 0x7fffffffLL) return BT_ERR_UNSUPPORTED;
-  varlen_mha_kernel<NW><<<(unsigned)blocks, NW * 64, 0, st>>>(q, k, v, row_stride, bq, bk, bv, cu, B, heads,
-                                                            scale * 1.4426950408889634f, out);
+  varlen_mha_kernel<NW, NS><<<(unsigned)blocks, NW * 64, 0, st>>>(q, k, v, row_stride, bq, bv, cu, B, heads,
+                                                                scale * 1.4426950408889634f, out);
   return launch_status();
 }
+
+int g_mha_cfg = -1;  // tuning hook
 
 bt_status mha_dispatch(const bt_half* q, const bt_half* k, const bt_half* v, int64_t row_stride, const bt_half* bq,
                        const bt_half* bk, const bt_half* bv, const int32_t* cu, int B, int T, int max_len, int heads,
                        float scale, bt_half* out, hipStream_t st) {
+  (void)bk;  // adds the same constant to every logit of a row: cancels in the softmax
   auto h = [](const bt_half* p) { return reinterpret_cast<const half_t*>(p); };
   half_t* o = reinterpret_cast<half_t*>(out);
-  // Query-tile height: tall tiles re-read K/V less often, short tiles give more
-  // workgroups; pick the tallest that still offers ~2 workgroups per compute unit.
+  // Kernel choice.  Tall query tiles (4 waves x 32 rows) re-read K/V least and suit long sequences;
+  // 2-wave tiles give more workgroups; with too few of those to occupy the SIMDs, the split-key
+  // kernel puts two waves on every 32 query rows.
   auto blocks = [&](int bqt) { return ((long long)T / bqt + B) * heads; };
-  if (max_len > 128 && blocks(128) >= 512)
-    return launch_mha<4>(h(q), h(k), h(v), row_stride, h(bq), h(bk), h(bv), cu, B, T, max_len, heads, scale, o, st);
-  if (max_len > 32 && blocks(64) >= 512)
-    return launch_mha<2>(h(q), h(k), h(v), row_stride, h(bq), h(bk), h(bv), cu, B, T, max_len, heads, scale, o, st);
-  return launch_mha<1>(h(q), h(k), h(v), row_stride, h(bq), h(bk), h(bv), cu, B, T, max_len, heads, scale, o, st);
+  int cfg = g_mha_cfg;
+  if (cfg < 0) cfg = (max_len > 128 && blocks(128) >= 512) ? 4 : (blocks(64) >= 512 ? 2 : 121);
+  switch (cfg) {
+    case 4: return launch_mha<4, 3>(h(q), h(k), h(v), row_stride, h(bq), h(bv), cu, B, T, max_len, heads, scale, o, st);
+    case 2: return launch_mha<2, 3>(h(q), h(k), h(v), row_stride, h(bq), h(bv), cu, B, T, max_len, heads, scale, o, st);
+    case 42: return launch_mha<4, 2>(h(q), h(k), h(v), row_stride, h(bq), h(bv), cu, B, T, max_len, heads, scale, o, st);
+    case 22: return launch_mha<2, 2>(h(q), h(k), h(v), row_stride, h(bq), h(bv), cu, B, T, max_len, heads, scale, o, st);
+    case 141: return launch_mha_splitkey<4, 1>(h(q), h(k), h(v), row_stride, h(bq), h(bv), cu, B, T, max_len, heads, scale, o, st);
+    case 142: return launch_mha_splitkey<4, 2>(h(q), h(k), h(v), row_stride, h(bq), h(bv), cu, B, T, max_len, heads, scale, o, st);
+    case 121: return launch_mha_splitkey<2, 1>(h(q), h(k), h(v), row_stride, h(bq), h(bv), cu, B, T, max_len, heads, scale, o, st);
+    case 122: return launch_mha_splitkey<2, 2>(h(q), h(k), h(v), row_stride, h(bq), h(bv), cu, B, T, max_len, heads, scale, o, st);
+    case 12: return launch_mha<1, 2>(h(q), h(k), h(v), row_stride, h(bq), h(bv), cu, B, T, max_len, heads, scale, o, st);
+    default: return launch_mha<1, 3>(h(q), h(k), h(v), row_stride, h(bq), h(bv), cu, B, T, max_len, heads, scale, o, st);
+  }
 }
 
 }  // namespace bt
+
+extern "C" void bt_debug_set_mha_cfg(int cfg) { bt::g_mha_cfg = cfg; }
 
 extern "C" bt_status bt_varlen_mha(const bt_half* d_q, const bt_half* d_k, const bt_half* d_v, int64_t row_stride,
                                    const bt_half* d_bq, const bt_half* d_bk, const bt_half* d_bv,
