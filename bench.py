@@ -195,6 +195,40 @@ def main():
         out["kernels"] = kernels
         out["kernel_time_sum_ms_per_step"] = round(sum(k["us"] * k["launches_per_step"] for k in kernels) / 1e3, 4)
 
+        # ---- two more measured points named by the metric ----------------------------------------
+        # (a) variable-length MHA alone on the "attention alone" workload (b16, max 256, U[1,256])
+        wm = I.WORKLOADS["mha_b16_s256"]
+        Lm = I.draw_lengths(wm)
+        Tm, s2m = int(Lm.sum()), int((Lm.astype(np.int64) ** 2).sum())
+        qkv_m = dev(I.make_qkv_packed(wm, Tm))
+        cu_m = dev(np.concatenate([[0], np.cumsum(Lm)]).astype(np.int32))
+        out_m = f16(Tm, wm.H)
+        qm = qkv_m.data_ptr()
+        mha_m = bind(lib.bt_varlen_mha, C.c_void_p(qm), C.c_void_p(qm + 2 * wm.H), C.c_void_p(qm + 4 * wm.H), 3 * wm.H,
+                     None, None, None, ptr(cu_m), wm.B, Tm, wm.S, wm.heads, wm.head_dim,
+                     C.c_float(wm.head_dim ** -0.5), ptr(out_m), None, 0, st)
+        us_m = time_launches(torch, mha_m, args.kernel_iters)
+        out["varlen_mha_b16_s256"] = {"us": round(us_m, 2), "valid_tokens": Tm, "sum_len_sq": s2m,
+                                      "tflops": round(4.0 * s2m * wm.H / us_m / 1e6, 2),
+                                      "frac_mfma_peak": round(4.0 * s2m * wm.H / us_m / 1e6 / PEAK_MFMA_F16, 4)}
+        # (b) the HBM-bound kernels at a streaming shape (tensors >> the 256 MB Infinity Cache), same code path
+        Ts = 262144
+        xs, rs, ys = f16(Ts, H), f16(Ts, H), f16(Ts, H)
+        xs.normal_(); rs.normal_()
+        ln_s = bind(lib.bt_add_bias_residual_layernorm, ptr(xs), ptr(P["b_o"]), ptr(rs), ptr(P["ln0_g"]), ptr(P["ln0_b"]),
+                    eps, Ts, H, ptr(ys), st)
+        us_ln = time_launches(torch, ln_s, 20, warm=3)
+        tok_s = torch.arange(Ts, dtype=torch.int32, device="cuda:0")
+        pk_s = bind(lib.bt_pack, ptr(xs), ptr(tok_s), Ts, H, ptr(ys), st)
+        us_pk = time_launches(torch, pk_s, 20, warm=3)
+        out["hbm_streaming"] = {
+            "tokens": Ts, "hidden": H,
+            "bias_residual_ln": {"us": round(us_ln, 1), "GBps": round(6.0 * Ts * H / us_ln / 1e3, 1),
+                                 "frac_hbm_peak": round(6.0 * Ts * H / us_ln / 1e3 / PEAK_HBM, 4)},
+            "pack": {"us": round(us_pk, 1), "GBps": round(4.0 * Ts * H / us_pk / 1e3, 1),
+                     "frac_hbm_peak": round(4.0 * Ts * H / us_pk / 1e3 / PEAK_HBM, 4)}}
+        del xs, rs, ys
+
     if args.calibrate_copy:
         # a plain device copy of known size (1 GiB read + 1 GiB written) for scaling rocprofv3's
         # FETCH_SIZE / WRITE_SIZE counters

@@ -12,7 +12,7 @@ from concurrent.futures import ThreadPoolExecutor
 PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
-LIB = os.path.join(PKG, "libbt.so")
+LIB = os.environ.get("BT_LIB_OUT") or os.path.join(PKG, "libbt.so")   # BT_LIB_OUT: build a variant elsewhere
 SOURCES = ["offsets.hip", "gemm.hip", "layernorm.hip", "mha.hip", "layer.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
@@ -28,9 +28,10 @@ EXTRA_FLAGS = {"mha.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"]}
 
 
 def _compile(src: str) -> str:
-    obj = os.path.join(PKG, "_build", src.replace(".hip", ".o"))
+    obj = os.path.join(PKG, "_build", ("tuning_" if os.environ.get("BT_TUNING") == "1" else "") + src.replace(".hip", ".o"))
     os.makedirs(os.path.dirname(obj), exist_ok=True)
-    cmd = [HIPCC, *FLAGS, *EXTRA_FLAGS.get(src, []), "-c", os.path.join(CSRC, src), "-o", obj]
+    tuning = ["-DBT_TUNING"] if os.environ.get("BT_TUNING") == "1" else []   # sweep hooks + every tile shape
+    cmd = [HIPCC, *FLAGS, *tuning, *EXTRA_FLAGS.get(src, []), "-c", os.path.join(CSRC, src), "-o", obj]
     r = subprocess.run(cmd, capture_output=True, text=True)
     if r.returncode != 0:
         raise RuntimeError(f"hipcc failed on {src}:\n{r.stdout}\n{r.stderr}")

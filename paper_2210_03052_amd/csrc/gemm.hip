@@ -27,17 +27,25 @@ constexpr int kGemmThreads = 256;  // fallback kernel
 #define BT_AS1 __attribute__((address_space(1)))
 #define BT_AS3 __attribute__((address_space(3)))
 
-// erf by the rational/exponential fit of Abramowitz & Stegun 7.1.26 (|error| <= 1.5e-7, far below
-// the fp16 rounding of the result); an order of magnitude fewer instructions than libm's erff,
-// which matters because the epilogue runs once per output element.
-__device__ __forceinline__ float erf_as(float x) {
+// Exact-form GELU, x * Phi(x), with Phi from the complementary error function fit of Abramowitz &
+// Stegun 7.1.26: erfc(z) = (a1 t + ... + a5 t^5) exp(-z^2), t = 1/(1 + p z), z >= 0, |error| <= 1.5e-7
+// (far below the fp16 rounding of the result).  With z = |x|/sqrt(2):
+//   h = 0.5 erfc(z),  Phi(x) = x >= 0 ? 1 - h : h,  so  x Phi(x) = max(x,0) - |x| h.
+// About a dozen VALU instructions (two transcendental) against ~40 for libm's erff: the epilogue
+// runs once per output element and is not overlapped with MFMA work.
+__device__ __forceinline__ float gelu_erf(float x) {
   const float ax = fabsf(x);
-  const float t = __builtin_amdgcn_rcpf(1.0f + 0.3275911f * ax);
-  const float poly = t * (0.254829592f + t * (-0.284496736f + t * (1.421413741f + t * (-1.453152027f + t * 1.061405429f))));
-  const float e = __builtin_amdgcn_exp2f(-1.4426950408889634f * ax * ax);
-  return copysignf(1.0f - poly * e, x);
+  const float t = __builtin_amdgcn_rcpf(__builtin_fmaf(ax, 0.3275911f * 0.70710678118654752f, 1.0f));
+  const float e = __builtin_amdgcn_exp2f(x * x * (-0.5f * 1.4426950408889634f));
+  // 0.5 * (a1..a5)
+  float poly = __builtin_fmaf(t, 0.5f * 1.061405429f, 0.5f * -1.453152027f);
+  poly = __builtin_fmaf(t, poly, 0.5f * 1.421413741f);
+  poly = __builtin_fmaf(t, poly, 0.5f * -0.284496736f);
+  poly = __builtin_fmaf(t, poly, 0.5f * 0.254829592f);
+  const float h = poly * t * e;
+  // x*Phi(x) = x*(1-h) for x >= 0 and x*h for x < 0, i.e. max(x,0) - |x|*h in both cases
+  return __builtin_fmaf(-ax, h, fmaxf(x, 0.f));
 }
-__device__ __forceinline__ float gelu_erf(float x) { return 0.5f * x * (1.0f + erf_as(x * 0.70710678118654752f)); }
 __device__ __forceinline__ float gelu_tanh(float x) {
   const float u = 0.7978845608028654f * (x + 0.044715f * x * x * x);
   return 0.5f * x * (1.0f + tanhf(u));
@@ -312,7 +320,9 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_simple_kernel(const half_t*
   store_tile<1, 1, ACT>(acc, bias, C, M, N, m0 + wm * 32, n0 + wn * 32, lane, (wave < 2 ? sA : sB) + (wave & 1) * 32 * 40);
 }
 
-int g_gemm_group_m = 0;  // tuning hook
+#ifdef BT_TUNING
+int g_gemm_group_m = 0;
+#endif
 
 template <int BM, int BN, int WGM, int WGN, int NS>
 static bt_status launch_pipe(const half_t* A, const half_t* W, const half_t* bias, half_t* C, int M, int N, int K,
@@ -322,11 +332,10 @@ static bt_status launch_pipe(const half_t* A, const half_t* W, const half_t* bia
   if (n_tiles > 0x7fffffffLL) return BT_ERR_UNSUPPORTED;
   dim3 grid((unsigned)n_tiles), block(WGM * WGN * 64);
   // strip height: the per-XCD share of tiles (n_tiles/8) should cover a patch with gm*BM ~ gn*BN
-  int group_m = g_gemm_group_m;
-  if (group_m <= 0) {
-    const double share = (double)n_tiles / 8.0;
-    group_m = (int)(sqrt(share * BN / BM) + 0.5);
-  }
+  int group_m = (int)(sqrt((double)n_tiles / 8.0 * BN / BM) + 0.5);
+#ifdef BT_TUNING
+  if (g_gemm_group_m > 0) group_m = g_gemm_group_m;
+#endif
   group_m = group_m < 1 ? 1 : (group_m > tiles_m ? tiles_m : group_m);
   switch (act) {
     case BT_ACT_NONE:
@@ -356,7 +365,9 @@ static bt_status launch_simple(const half_t* A, const half_t* W, const half_t* b
   return launch_status();
 }
 
-int g_gemm_cfg = -1;  // tuning hook, set through bt_debug_set_gemm_cfg
+#ifdef BT_TUNING
+int g_gemm_cfg = -1;
+#endif
 
 bt_status gemm_dispatch(const bt_half* A, const bt_half* W, const bt_half* bias, int M, int N, int K, bt_act act,
                         bt_half* C, hipStream_t st) {
@@ -366,38 +377,45 @@ bt_status gemm_dispatch(const bt_half* A, const bt_half* W, const bt_half* bias,
   half_t* c = reinterpret_cast<half_t*>(C);
   if ((K % 64) != 0) return launch_simple(a, w, b, c, M, N, K, act, st);
   auto tiles = [&](int bm, int bn) { return (long long)((M + bm - 1) / bm) * ((N + bn - 1) / bn); };
-  int cfg = g_gemm_cfg;
-  // Tile choice.  A compute unit ingests operands at ~64 B/clk, so big tiles (more flops per byte
-  // staged) win as long as there are enough of them to occupy most of the 256 compute units.
-  if (cfg < 0) cfg = tiles(256, 128) >= 150 ? 11 : (tiles(128, 64) >= 150 ? 16 : 5);
-  switch (cfg) {
+#ifdef BT_TUNING
+  switch (g_gemm_cfg) {  // every tile shape the sweeps compared
     case 0: return launch_pipe<128, 128, 2, 2, 4>(a, w, b, c, M, N, K, act, st);
     case 1: return launch_pipe<128, 128, 2, 2, 2>(a, w, b, c, M, N, K, act, st);
     case 2: return launch_pipe<128, 128, 2, 2, 3>(a, w, b, c, M, N, K, act, st);
     case 3: return launch_pipe<128, 64, 2, 2, 4>(a, w, b, c, M, N, K, act, st);
     case 4: return launch_pipe<128, 64, 2, 2, 3>(a, w, b, c, M, N, K, act, st);
-    case 5: return launch_pipe<64, 64, 2, 2, 4>(a, w, b, c, M, N, K, act, st);
     case 6: return launch_pipe<256, 128, 2, 2, 3>(a, w, b, c, M, N, K, act, st);
     case 7: return launch_pipe<192, 128, 2, 2, 3>(a, w, b, c, M, N, K, act, st);
     case 8: return launch_pipe<192, 128, 2, 2, 4>(a, w, b, c, M, N, K, act, st);
     case 9: return launch_pipe<128, 192, 2, 2, 3>(a, w, b, c, M, N, K, act, st);
     case 10: return launch_pipe<192, 192, 2, 2, 3>(a, w, b, c, M, N, K, act, st);
-    case 11: return launch_pipe<256, 128, 4, 2, 3>(a, w, b, c, M, N, K, act, st);   // 8 waves, 64x64 each
     case 12: return launch_pipe<64, 128, 2, 2, 4>(a, w, b, c, M, N, K, act, st);
     case 13: return launch_pipe<192, 64, 2, 2, 4>(a, w, b, c, M, N, K, act, st);
-    case 14: return launch_pipe<128, 128, 4, 2, 4>(a, w, b, c, M, N, K, act, st);   // 8 waves, 32x64 each
-    case 15: return launch_pipe<256, 256, 4, 2, 2>(a, w, b, c, M, N, K, act, st);   // 8 waves, 64x128 each
-    case 16: return launch_pipe<128, 64, 4, 2, 4>(a, w, b, c, M, N, K, act, st);    // 8 waves, 32x32 each
-    case 17: return launch_pipe<256, 64, 4, 2, 4>(a, w, b, c, M, N, K, act, st);    // 8 waves, 64x32 each
-    case 18: return launch_pipe<256, 192, 4, 2, 2>(a, w, b, c, M, N, K, act, st);   // 8 waves, 64x96 each
-    default: return launch_simple(a, w, b, c, M, N, K, act, st);
+    case 14: return launch_pipe<128, 128, 4, 2, 4>(a, w, b, c, M, N, K, act, st);
+    case 15: return launch_pipe<256, 256, 4, 2, 2>(a, w, b, c, M, N, K, act, st);
+    case 17: return launch_pipe<256, 64, 4, 2, 4>(a, w, b, c, M, N, K, act, st);
+    case 18: return launch_pipe<256, 192, 4, 2, 2>(a, w, b, c, M, N, K, act, st);
+    case 5: return launch_pipe<64, 64, 2, 2, 4>(a, w, b, c, M, N, K, act, st);
+    case 11: return launch_pipe<256, 128, 4, 2, 3>(a, w, b, c, M, N, K, act, st);
+    case 16: return launch_pipe<128, 64, 4, 2, 4>(a, w, b, c, M, N, K, act, st);
+    case 99: return launch_simple(a, w, b, c, M, N, K, act, st);
+    default: break;
   }
+#endif
+  // Tile choice.  A compute unit ingests operands at ~50 B/clk, so big tiles (more flops per byte
+  // staged) win as long as there are enough of them to occupy most of the 256 compute units:
+  // 256x128 on 8 waves (64x64 each), else 128x64 on 8 waves (32x32 each), else 64x64 on 4 waves.
+  if (tiles(256, 128) >= 150) return launch_pipe<256, 128, 4, 2, 3>(a, w, b, c, M, N, K, act, st);
+  if (tiles(128, 64) >= 150) return launch_pipe<128, 64, 4, 2, 4>(a, w, b, c, M, N, K, act, st);
+  return launch_pipe<64, 64, 2, 2, 4>(a, w, b, c, M, N, K, act, st);
 }
 
 }  // namespace bt
 
+#ifdef BT_TUNING  // sweep hooks, only in builds made with BT_TUNING=1 (never in the shipped library)
 extern "C" void bt_debug_set_gemm_cfg(int cfg) { bt::g_gemm_cfg = cfg; }
 extern "C" void bt_debug_set_gemm_group_m(int g) { bt::g_gemm_group_m = g; }
+#endif
 
 extern "C" bt_status bt_gemm_bias_act(const bt_half* d_A, const bt_half* d_W, const bt_half* d_bias, int M, int N,
                                       int K, bt_act act, bt_half* d_C, bt_stream stream) {

@@ -143,16 +143,42 @@ __device__ __forceinline__ void process_tile(const half_t* sk, const half_t* sv,
   }
 }
 
-// Locate the (sequence, q-tile) a workgroup owns: prefix sum of per-sequence tile counts, 64
-// sequences at a time.  Results are wave-uniform (returned through readfirstlane).
-__device__ __forceinline__ bool locate_tile(const int32_t* __restrict__ cu, int B, int BQ, int qtile, int lane,
-                                            int& tok0, int& L, int& qt) {
+// Locate the (sequence, q-tile) a workgroup owns.  Results are wave-uniform (readfirstlane).
+// Up to 64 sequences: workgroups are ordered longest sequence first (by q-tile count, ties by index),
+// so the workgroups that walk the most key tiles start first and short ones fill the tail -- the
+// work list is never materialised, every wave derives its entry from cu_seqlens with ballots.
+// More than 64 sequences: plain sequence order, prefix sum of per-sequence tile counts, 64 at a time.
+__device__ __forceinline__ bool locate_tile(const int32_t* __restrict__ cu, int B, int BQ, int max_tiles, int qtile,
+                                            int lane, int& tok0, int& L, int& qt) {
+  if (B <= kWave) {
+    const int start = lane < B ? cu[lane] : 0;
+    const int len = lane < B ? cu[lane + 1] - start : 0;
+    const int nt = min((len + BQ - 1) / BQ, max_tiles);
+    const unsigned long long below = (1ull << lane) - 1ull;
+    int running = 0;
+    for (int v = max_tiles; v >= 1; --v) {
+      const unsigned long long grp = __ballot(nt == v);  // sequences with exactly v q-tiles
+      const int c = __popcll(grp);
+      if (qtile < running + c * v) {
+        const int idx = qtile - running;
+        const int j = idx / v;  // j-th sequence of the group, its q-tile idx % v
+        const unsigned long long me = __ballot(nt == v && __popcll(grp & below) == j);
+        const int src = __ffsll((long long)me) - 1;
+        tok0 = __builtin_amdgcn_readfirstlane(__shfl(start, src, kWave));
+        L = __builtin_amdgcn_readfirstlane(__shfl(len, src, kWave));
+        qt = idx - j * v;
+        return true;
+      }
+      running += c * v;
+    }
+    return false;
+  }
   int running = 0;
   for (int b0 = 0; b0 < B; b0 += kWave) {
     const int b = b0 + lane;
     const int start = b < B ? cu[b] : 0;
     const int len = b < B ? cu[b + 1] - start : 0;
-    const int nt = (len + BQ - 1) / BQ;
+    const int nt = min((len + BQ - 1) / BQ, max_tiles);
     int incl = nt;
 #pragma unroll
     for (int o = 1; o < kWave; o <<= 1) {
@@ -177,7 +203,7 @@ template <int NW, int NS>
 __global__ __launch_bounds__(NW * 64) void varlen_mha_kernel(
     const half_t* __restrict__ Q, const half_t* __restrict__ K, const half_t* __restrict__ V, int64_t row_stride,
     const half_t* __restrict__ bq, const half_t* __restrict__ bv, const int32_t* __restrict__ cu, int B, int heads,
-    float scale_log2e, half_t* __restrict__ out) {
+    int max_tiles, float scale_log2e, half_t* __restrict__ out) {
   constexpr int BQ = NW * 32;
   constexpr int TILE = kKT * kD;            // halves per K (or V) tile
   constexpr int PER = 8 / NW;               // DMA instructions per wave per operand tile (8 rows each)
@@ -194,7 +220,7 @@ __global__ __launch_bounds__(NW * 64) void varlen_mha_kernel(
   const int qtile = blockIdx.x / heads;
 
   int tok0 = 0, L = 0, qt = -1;
-  if (!locate_tile(cu, B, BQ, qtile, lane, tok0, L, qt)) return;  // same decision in every wave
+  if (!locate_tile(cu, B, BQ, max_tiles, qtile, lane, tok0, L, qt)) return;  // same decision in every wave
 
   const int q0 = qt * BQ;
   const int hofs = head * kD;
@@ -306,7 +332,7 @@ template <int NK, int NS>
 __global__ __launch_bounds__(NK * 64) void varlen_mha_splitkey_kernel(
     const half_t* __restrict__ Q, const half_t* __restrict__ K, const half_t* __restrict__ V, int64_t row_stride,
     const half_t* __restrict__ bq, const half_t* __restrict__ bv, const int32_t* __restrict__ cu, int B, int heads,
-    float scale_log2e, half_t* __restrict__ out) {
+    int max_tiles, float scale_log2e, half_t* __restrict__ out) {
   constexpr int BQ = 32;
   constexpr int TILE = kKT * kD;       // halves per K (or V) tile
   constexpr int WAVE_LDS = NS * 2 * TILE;  // halves per wave: NS x (K tile + V tile), >= 8 KB + 256 B for the merge
@@ -322,7 +348,7 @@ __global__ __launch_bounds__(NK * 64) void varlen_mha_splitkey_kernel(
   const int qtile = blockIdx.x / heads;
 
   int tok0 = 0, L = 0, qt = -1;
-  if (!locate_tile(cu, B, BQ, qtile, lane, tok0, L, qt)) return;  // same decision in every wave
+  if (!locate_tile(cu, B, BQ, max_tiles, qtile, lane, tok0, L, qt)) return;  // same decision in every wave
 
   const int q0 = qt * BQ;
   const int hofs = head * kD;
@@ -462,7 +488,7 @@ static bt_status launch_mha_splitkey(const half_t* q, const half_t* k, const hal
   const long long blocks = tiles * heads;
   if (blocks > 0x7fffffffLL) return BT_ERR_UNSUPPORTED;
   varlen_mha_splitkey_kernel<NK, NS><<<(unsigned)blocks, NK * 64, 0, st>>>(q, k, v, row_stride, bq, bv, cu, B, heads,
-                                                                         scale * 1.4426950408889634f, out);
+                                                                         (max_len + BQ - 1) / BQ, scale * 1.4426950408889634f, out);
   return launch_status();
 }
 
@@ -478,11 +504,13 @@ static bt_status launch_mha(const half_t* q, const half_t* k, const half_t* v, i
   const long long blocks = tiles * heads;
   if (blocks > 0x7fffffffLL) return BT_ERR_UNSUPPORTED;
   varlen_mha_kernel<NW, NS><<<(unsigned)blocks, NW * 64, 0, st>>>(q, k, v, row_stride, bq, bv, cu, B, heads,
-                                                                scale * 1.4426950408889634f, out);
+                                                                (max_len + BQ - 1) / BQ, scale * 1.4426950408889634f, out);
   return launch_status();
 }
 
-int g_mha_cfg = -1;  // tuning hook
+#ifdef BT_TUNING
+int g_mha_cfg = -1;
+#endif
 
 bt_status mha_dispatch(const bt_half* q, const bt_half* k, const bt_half* v, int64_t row_stride, const bt_half* bq,
                        const bt_half* bk, const bt_half* bv, const int32_t* cu, int B, int T, int max_len, int heads,
@@ -490,29 +518,37 @@ bt_status mha_dispatch(const bt_half* q, const bt_half* k, const bt_half* v, int
   (void)bk;  // adds the same constant to every logit of a row: cancels in the softmax
   auto h = [](const bt_half* p) { return reinterpret_cast<const half_t*>(p); };
   half_t* o = reinterpret_cast<half_t*>(out);
+#define BT_MHA_ARGS h(q), h(k), h(v), row_stride, h(bq), h(bv), cu, B, T, max_len, heads, scale, o, st
+#ifdef BT_TUNING
+  switch (g_mha_cfg) {
+    case 4: return launch_mha<4, 3>(BT_MHA_ARGS);
+    case 2: return launch_mha<2, 3>(BT_MHA_ARGS);
+    case 1: return launch_mha<1, 3>(BT_MHA_ARGS);
+    case 42: return launch_mha<4, 2>(BT_MHA_ARGS);
+    case 22: return launch_mha<2, 2>(BT_MHA_ARGS);
+    case 12: return launch_mha<1, 2>(BT_MHA_ARGS);
+    case 141: return launch_mha_splitkey<4, 1>(BT_MHA_ARGS);
+    case 142: return launch_mha_splitkey<4, 2>(BT_MHA_ARGS);
+    case 121: return launch_mha_splitkey<2, 1>(BT_MHA_ARGS);
+    case 122: return launch_mha_splitkey<2, 2>(BT_MHA_ARGS);
+    default: break;
+  }
+#endif
   // Kernel choice.  Tall query tiles (4 waves x 32 rows) re-read K/V least and suit long sequences;
   // 2-wave tiles give more workgroups; with too few of those to occupy the SIMDs, the split-key
   // kernel puts two waves on every 32 query rows.
   auto blocks = [&](int bqt) { return ((long long)T / bqt + B) * heads; };
-  int cfg = g_mha_cfg;
-  if (cfg < 0) cfg = (max_len > 128 && blocks(128) >= 512) ? 4 : (blocks(64) >= 512 ? 2 : 121);
-  switch (cfg) {
-    case 4: return launch_mha<4, 3>(h(q), h(k), h(v), row_stride, h(bq), h(bv), cu, B, T, max_len, heads, scale, o, st);
-    case 2: return launch_mha<2, 3>(h(q), h(k), h(v), row_stride, h(bq), h(bv), cu, B, T, max_len, heads, scale, o, st);
-    case 42: return launch_mha<4, 2>(h(q), h(k), h(v), row_stride, h(bq), h(bv), cu, B, T, max_len, heads, scale, o, st);
-    case 22: return launch_mha<2, 2>(h(q), h(k), h(v), row_stride, h(bq), h(bv), cu, B, T, max_len, heads, scale, o, st);
-    case 141: return launch_mha_splitkey<4, 1>(h(q), h(k), h(v), row_stride, h(bq), h(bv), cu, B, T, max_len, heads, scale, o, st);
-    case 142: return launch_mha_splitkey<4, 2>(h(q), h(k), h(v), row_stride, h(bq), h(bv), cu, B, T, max_len, heads, scale, o, st);
-    case 121: return launch_mha_splitkey<2, 1>(h(q), h(k), h(v), row_stride, h(bq), h(bv), cu, B, T, max_len, heads, scale, o, st);
-    case 122: return launch_mha_splitkey<2, 2>(h(q), h(k), h(v), row_stride, h(bq), h(bv), cu, B, T, max_len, heads, scale, o, st);
-    case 12: return launch_mha<1, 2>(h(q), h(k), h(v), row_stride, h(bq), h(bv), cu, B, T, max_len, heads, scale, o, st);
-    default: return launch_mha<1, 3>(h(q), h(k), h(v), row_stride, h(bq), h(bv), cu, B, T, max_len, heads, scale, o, st);
-  }
+  if (max_len > 128 && blocks(128) >= 512) return launch_mha<4, 3>(BT_MHA_ARGS);
+  if (blocks(64) >= 512) return launch_mha<2, 3>(BT_MHA_ARGS);
+  return launch_mha_splitkey<2, 1>(BT_MHA_ARGS);
+#undef BT_MHA_ARGS
 }
 
 }  // namespace bt
 
+#ifdef BT_TUNING  // sweep hook, only in builds made with BT_TUNING=1
 extern "C" void bt_debug_set_mha_cfg(int cfg) { bt::g_mha_cfg = cfg; }
+#endif
 
 extern "C" bt_status bt_varlen_mha(const bt_half* d_q, const bt_half* d_k, const bt_half* d_v, int64_t row_stride,
                                    const bt_half* d_bq, const bt_half* d_bk, const bt_half* d_bv,

@@ -163,6 +163,20 @@ def test_varlen_mha_shapes(bt, lengths, heads):
     assert _mha_case(bt, lengths, heads, seed=sum(lengths) + heads) <= 4e-3
 
 
+def test_varlen_mha_long_ragged_tall_tiles(bt):
+    """Enough long sequences for the 4-wave (128 query rows) kernel; ragged q and key tails,
+    lengths out of order so that the longest-first workgroup order is exercised."""
+    lengths = [512, 300, 1024, 77, 640, 129, 1000, 513, 256, 900, 64, 700]
+    assert _mha_case(bt, lengths, 12, seed=77) <= 4e-3
+
+
+def test_varlen_mha_many_sequences(bt):
+    """More than 64 sequences (plain sequence order path), two-wave kernel."""
+    rng = np.random.default_rng(5)
+    lengths = rng.integers(1, 200, 100).tolist()
+    assert _mha_case(bt, lengths, 6, seed=78) <= 4e-3
+
+
 def test_varlen_mha_bias_and_loose_max_len(bt):
     assert _mha_case(bt, [50, 3, 129], 4, seed=5, with_bias=True) <= 4e-3
     assert _mha_case(bt, [50, 3, 129], 4, seed=6, max_len=512) <= 4e-3
