@@ -50,6 +50,8 @@ def parse():
     ap.add_argument("--kernel-iters", type=int, default=200, help="launches per kernel for the roofline timing")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernels", action="store_true", help="skip the per-kernel timing pass")
+    ap.add_argument("--fold", action="store_true",
+                    help="LayerNorm folded into the GEMM epilogues (5 launches per layer) instead of the plain 7-launch layers")
     ap.add_argument("--calibrate-copy", action="store_true", help="also run one 1 GiB device copy (counter scaling)")
     return ap.parse_args()
 
@@ -101,6 +103,7 @@ def main():
     lengths_d = dev(L)
     params = [I.make_layer_params(wl, i) for i in range(nl)]
     layers = [bt.Layer(p) for p in params]
+    fold = bt.encoder_prepare(layers) if args.fold else None   # depends on the parameters only: not timed
     ws = torch.empty(bt.layer_workspace_bytes(layers[0], wl.B * wl.S, wl.B, wl.S), dtype=torch.uint8, device="cuda:0")
     x_packed = torch.empty((wl.B * wl.S, H), dtype=torch.float16, device="cuda:0")
     y_packed = torch.empty((wl.B * wl.S, H), dtype=torch.float16, device="cuda:0")
@@ -109,7 +112,7 @@ def main():
     def step():
         cu, tok, t = bt.build_offsets(lengths=lengths_d, S=wl.S)
         xp = bt.pack(x_padded, tok, out=x_packed[:t])
-        yp = bt.encoder_fwd(layers, xp, cu, wl.S, out=y_packed[:t], ws=ws)
+        yp = bt.encoder_fwd(layers, xp, cu, wl.S, out=y_packed[:t], ws=ws, fold=fold)
         bt.unpack(yp, tok, wl.B, wl.S, out=y_padded)
 
     for _ in range(args.warmup):
@@ -132,7 +135,7 @@ def main():
         "vs_baseline": None, "dtype": "f16", "data": "synthetic",
         "config": {"workload": args.workload, "batch": wl.B, "max_seq": wl.S, "hidden": H, "heads": wl.heads,
                    "ffn": F, "layers": nl, "length_law": wl.length_law, "valid_tokens": T, "sum_len_sq": sum_l2,
-                   "step": "build_offsets+pack+encoder_fwd+unpack"},
+                   "step": "build_offsets+pack+encoder_fwd+unpack", "layernorm_folded": fold is not None},
         "useful_tflops_per_s": round(flops_step / (ms_per_step * 1e-3) / 1e12, 2),
     }
 

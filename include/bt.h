@@ -162,13 +162,36 @@ bt_status bt_encoder_layer_fwd(const bt_layer* layer, const bt_half* d_x, const 
                                bt_stream stream);
 
 /*
+ * LayerNorm folding (optional, for bt_encoder_fwd).  A LayerNorm followed by a linear layer satisfies
+ *   LN(z) W^T + b = rstd (u W^T - mu c) + d,   u = gamma (.) z,  c = W gamma,  d = W beta + b,
+ * so the add-bias + residual + LayerNorm of Sec. III-C1 can live entirely in GEMM epilogues: the GEMM
+ * in front of the LayerNorm adds bias and residual, writes u and accumulates the row sums of z and
+ * z^2; the GEMM behind it applies mu, rstd, c and d.  The vectors c, d depend on the weights only;
+ * bt_encoder_prepare computes them once (fp32, on the device):
+ *   per layer  [ c_qkv (3H) | d_qkv (3H) | c_1 (F) | d_1 (F) ]
+ * where c_qkv/d_qkv of layer i use the second LayerNorm of layer i-1 (unused for layer 0).
+ * d_fold: device buffer of bt_encoder_fold_bytes() bytes, 16-byte aligned, owned by the caller; it must
+ * be recomputed when any weight, bias or LayerNorm parameter of the stack changes.
+ */
+size_t bt_encoder_fold_bytes(const bt_layer* layers, int n_layers);
+bt_status bt_encoder_prepare(const bt_layer* layers, int n_layers, float* d_fold, size_t fold_bytes,
+                             bt_stream stream);
+
+/*
  * A stack of n_layers encoder layers (Sec. IV-E): layer i+1 reads layer i's
  * output.  `layers` is a HOST array of n_layers descriptors with identical
- * H/heads/F.  The workspace (sized by bt_layer_workspace_bytes) also holds the
- * ping-pong buffer between layers; d_x is not modified; d_y receives the last
- * layer's output.
+ * H / heads / F / ln_eps.  The workspace (sized by bt_layer_workspace_bytes) also
+ * holds the ping-pong buffer between layers; d_x is not modified; d_y receives
+ * the last layer's output.
+ * d_fold == NULL: each layer runs as bt_encoder_layer_fwd does (7 launches per layer).
+ * d_fold from bt_encoder_prepare: the LayerNorms are folded into the GEMM epilogues
+ * (5 launches per layer plus one normalisation at the end); same function, the
+ * results differ from the unfolded path only by fp16 rounding.  The row sums are
+ * accumulated with floating-point atomics in no fixed order, so two folded runs on
+ * the same input may differ in the last fp16 bit; the unfolded path is bit-reproducible
+ * and, on the BERT shapes measured so far, just as fast: folding is opt-in.
  */
-bt_status bt_encoder_fwd(const bt_layer* layers, int n_layers, const bt_half* d_x,
+bt_status bt_encoder_fwd(const bt_layer* layers, int n_layers, const float* d_fold, const bt_half* d_x,
                          const int32_t* d_cu_seqlens, int B, int T, int max_len, bt_half* d_y,
                          void* d_ws, size_t ws_bytes, bt_stream stream);
 

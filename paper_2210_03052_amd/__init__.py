@@ -53,8 +53,10 @@ _SIGNATURES = {
     "bt_layer_workspace_bytes": (_c.c_size_t, [_c.POINTER(bt_layer), _c.c_int, _c.c_int, _c.c_int]),
     "bt_encoder_layer_fwd": (_c.c_int, [_c.POINTER(bt_layer), _c.c_void_p, _c.c_void_p, _c.c_int, _c.c_int,
                                         _c.c_int, _c.c_void_p, _c.c_void_p, _c.c_size_t, _c.c_void_p]),
-    "bt_encoder_fwd": (_c.c_int, [_c.POINTER(bt_layer), _c.c_int, _c.c_void_p, _c.c_void_p, _c.c_int, _c.c_int,
-                                  _c.c_int, _c.c_void_p, _c.c_void_p, _c.c_size_t, _c.c_void_p]),
+    "bt_encoder_fold_bytes": (_c.c_size_t, [_c.POINTER(bt_layer), _c.c_int]),
+    "bt_encoder_prepare": (_c.c_int, [_c.POINTER(bt_layer), _c.c_int, _c.c_void_p, _c.c_size_t, _c.c_void_p]),
+    "bt_encoder_fwd": (_c.c_int, [_c.POINTER(bt_layer), _c.c_int, _c.c_void_p, _c.c_void_p, _c.c_void_p, _c.c_int,
+                                  _c.c_int, _c.c_int, _c.c_void_p, _c.c_void_p, _c.c_size_t, _c.c_void_p]),
 }
 EXPORTED = tuple(_SIGNATURES)
 
@@ -267,17 +269,32 @@ def encoder_layer_fwd(layer: Layer, x, cu_seqlens, max_len, out=None, ws=None):
     return out
 
 
-def encoder_fwd(layers, x, cu_seqlens, max_len, out=None, ws=None):
-    """bt_encoder_fwd: the stack of layers on packed fp16 [T,H]."""
+def encoder_prepare(layers):
+    """bt_encoder_prepare: the fold vectors (fp32, device) that move every LayerNorm of the stack
+    into GEMM epilogues.  Depends on the parameters only: compute once, pass to encoder_fwd."""
+    torch = _torch()
+    lib = load_library()
+    arr = (bt_layer * len(layers))(*[l.desc for l in layers])
+    n = int(lib.bt_encoder_fold_bytes(arr, len(layers)))
+    fold = torch.empty(n // 4, dtype=torch.float32, device=layers[0].tensors["w_o"].device)
+    _call("bt_encoder_prepare", arr, len(layers), _ptr(fold), n, _stream())
+    return fold
+
+
+def encoder_fwd(layers, x, cu_seqlens, max_len, out=None, ws=None, fold=None):
+    """bt_encoder_fwd: the stack of layers on packed fp16 [T,H]; `fold` from encoder_prepare
+    selects the LayerNorm-folded pipeline."""
     torch = _torch()
     _chk(x, torch.float16, "x", 2)
     _chk(cu_seqlens, torch.int32, "cu_seqlens", 1)
+    if fold is not None:
+        _chk(fold, torch.float32, "fold", 1)
     T, B = x.shape[0], cu_seqlens.shape[0] - 1
     if out is None:
         out = torch.empty_like(x)
     if ws is None:
         ws, _ = _workspace(layers[0], T, B, max_len, x.device)
     arr = (bt_layer * len(layers))(*[l.desc for l in layers])
-    _call("bt_encoder_fwd", arr, len(layers), _ptr(x), _ptr(cu_seqlens), B, T, int(max_len), _ptr(out), _ptr(ws),
-          ws.numel(), _stream())
+    _call("bt_encoder_fwd", arr, len(layers), _ptr(fold), _ptr(x), _ptr(cu_seqlens), B, T, int(max_len), _ptr(out),
+          _ptr(ws), ws.numel(), _stream())
     return out

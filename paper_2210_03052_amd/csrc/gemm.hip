@@ -71,38 +71,118 @@ __device__ __forceinline__ void wait_vmcnt() {
 }
 
 // Shared epilogue.  acc[i][j][4g+t] = C[m][n] with m = m_base + i*32 + l32, n = n_base + j*32 + 8g + 4hf + t.
-// Bias and activation are applied to the fp32 accumulators; the fp16 tile of this wave is then
-// transposed through a private LDS region (rows padded to WN+8 halves) so that global memory is
-// written with 16-byte-per-lane stores, 8 lanes covering 128 contiguous bytes of an output row.
-template <int MI, int NI, int ACT>
-__device__ __forceinline__ void store_tile(const float16_t (&acc)[MI][NI], const half_t* __restrict__ bias,
-                                           half_t* __restrict__ C, int M, int N, int m_base, int n_base, int lane,
+// Three forms, all on the fp32 accumulators, one rounding to fp16:
+//   EPI_PLAIN  C = act(acc + bias)                                         (Sec. III-C2)
+//   EPI_FOLD   C = act(rstd_m (acc - mu_m c_n) + d_n): the A operand was u = gamma (.) z, the scaled
+//              but NOT yet normalised input of a LayerNorm; since LN(z) W^T = rstd (u W^T - mu c) + d
+//              with c = W gamma, d = W beta + bias, the normalisation moves into this epilogue and the
+//              LayerNorm kernel in front of the GEMM disappears.  mu, rstd come from per-row sums.
+//   EPI_RESID  v = acc + bias + residual, C = u = gamma_out (.) v, and the per-row sums of v and v^2
+//              are accumulated with atomics for the LayerNorm that follows (add-bias + residual of
+//              Sec. III-C1 fused here; the normalisation itself is folded into the next GEMM).  The
+//              residual is either a plain tensor or itself a folded LayerNorm output
+//              rstd (u_r - mu gamma_r) + beta_r.
+// The fp16 tile of this wave is then transposed through a private LDS region (rows padded to WN+8
+// halves) so that global memory is written with 16-byte-per-lane stores, 8 lanes covering 128
+// contiguous bytes of an output row.
+template <int MI, int NI, int ACT, int EPI>
+__device__ __forceinline__ void store_tile(const float16_t (&acc)[MI][NI], const GemmEpi& ep, half_t* __restrict__ C,
+                                           int M, int N, int m_base, int n_base, int lane,
                                            half_t* stage /* this wave's LDS region: MI*32 x (NI*32+8) halves */) {
   constexpr int WN = NI * 32, LD = WN + 8;
   const int l32 = lane & 31, hf = lane >> 5;
+  // per-row LayerNorm statistics of the A operand (FOLD) / of the residual source (RESID)
+  float mu[MI], rstd[MI], s0[MI], s1[MI];
+  const float* row_stats = EPI == EPI_FOLD ? ep.ln_stats : (EPI == EPI_RESID ? ep.resid_stats : nullptr);
+#pragma unroll
+  for (int i = 0; i < MI; ++i) {
+    mu[i] = 0.f; rstd[i] = 1.f; s0[i] = 0.f; s1[i] = 0.f;
+    const int m = m_base + i * 32 + l32;
+    if (EPI != EPI_PLAIN && row_stats && m < M) {
+      const float2 st = *reinterpret_cast<const float2*>(row_stats + 2 * (size_t)m);
+      mu[i] = st.x * ep.inv_h;
+      rstd[i] = rsqrtf(fmaxf(st.y * ep.inv_h - mu[i] * mu[i], 0.f) + ep.eps);
+    }
+  }
 #pragma unroll
   for (int j = 0; j < NI; ++j) {
 #pragma unroll
     for (int g = 0; g < 4; ++g) {
       const int nl = j * 32 + 8 * g + 4 * hf;
       const int n = n_base + nl;
-      float bv[4] = {0.f, 0.f, 0.f, 0.f};
-      if (bias && n < N) {  // N % 8 == 0: the 4 columns are all in or all out
-        const half4_t b4 = *reinterpret_cast<const half4_t*>(bias + n);
+      const bool n_ok = n < N;  // N % 8 == 0: the 4 columns are all in or all out
+      float bv[4] = {0.f, 0.f, 0.f, 0.f}, cv[4] = {0.f, 0.f, 0.f, 0.f};
+      float rg[4] = {0.f, 0.f, 0.f, 0.f}, rb[4] = {0.f, 0.f, 0.f, 0.f}, og[4] = {1.f, 1.f, 1.f, 1.f};
+      if (n_ok) {
+        if (EPI == EPI_FOLD) {
+          const float4_t c4 = *reinterpret_cast<const float4_t*>(ep.fold_c + n);
+          const float4_t d4 = *reinterpret_cast<const float4_t*>(ep.fold_d + n);
 #pragma unroll
-        for (int t = 0; t < 4; ++t) bv[t] = (float)b4[t];
+          for (int t = 0; t < 4; ++t) { cv[t] = c4[t]; bv[t] = d4[t]; }
+        } else if (ep.bias) {
+          const half4_t b4 = *reinterpret_cast<const half4_t*>(ep.bias + n);
+#pragma unroll
+          for (int t = 0; t < 4; ++t) bv[t] = (float)b4[t];
+        }
+        if (EPI == EPI_RESID) {
+          const half4_t g4 = *reinterpret_cast<const half4_t*>(ep.out_gamma + n);
+#pragma unroll
+          for (int t = 0; t < 4; ++t) og[t] = (float)g4[t];
+          if (ep.resid_stats) {
+            const half4_t a4 = *reinterpret_cast<const half4_t*>(ep.resid_gamma + n);
+            const half4_t b4 = *reinterpret_cast<const half4_t*>(ep.resid_beta + n);
+#pragma unroll
+            for (int t = 0; t < 4; ++t) { rg[t] = (float)a4[t]; rb[t] = (float)b4[t]; }
+          }
+        }
       }
 #pragma unroll
       for (int i = 0; i < MI; ++i) {
+        const int m = m_base + i * 32 + l32;
+        float v[4];
+#pragma unroll
+        for (int t = 0; t < 4; ++t) v[t] = acc[i][j][4 * g + t];
+        if (EPI == EPI_FOLD) {
+#pragma unroll
+          for (int t = 0; t < 4; ++t) v[t] = __builtin_fmaf(rstd[i], v[t] - mu[i] * cv[t], bv[t]);
+        } else {
+#pragma unroll
+          for (int t = 0; t < 4; ++t) v[t] += bv[t];
+        }
+        if (EPI == EPI_RESID) {
+          if (n_ok && m < M) {
+            const half4_t r4 = *reinterpret_cast<const half4_t*>(ep.resid + (size_t)m * N + n);
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+              const float r = ep.resid_stats ? __builtin_fmaf(rstd[i], (float)r4[t] - mu[i] * rg[t], rb[t]) : (float)r4[t];
+              v[t] += r;
+              s0[i] += v[t];
+              s1[i] = __builtin_fmaf(v[t], v[t], s1[i]);
+              v[t] *= og[t];
+            }
+          }
+        } else {
+#pragma unroll
+          for (int t = 0; t < 4; ++t) {
+            if (ACT == BT_ACT_GELU_ERF) v[t] = gelu_erf(v[t]);
+            else if (ACT == BT_ACT_GELU_TANH) v[t] = gelu_tanh(v[t]);
+          }
+        }
         half4_t o;
 #pragma unroll
-        for (int t = 0; t < 4; ++t) {
-          float v = acc[i][j][4 * g + t] + bv[t];
-          if (ACT == BT_ACT_GELU_ERF) v = gelu_erf(v);
-          else if (ACT == BT_ACT_GELU_TANH) v = gelu_tanh(v);
-          o[t] = (half_t)v;
-        }
+        for (int t = 0; t < 4; ++t) o[t] = (half_t)v[t];
         *reinterpret_cast<half4_t*>(stage + (i * 32 + l32) * LD + nl) = o;
+      }
+    }
+  }
+  if (EPI == EPI_RESID) {
+#pragma unroll
+    for (int i = 0; i < MI; ++i) {  // the two 32-lane halves hold the two column halves of the same row
+      const float t0 = s0[i] + __shfl_xor(s0[i], 32, kWave), t1 = s1[i] + __shfl_xor(s1[i], 32, kWave);
+      const int m = m_base + i * 32 + l32;
+      if (hf == 0 && m < M) {
+        atomicAdd(ep.stats_out + 2 * (size_t)m, t0);
+        atomicAdd(ep.stats_out + 2 * (size_t)m + 1, t1);
       }
     }
   }
@@ -117,13 +197,21 @@ __device__ __forceinline__ void store_tile(const float16_t (&acc)[MI][NI], const
   }
 }
 
+// Rows [m0, m0+rows) of a per-row statistics buffer are cleared by the workgroups of tile column 0,
+// ahead of the later kernel that accumulates into it (saves a fill kernel per LayerNorm).
+__device__ __forceinline__ void clear_stats(float* stats, int m0, int rows, int M, int tid) {
+  if (stats && tid < rows && m0 + tid < M) {
+    stats[2 * (size_t)(m0 + tid)] = 0.f;
+    stats[2 * (size_t)(m0 + tid) + 1] = 0.f;
+  }
+}
+
 // ---------------------------------------------------------------------------
 // Pipelined kernel: direct-to-LDS slabs, NS stages, WGM x WGN wavefronts.
 // ---------------------------------------------------------------------------
-template <int BM, int BN, int WGM, int WGN, int NS, int ACT>
+template <int BM, int BN, int WGM, int WGN, int NS, int ACT, int EPI>
 __global__ __launch_bounds__(WGM* WGN * 64) void gemm_pipe_kernel(const half_t* __restrict__ A,
-                                                                  const half_t* __restrict__ W,
-                                                                  const half_t* __restrict__ bias,
+                                                                  const half_t* __restrict__ W, const GemmEpi ep,
                                                                   half_t* __restrict__ C, int M, int N, int K,
                                                                   int tiles_n, int n_tiles, int group_m) {
   constexpr int BK = 64, KS = BK / 16;
@@ -161,6 +249,7 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_pipe_kernel(const half_t* 
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform: LDS DMA bases live in M0
   const int wm = wave / WGN, wn = wave % WGN;
   const int l32 = lane & 31, hf = lane >> 5;
+  if (tn == 0) clear_stats(ep.zero_stats, m0, BM, M, tid);
 
   // DMA source pointers.  Instruction q of this wave fills LDS rows [r0, r0+8) of the slab; lane i
   // lands at row r0 + i/8, physical chunk i%8, and therefore fetches logical chunk
@@ -268,16 +357,15 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_pipe_kernel(const half_t* 
     stage = nstage;
   }
   __builtin_amdgcn_s_barrier();  // every wave is done reading the last slab: LDS becomes staging space
-  store_tile<MI, NI, ACT>(acc, bias, C, M, N, m0 + wm * WM, n0 + wn * WN, lane, smem + wave * STAGE_HALVES);
+  store_tile<MI, NI, ACT, EPI>(acc, ep, C, M, N, m0 + wm * WM, n0 + wn * WN, lane, smem + wave * STAGE_HALVES);
 }
 
 // ---------------------------------------------------------------------------
 // Fallback kernel: register-staged, 64x64x64 tile, padded LDS rows, K tail zero-filled.
 // ---------------------------------------------------------------------------
-template <int ACT>
+template <int ACT, int EPI>
 __global__ __launch_bounds__(kGemmThreads) void gemm_simple_kernel(const half_t* __restrict__ A,
-                                                                   const half_t* __restrict__ W,
-                                                                   const half_t* __restrict__ bias,
+                                                                   const half_t* __restrict__ W, const GemmEpi ep,
                                                                    half_t* __restrict__ C, int M, int N, int K,
                                                                    int tiles_n) {
   constexpr int BM = 64, BN = 64, BK = 64, LDS = BK + 8, CH = BM * (BK / 8) / kGemmThreads;
@@ -288,6 +376,7 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_simple_kernel(const half_t*
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave >> 1, wn = wave & 1, l32 = lane & 31, hf = lane >> 5;
   const int kc = (tid & 7) * 8;
+  if (tn == 0) clear_stats(ep.zero_stats, m0, BM, M, tid);
   float16_t acc[1][1];
 #pragma unroll
   for (int r = 0; r < 16; ++r) acc[0][0][r] = 0.f;
@@ -317,16 +406,18 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_simple_kernel(const half_t*
     }
   }
   __syncthreads();  // operand tiles are dead: reuse them as per-wave staging space (32 x 40 halves each)
-  store_tile<1, 1, ACT>(acc, bias, C, M, N, m0 + wm * 32, n0 + wn * 32, lane, (wave < 2 ? sA : sB) + (wave & 1) * 32 * 40);
+  store_tile<1, 1, ACT, EPI>(acc, ep, C, M, N, m0 + wm * 32, n0 + wn * 32, lane, (wave < 2 ? sA : sB) + (wave & 1) * 32 * 40);
 }
 
 #ifdef BT_TUNING
 int g_gemm_group_m = 0;
+int g_gemm_cfg = -1;
 #endif
 
+// act x epilogue combinations that exist: PLAIN and FOLD with any activation, RESID without one.
 template <int BM, int BN, int WGM, int WGN, int NS>
-static bt_status launch_pipe(const half_t* A, const half_t* W, const half_t* bias, half_t* C, int M, int N, int K,
-                             bt_act act, hipStream_t st) {
+static bt_status launch_pipe(const half_t* A, const half_t* W, half_t* C, int M, int N, int K, bt_act act, int epi,
+                             const GemmEpi& ep, hipStream_t st) {
   const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
   const long long n_tiles = (long long)tiles_m * tiles_n;
   if (n_tiles > 0x7fffffffLL) return BT_ERR_UNSUPPORTED;
@@ -337,77 +428,80 @@ static bt_status launch_pipe(const half_t* A, const half_t* W, const half_t* bia
   if (g_gemm_group_m > 0) group_m = g_gemm_group_m;
 #endif
   group_m = group_m < 1 ? 1 : (group_m > tiles_m ? tiles_m : group_m);
-  switch (act) {
-    case BT_ACT_NONE:
-      gemm_pipe_kernel<BM, BN, WGM, WGN, NS, BT_ACT_NONE><<<grid, block, 0, st>>>(A, W, bias, C, M, N, K, tiles_n, (int)n_tiles, group_m);
-      break;
-    case BT_ACT_GELU_ERF:
-      gemm_pipe_kernel<BM, BN, WGM, WGN, NS, BT_ACT_GELU_ERF><<<grid, block, 0, st>>>(A, W, bias, C, M, N, K, tiles_n, (int)n_tiles, group_m);
-      break;
-    default:
-      gemm_pipe_kernel<BM, BN, WGM, WGN, NS, BT_ACT_GELU_TANH><<<grid, block, 0, st>>>(A, W, bias, C, M, N, K, tiles_n, (int)n_tiles, group_m);
-      break;
+#define BT_LAUNCH(ACT, EPI) \
+  gemm_pipe_kernel<BM, BN, WGM, WGN, NS, ACT, EPI><<<grid, block, 0, st>>>(A, W, ep, C, M, N, K, tiles_n, (int)n_tiles, group_m)
+  if (epi == EPI_RESID) {
+    BT_LAUNCH(BT_ACT_NONE, EPI_RESID);
+  } else if (epi == EPI_FOLD) {
+    if (act == BT_ACT_NONE) BT_LAUNCH(BT_ACT_NONE, EPI_FOLD);
+    else if (act == BT_ACT_GELU_ERF) BT_LAUNCH(BT_ACT_GELU_ERF, EPI_FOLD);
+    else BT_LAUNCH(BT_ACT_GELU_TANH, EPI_FOLD);
+  } else {
+    if (act == BT_ACT_NONE) BT_LAUNCH(BT_ACT_NONE, EPI_PLAIN);
+    else if (act == BT_ACT_GELU_ERF) BT_LAUNCH(BT_ACT_GELU_ERF, EPI_PLAIN);
+    else BT_LAUNCH(BT_ACT_GELU_TANH, EPI_PLAIN);
   }
+#undef BT_LAUNCH
   return launch_status();
 }
 
-static bt_status launch_simple(const half_t* A, const half_t* W, const half_t* bias, half_t* C, int M, int N, int K,
-                               bt_act act, hipStream_t st) {
+static bt_status launch_simple(const half_t* A, const half_t* W, half_t* C, int M, int N, int K, bt_act act, int epi,
+                               const GemmEpi& ep, hipStream_t st) {
   const int tiles_n = (N + 63) / 64;
   const long long n_tiles = (long long)((M + 63) / 64) * tiles_n;
   if (n_tiles > 0x7fffffffLL) return BT_ERR_UNSUPPORTED;
   dim3 grid((unsigned)n_tiles), block(kGemmThreads);
-  switch (act) {
-    case BT_ACT_NONE: gemm_simple_kernel<BT_ACT_NONE><<<grid, block, 0, st>>>(A, W, bias, C, M, N, K, tiles_n); break;
-    case BT_ACT_GELU_ERF: gemm_simple_kernel<BT_ACT_GELU_ERF><<<grid, block, 0, st>>>(A, W, bias, C, M, N, K, tiles_n); break;
-    default: gemm_simple_kernel<BT_ACT_GELU_TANH><<<grid, block, 0, st>>>(A, W, bias, C, M, N, K, tiles_n); break;
+#define BT_LAUNCH(ACT, EPI) gemm_simple_kernel<ACT, EPI><<<grid, block, 0, st>>>(A, W, ep, C, M, N, K, tiles_n)
+  if (epi == EPI_RESID) {
+    BT_LAUNCH(BT_ACT_NONE, EPI_RESID);
+  } else if (epi == EPI_FOLD) {
+    if (act == BT_ACT_NONE) BT_LAUNCH(BT_ACT_NONE, EPI_FOLD);
+    else if (act == BT_ACT_GELU_ERF) BT_LAUNCH(BT_ACT_GELU_ERF, EPI_FOLD);
+    else BT_LAUNCH(BT_ACT_GELU_TANH, EPI_FOLD);
+  } else {
+    if (act == BT_ACT_NONE) BT_LAUNCH(BT_ACT_NONE, EPI_PLAIN);
+    else if (act == BT_ACT_GELU_ERF) BT_LAUNCH(BT_ACT_GELU_ERF, EPI_PLAIN);
+    else BT_LAUNCH(BT_ACT_GELU_TANH, EPI_PLAIN);
   }
+#undef BT_LAUNCH
   return launch_status();
 }
 
-#ifdef BT_TUNING
-int g_gemm_cfg = -1;
-#endif
-
-bt_status gemm_dispatch(const bt_half* A, const bt_half* W, const bt_half* bias, int M, int N, int K, bt_act act,
-                        bt_half* C, hipStream_t st) {
+bt_status gemm_dispatch(const bt_half* A, const bt_half* W, int M, int N, int K, bt_act act, int epi,
+                        const GemmEpi& ep, bt_half* C, hipStream_t st) {
   const half_t* a = reinterpret_cast<const half_t*>(A);
   const half_t* w = reinterpret_cast<const half_t*>(W);
-  const half_t* b = reinterpret_cast<const half_t*>(bias);
   half_t* c = reinterpret_cast<half_t*>(C);
-  if ((K % 64) != 0) return launch_simple(a, w, b, c, M, N, K, act, st);
+  if (epi == EPI_RESID && act != BT_ACT_NONE) return BT_ERR_INVALID_ARG;
+  if ((K % 64) != 0) return launch_simple(a, w, c, M, N, K, act, epi, ep, st);
   auto tiles = [&](int bm, int bn) { return (long long)((M + bm - 1) / bm) * ((N + bn - 1) / bn); };
+#define BT_PIPE(BM, BN, WGM, WGN, NS) launch_pipe<BM, BN, WGM, WGN, NS>(a, w, c, M, N, K, act, epi, ep, st)
 #ifdef BT_TUNING
-  switch (g_gemm_cfg) {  // every tile shape the sweeps compared
-    case 0: return launch_pipe<128, 128, 2, 2, 4>(a, w, b, c, M, N, K, act, st);
-    case 1: return launch_pipe<128, 128, 2, 2, 2>(a, w, b, c, M, N, K, act, st);
-    case 2: return launch_pipe<128, 128, 2, 2, 3>(a, w, b, c, M, N, K, act, st);
-    case 3: return launch_pipe<128, 64, 2, 2, 4>(a, w, b, c, M, N, K, act, st);
-    case 4: return launch_pipe<128, 64, 2, 2, 3>(a, w, b, c, M, N, K, act, st);
-    case 6: return launch_pipe<256, 128, 2, 2, 3>(a, w, b, c, M, N, K, act, st);
-    case 7: return launch_pipe<192, 128, 2, 2, 3>(a, w, b, c, M, N, K, act, st);
-    case 8: return launch_pipe<192, 128, 2, 2, 4>(a, w, b, c, M, N, K, act, st);
-    case 9: return launch_pipe<128, 192, 2, 2, 3>(a, w, b, c, M, N, K, act, st);
-    case 10: return launch_pipe<192, 192, 2, 2, 3>(a, w, b, c, M, N, K, act, st);
-    case 12: return launch_pipe<64, 128, 2, 2, 4>(a, w, b, c, M, N, K, act, st);
-    case 13: return launch_pipe<192, 64, 2, 2, 4>(a, w, b, c, M, N, K, act, st);
-    case 14: return launch_pipe<128, 128, 4, 2, 4>(a, w, b, c, M, N, K, act, st);
-    case 15: return launch_pipe<256, 256, 4, 2, 2>(a, w, b, c, M, N, K, act, st);
-    case 17: return launch_pipe<256, 64, 4, 2, 4>(a, w, b, c, M, N, K, act, st);
-    case 18: return launch_pipe<256, 192, 4, 2, 2>(a, w, b, c, M, N, K, act, st);
-    case 5: return launch_pipe<64, 64, 2, 2, 4>(a, w, b, c, M, N, K, act, st);
-    case 11: return launch_pipe<256, 128, 4, 2, 3>(a, w, b, c, M, N, K, act, st);
-    case 16: return launch_pipe<128, 64, 4, 2, 4>(a, w, b, c, M, N, K, act, st);
-    case 99: return launch_simple(a, w, b, c, M, N, K, act, st);
+  switch (g_gemm_cfg) {  // tile shapes the sweeps compared
+    case 0: return BT_PIPE(128, 128, 2, 2, 4);
+    case 1: return BT_PIPE(128, 128, 2, 2, 2);
+    case 2: return BT_PIPE(128, 128, 2, 2, 3);
+    case 3: return BT_PIPE(128, 64, 2, 2, 4);
+    case 6: return BT_PIPE(256, 128, 2, 2, 3);
+    case 7: return BT_PIPE(192, 128, 2, 2, 3);
+    case 14: return BT_PIPE(128, 128, 4, 2, 4);
+    case 15: return BT_PIPE(256, 256, 4, 2, 2);
+    case 17: return BT_PIPE(256, 64, 4, 2, 4);
+    case 18: return BT_PIPE(256, 192, 4, 2, 2);
+    case 5: return BT_PIPE(64, 64, 2, 2, 4);
+    case 11: return BT_PIPE(256, 128, 4, 2, 3);
+    case 16: return BT_PIPE(128, 64, 4, 2, 4);
+    case 99: return launch_simple(a, w, c, M, N, K, act, epi, ep, st);
     default: break;
   }
 #endif
   // Tile choice.  A compute unit ingests operands at ~50 B/clk, so big tiles (more flops per byte
   // staged) win as long as there are enough of them to occupy most of the 256 compute units:
   // 256x128 on 8 waves (64x64 each), else 128x64 on 8 waves (32x32 each), else 64x64 on 4 waves.
-  if (tiles(256, 128) >= 150) return launch_pipe<256, 128, 4, 2, 3>(a, w, b, c, M, N, K, act, st);
-  if (tiles(128, 64) >= 150) return launch_pipe<128, 64, 4, 2, 4>(a, w, b, c, M, N, K, act, st);
-  return launch_pipe<64, 64, 2, 2, 4>(a, w, b, c, M, N, K, act, st);
+  if (tiles(256, 128) >= 150) return BT_PIPE(256, 128, 4, 2, 3);
+  if (tiles(128, 64) >= 150) return BT_PIPE(128, 64, 4, 2, 4);
+  return BT_PIPE(64, 64, 2, 2, 4);
+#undef BT_PIPE
 }
 
 }  // namespace bt
@@ -425,5 +519,7 @@ extern "C" bt_status bt_gemm_bias_act(const bt_half* d_A, const bt_half* d_W, co
   if (!d_A || !d_W || !d_C || !bt::aligned16(d_A) || !bt::aligned16(d_W) || !bt::aligned16(d_C))
     return BT_ERR_INVALID_ARG;
   if (d_bias && (reinterpret_cast<uintptr_t>(d_bias) & 7u)) return BT_ERR_INVALID_ARG;
-  return bt::gemm_dispatch(d_A, d_W, d_bias, M, N, K, act, d_C, static_cast<hipStream_t>(stream));
+  bt::GemmEpi ep;
+  ep.bias = reinterpret_cast<const bt::half_t*>(d_bias);
+  return bt::gemm_dispatch(d_A, d_W, M, N, K, act, bt::EPI_PLAIN, ep, d_C, static_cast<hipStream_t>(stream));
 }

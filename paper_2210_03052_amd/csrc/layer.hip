@@ -1,47 +1,69 @@
 // Padding-free encoder layer (Fig. 2(c)) and the stack of layers (Sec. IV-E):
 // a host-side sequence of launches on the caller's stream, no synchronisation.
+//
+// Plain pipeline (7 launches per layer):
 //   GEMM0 (+bias) -> varlen MHA -> GEMM1 -> bias+residual+LN
 //   -> GEMM2 (+bias, GELU in the epilogue) -> GEMM3 -> bias+residual+LN
+//
+// Folded pipeline (bt_encoder_fwd with fold vectors, 5 launches per layer): the add-bias + residual
+// of Sec. III-C1 moves into the epilogue of GEMM1 / GEMM3, which also accumulates the row sums of
+// the LayerNorm input and writes u = gamma (.) z; the normalisation itself moves into the epilogue
+// of the GEMM that consumes the LayerNorm output (GEMM2, next layer's GEMM0) through
+//   LN(z) W^T + b = rstd (u W^T - mu c) + d,   c = W gamma,  d = W beta + b,
+// and the residual branches rebuild LN(z) = rstd (u - mu gamma) + beta on the fly.  One explicit
+// normalisation remains, at the end of the stack.
 #include "common.h"
 
 namespace bt {
-bt_status gemm_dispatch(const bt_half* A, const bt_half* W, const bt_half* bias, int M, int N, int K, bt_act act,
-                        bt_half* C, hipStream_t st);
+bt_status gemm_dispatch(const bt_half* A, const bt_half* W, int M, int N, int K, bt_act act, int epi,
+                        const GemmEpi& ep, bt_half* C, hipStream_t st);
 bt_status layernorm_dispatch(const bt_half* x, const bt_half* bias, const bt_half* residual, const bt_half* gamma,
                              const bt_half* beta, float eps, int T, int H, bt_half* y, hipStream_t st);
+bt_status ln_finalize_dispatch(const bt_half* u, const float* stats, const bt_half* gamma, const bt_half* beta,
+                               float eps, int T, int H, bt_half* y, hipStream_t st);
+bt_status fold_vectors_dispatch(const bt_half* W, const bt_half* gamma, const bt_half* beta, const bt_half* bias,
+                                int N, int K, float* c, float* d, hipStream_t st);
 bt_status mha_dispatch(const bt_half* q, const bt_half* k, const bt_half* v, int64_t row_stride, const bt_half* bq,
                        const bt_half* bk, const bt_half* bv, const int32_t* cu, int B, int T, int max_len, int heads,
                        float scale, bt_half* out, hipStream_t st);
 
 static inline size_t align256(size_t n) { return (n + 255) & ~(size_t)255; }
+static inline const half_t* hp(const bt_half* p) { return reinterpret_cast<const half_t*>(p); }
 
 // Workspace layout for T tokens (every region 256-byte aligned):
-//   qkv [T,3H] | attn [T,H] | proj [T,H] (GEMM1 and GEMM3 output) | y1 [T,H] | g [T,F] | ping [T,H] | pong [T,H]
+//   qkv [T,3H] | attn [T,H] | proj [T,H] (GEMM1 and GEMM3 output) | y1 [T,H] | g [T,F] | ping [T,H] |
+//   pong [T,H] | stats1 [T,2] fp32 | stats2 [T,2] fp32
 struct Workspace {
   bt_half *qkv, *attn, *proj, *y1, *g, *ping, *pong;
+  float *stats1, *stats2;
   size_t bytes;
 };
 
 static Workspace carve(void* ws, int T, int H, int F) {
   Workspace w;
-  char* p = static_cast<char*>(ws);
+  uintptr_t base = reinterpret_cast<uintptr_t>(ws);
   size_t off = 0;
-  auto take = [&](size_t halves) {
-    bt_half* r = reinterpret_cast<bt_half*>(p + off);
-    off += align256(halves * sizeof(bt_half));
+  auto take = [&](size_t bytes) {
+    void* r = reinterpret_cast<void*>(base + off);
+    off += align256(bytes);
     return r;
   };
   const size_t t = (size_t)T;
-  w.qkv = take(t * 3 * H);
-  w.attn = take(t * H);
-  w.proj = take(t * H);
-  w.y1 = take(t * H);
-  w.g = take(t * F);
-  w.ping = take(t * H);
-  w.pong = take(t * H);
+  w.qkv = static_cast<bt_half*>(take(t * 3 * H * 2));
+  w.attn = static_cast<bt_half*>(take(t * H * 2));
+  w.proj = static_cast<bt_half*>(take(t * H * 2));
+  w.y1 = static_cast<bt_half*>(take(t * H * 2));
+  w.g = static_cast<bt_half*>(take(t * F * 2));
+  w.ping = static_cast<bt_half*>(take(t * H * 2));
+  w.pong = static_cast<bt_half*>(take(t * H * 2));
+  w.stats1 = static_cast<float*>(take(t * 2 * sizeof(float)));
+  w.stats2 = static_cast<float*>(take(t * 2 * sizeof(float)));
   w.bytes = off;
   return w;
 }
+
+// Fold vectors of one layer: [c_qkv (3H) | d_qkv (3H) | c_1 (F) | d_1 (F)] fp32.
+static inline size_t fold_floats(int H, int F) { return (size_t)6 * H + (size_t)2 * F; }
 
 static bt_status check_layer(const bt_layer* l) {
   if (!l) return BT_ERR_INVALID_ARG;
@@ -56,21 +78,98 @@ static bt_status check_layer(const bt_layer* l) {
   return BT_OK;
 }
 
+static bt_status check_stack(const bt_layer* layers, int n_layers) {
+  if (!layers || n_layers < 1) return BT_ERR_INVALID_ARG;
+  for (int i = 0; i < n_layers; ++i) {
+    bt_status s = check_layer(&layers[i]);
+    if (s != BT_OK) return s;
+    if (layers[i].H != layers[0].H || layers[i].F != layers[0].F || layers[i].heads != layers[0].heads ||
+        layers[i].ln_eps != layers[0].ln_eps)
+      return BT_ERR_INVALID_ARG;
+  }
+  return BT_OK;
+}
+
 static bt_status layer_fwd(const bt_layer* l, const bt_half* x, const int32_t* cu, int B, int T, int max_len,
                            bt_half* y, const Workspace& w, hipStream_t st) {
   const int H = l->H, F = l->F;
   bt_status s;
-  if ((s = gemm_dispatch(x, l->w_qkv, l->b_qkv, T, 3 * H, H, BT_ACT_NONE, w.qkv, st)) != BT_OK) return s;
+  GemmEpi ep;
+  ep.bias = hp(l->b_qkv);
+  if ((s = gemm_dispatch(x, l->w_qkv, T, 3 * H, H, BT_ACT_NONE, EPI_PLAIN, ep, w.qkv, st)) != BT_OK) return s;
   const float scale = 1.0f / sqrtf((float)l->head_dim);
   if ((s = mha_dispatch(w.qkv, w.qkv + H, w.qkv + 2 * H, 3 * (int64_t)H, nullptr, nullptr, nullptr, cu, B, T,
                         max_len, l->heads, scale, w.attn, st)) != BT_OK)
     return s;
-  if ((s = gemm_dispatch(w.attn, l->w_o, nullptr, T, H, H, BT_ACT_NONE, w.proj, st)) != BT_OK) return s;
+  ep.bias = nullptr;
+  if ((s = gemm_dispatch(w.attn, l->w_o, T, H, H, BT_ACT_NONE, EPI_PLAIN, ep, w.proj, st)) != BT_OK) return s;
   if ((s = layernorm_dispatch(w.proj, l->b_o, x, l->ln0_g, l->ln0_b, l->ln_eps, T, H, w.y1, st)) != BT_OK) return s;
   const bt_act act = l->gelu_kind == 0 ? BT_ACT_GELU_ERF : BT_ACT_GELU_TANH;
-  if ((s = gemm_dispatch(w.y1, l->w_1, l->b_1, T, F, H, act, w.g, st)) != BT_OK) return s;
-  if ((s = gemm_dispatch(w.g, l->w_2, nullptr, T, H, F, BT_ACT_NONE, w.proj, st)) != BT_OK) return s;
+  ep.bias = hp(l->b_1);
+  if ((s = gemm_dispatch(w.y1, l->w_1, T, F, H, act, EPI_PLAIN, ep, w.g, st)) != BT_OK) return s;
+  ep.bias = nullptr;
+  if ((s = gemm_dispatch(w.g, l->w_2, T, H, F, BT_ACT_NONE, EPI_PLAIN, ep, w.proj, st)) != BT_OK) return s;
   return layernorm_dispatch(w.proj, l->b_2, w.y1, l->ln1_g, l->ln1_b, l->ln_eps, T, H, y, st);
+}
+
+// Folded stack.  Between layers the activation lives as (u2 = gamma1 (.) z2, stats2); inside a layer
+// as (u1 = gamma0 (.) z1, stats1).  stats1 is cleared by GEMM0's tile column 0 (its last reader was
+// the previous layer's GEMM3), stats2 by GEMM2's (last readers: this layer's GEMM0 and GEMM1).
+static bt_status stack_fwd_folded(const bt_layer* layers, int n_layers, const float* fold, const bt_half* x,
+                                  const int32_t* cu, int B, int T, int max_len, bt_half* y, const Workspace& w,
+                                  hipStream_t st) {
+  const int H = layers[0].H, F = layers[0].F;
+  const float inv_h = 1.0f / (float)H, eps = layers[0].ln_eps;
+  const float scale = 1.0f / sqrtf((float)layers[0].head_dim);
+  const size_t per_layer = fold_floats(H, F);
+  bt_status s;
+  const bt_half* in = x;  // layer input: plain x for layer 0, u2 of the previous layer afterwards
+  for (int i = 0; i < n_layers; ++i) {
+    const bt_layer* l = &layers[i];
+    const bt_layer* prev = i > 0 ? &layers[i - 1] : nullptr;
+    const float* fv = fold + (size_t)i * per_layer;
+    bt_half* u2 = (i & 1) ? w.pong : w.ping;
+    {  // GEMM0: QKV projection of LN1_{i-1}(z2) (folded) or of the plain input
+      GemmEpi ep;
+      ep.zero_stats = w.stats1;
+      if (prev) {
+        ep.ln_stats = w.stats2; ep.fold_c = fv; ep.fold_d = fv + 3 * H; ep.inv_h = inv_h; ep.eps = eps;
+      } else {
+        ep.bias = hp(l->b_qkv);
+      }
+      if ((s = gemm_dispatch(in, l->w_qkv, T, 3 * H, H, BT_ACT_NONE, prev ? EPI_FOLD : EPI_PLAIN, ep, w.qkv, st)) !=
+          BT_OK)
+        return s;
+    }
+    if ((s = mha_dispatch(w.qkv, w.qkv + H, w.qkv + 2 * H, 3 * (int64_t)H, nullptr, nullptr, nullptr, cu, B, T,
+                          max_len, l->heads, scale, w.attn, st)) != BT_OK)
+      return s;
+    {  // GEMM1: z1 = attn W_o^T + b_o + layer input;  u1 = gamma0 (.) z1, stats1 += sums of z1
+      GemmEpi ep;
+      ep.bias = hp(l->b_o); ep.inv_h = inv_h; ep.eps = eps;
+      ep.resid = hp(in);
+      if (prev) { ep.resid_stats = w.stats2; ep.resid_gamma = hp(prev->ln1_g); ep.resid_beta = hp(prev->ln1_b); }
+      ep.out_gamma = hp(l->ln0_g); ep.stats_out = w.stats1;
+      if ((s = gemm_dispatch(w.attn, l->w_o, T, H, H, BT_ACT_NONE, EPI_RESID, ep, w.y1, st)) != BT_OK) return s;
+    }
+    {  // GEMM2: GELU(LN0(z1) W_1^T + b_1), LayerNorm folded
+      GemmEpi ep;
+      ep.zero_stats = w.stats2;
+      ep.ln_stats = w.stats1; ep.fold_c = fv + 6 * H; ep.fold_d = fv + 6 * H + F; ep.inv_h = inv_h; ep.eps = eps;
+      const bt_act act = l->gelu_kind == 0 ? BT_ACT_GELU_ERF : BT_ACT_GELU_TANH;
+      if ((s = gemm_dispatch(w.y1, l->w_1, T, F, H, act, EPI_FOLD, ep, w.g, st)) != BT_OK) return s;
+    }
+    {  // GEMM3: z2 = g W_2^T + b_2 + LN0(z1);  u2 = gamma1 (.) z2, stats2 += sums of z2
+      GemmEpi ep;
+      ep.bias = hp(l->b_2); ep.inv_h = inv_h; ep.eps = eps;
+      ep.resid = hp(w.y1); ep.resid_stats = w.stats1; ep.resid_gamma = hp(l->ln0_g); ep.resid_beta = hp(l->ln0_b);
+      ep.out_gamma = hp(l->ln1_g); ep.stats_out = w.stats2;
+      if ((s = gemm_dispatch(w.g, l->w_2, T, H, F, BT_ACT_NONE, EPI_RESID, ep, u2, st)) != BT_OK) return s;
+    }
+    in = u2;
+  }
+  const bt_layer* last = &layers[n_layers - 1];
+  return ln_finalize_dispatch(in, w.stats2, last->ln1_g, last->ln1_b, eps, T, H, y, st);
 }
 
 static bt_status check_io(const bt_half* x, const int32_t* cu, int B, int T, int max_len, bt_half* y, void* ws) {
@@ -116,21 +215,46 @@ extern "C" bt_status bt_encoder_layer_fwd(const bt_layer* layer, const bt_half* 
   return layer_fwd(layer, d_x, d_cu_seqlens, B, T, max_len, d_y, w, static_cast<hipStream_t>(stream));
 }
 
-extern "C" bt_status bt_encoder_fwd(const bt_layer* layers, int n_layers, const bt_half* d_x,
+extern "C" size_t bt_encoder_fold_bytes(const bt_layer* layers, int n_layers) {
+  if (!layers || n_layers < 1 || layers[0].H < 1 || layers[0].F < 1) return 0;
+  return (size_t)n_layers * fold_floats(layers[0].H, layers[0].F) * sizeof(float);
+}
+
+extern "C" bt_status bt_encoder_prepare(const bt_layer* layers, int n_layers, float* d_fold, size_t fold_bytes,
+                                        bt_stream stream) {
+  bt_status s = check_stack(layers, n_layers);
+  if (s != BT_OK) return s;
+  if (!d_fold || (reinterpret_cast<uintptr_t>(d_fold) & 15u)) return BT_ERR_INVALID_ARG;
+  if (fold_bytes < bt_encoder_fold_bytes(layers, n_layers)) return BT_ERR_WORKSPACE;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  const int H = layers[0].H, F = layers[0].F;
+  const size_t per_layer = fold_floats(H, F);
+  for (int i = 0; i < n_layers; ++i) {
+    float* fv = d_fold + (size_t)i * per_layer;
+    const bt_layer* l = &layers[i];
+    if (i > 0) {  // layer 0 reads a plain input: its c_qkv / d_qkv stay unused
+      const bt_layer* p = &layers[i - 1];
+      if ((s = fold_vectors_dispatch(l->w_qkv, p->ln1_g, p->ln1_b, l->b_qkv, 3 * H, H, fv, fv + 3 * H, st)) != BT_OK)
+        return s;
+    }
+    if ((s = fold_vectors_dispatch(l->w_1, l->ln0_g, l->ln0_b, l->b_1, F, H, fv + 6 * H, fv + 6 * H + F, st)) != BT_OK)
+      return s;
+  }
+  return BT_OK;
+}
+
+extern "C" bt_status bt_encoder_fwd(const bt_layer* layers, int n_layers, const float* d_fold, const bt_half* d_x,
                                     const int32_t* d_cu_seqlens, int B, int T, int max_len, bt_half* d_y, void* d_ws,
                                     size_t ws_bytes, bt_stream stream) {
-  if (!layers || n_layers < 1) return BT_ERR_INVALID_ARG;
-  bt_status s;
-  for (int i = 0; i < n_layers; ++i) {
-    if ((s = check_layer(&layers[i])) != BT_OK) return s;
-    if (layers[i].H != layers[0].H || layers[i].F != layers[0].F || layers[i].heads != layers[0].heads)
-      return BT_ERR_INVALID_ARG;
-  }
+  bt_status s = check_stack(layers, n_layers);
+  if (s != BT_OK) return s;
   if ((s = check_io(d_x, d_cu_seqlens, B, T, max_len, d_y, d_ws)) != BT_OK) return s;
+  if (d_fold && (reinterpret_cast<uintptr_t>(d_fold) & 15u)) return BT_ERR_INVALID_ARG;
   if (B == 0 || T == 0) return BT_OK;
   const Workspace w = carve(d_ws, T, layers[0].H, layers[0].F);
   if (ws_bytes < w.bytes) return BT_ERR_WORKSPACE;
   hipStream_t st = static_cast<hipStream_t>(stream);
+  if (d_fold) return stack_fwd_folded(layers, n_layers, d_fold, d_x, d_cu_seqlens, B, T, max_len, d_y, w, st);
   const bt_half* in = d_x;
   for (int i = 0; i < n_layers; ++i) {
     bt_half* outp = (i == n_layers - 1) ? d_y : ((i & 1) ? w.pong : w.ping);

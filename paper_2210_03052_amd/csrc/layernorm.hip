@@ -70,6 +70,78 @@ __global__ __launch_bounds__(256) void bias_residual_ln_kernel(const half_t* x,
   }
 }
 
+// Normalisation of a row whose scaled values u = gamma (.) z and sums (sum z, sum z^2) were produced by
+// a GEMM epilogue (EPI_RESID): y = rstd (u - mu gamma) + beta.  Used once, at the end of a stack whose
+// inner LayerNorms are folded into the GEMMs that follow them.
+__global__ __launch_bounds__(256) void ln_finalize_kernel(const half_t* __restrict__ u, const float* __restrict__ stats,
+                                                          const half_t* __restrict__ gamma,
+                                                          const half_t* __restrict__ beta, float eps, int T, int H,
+                                                          half_t* __restrict__ y) {
+  const int lane = threadIdx.x & 63;
+  const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (row >= T) return;
+  const float inv_h = 1.0f / (float)H;
+  const float mu = stats[2 * (size_t)row] * inv_h;
+  const float rstd = rsqrtf(fmaxf(stats[2 * (size_t)row + 1] * inv_h - mu * mu, 0.f) + eps);
+  const size_t base = (size_t)row * H;
+  for (int c = lane; c < (H >> 3); c += kWave) {
+    const half8_t a = *reinterpret_cast<const half8_t*>(u + base + c * 8);
+    const half8_t g = *reinterpret_cast<const half8_t*>(gamma + c * 8);
+    const half8_t b = *reinterpret_cast<const half8_t*>(beta + c * 8);
+    half8_t o;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) o[e] = (half_t)(rstd * ((float)a[e] - mu * (float)g[e]) + (float)b[e]);
+    *reinterpret_cast<half8_t*>(y + base + c * 8) = o;
+  }
+}
+
+// c[n] = sum_k W[n][k] gamma[k],  d[n] = sum_k W[n][k] beta[k] + bias[n]: the two vectors that move a
+// LayerNorm (gamma, beta) into the epilogue of the GEMM with weight W.  One wavefront per output n.
+__global__ __launch_bounds__(256) void fold_vectors_kernel(const half_t* __restrict__ W,
+                                                           const half_t* __restrict__ gamma,
+                                                           const half_t* __restrict__ beta,
+                                                           const half_t* __restrict__ bias, int N, int K,
+                                                           float* __restrict__ c, float* __restrict__ d) {
+  const int lane = threadIdx.x & 63;
+  const int n = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (n >= N) return;
+  float sc = 0.f, sd = 0.f;
+  for (int k = lane * 8; k < K; k += kWave * 8) {
+    const half8_t w = *reinterpret_cast<const half8_t*>(W + (size_t)n * K + k);
+    const half8_t g = *reinterpret_cast<const half8_t*>(gamma + k);
+    const half8_t b = *reinterpret_cast<const half8_t*>(beta + k);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      sc = __builtin_fmaf((float)w[e], (float)g[e], sc);
+      sd = __builtin_fmaf((float)w[e], (float)b[e], sd);
+    }
+  }
+  sc = wave_sum(sc);
+  sd = wave_sum(sd);
+  if (lane == 0) {
+    c[n] = sc;
+    d[n] = sd + (bias ? (float)bias[n] : 0.f);
+  }
+}
+
+bt_status ln_finalize_dispatch(const bt_half* u, const float* stats, const bt_half* gamma, const bt_half* beta,
+                               float eps, int T, int H, bt_half* y, hipStream_t st) {
+  ln_finalize_kernel<<<(T + 3) / 4, 256, 0, st>>>(reinterpret_cast<const half_t*>(u), stats,
+                                                  reinterpret_cast<const half_t*>(gamma),
+                                                  reinterpret_cast<const half_t*>(beta), eps, T, H,
+                                                  reinterpret_cast<half_t*>(y));
+  return launch_status();
+}
+
+bt_status fold_vectors_dispatch(const bt_half* W, const bt_half* gamma, const bt_half* beta, const bt_half* bias,
+                                int N, int K, float* c, float* d, hipStream_t st) {
+  fold_vectors_kernel<<<(N + 3) / 4, 256, 0, st>>>(reinterpret_cast<const half_t*>(W),
+                                                   reinterpret_cast<const half_t*>(gamma),
+                                                   reinterpret_cast<const half_t*>(beta),
+                                                   reinterpret_cast<const half_t*>(bias), N, K, c, d);
+  return launch_status();
+}
+
 bt_status layernorm_dispatch(const bt_half* x, const bt_half* bias, const bt_half* residual, const bt_half* gamma,
                              const bt_half* beta, float eps, int T, int H, bt_half* y, hipStream_t st) {
   const half_t* px = reinterpret_cast<const half_t*>(x);

@@ -77,8 +77,8 @@ def test_layer_checks(lib):
     one = 256
     good = bt.bt_layer(768, 12, 64, 3072, 1e-12, 0, *[one] * 12)
     n = lib.bt_layer_workspace_bytes(ctypes.byref(good), 100, 4, 64)
-    # qkv + attn + proj + y1 + g + ping + pong, each 256-byte aligned
-    assert n >= 2 * 100 * (3 * 768 + 5 * 768 + 3072) and n % 256 == 0
+    # qkv + attn + proj + y1 + g + ping + pong + two per-row statistics buffers, each 256-byte aligned
+    assert n >= 2 * 100 * (3 * 768 + 5 * 768 + 3072) + 2 * 100 * 8 and n % 256 == 0
     assert lib.bt_layer_workspace_bytes(ctypes.byref(good), 0, 4, 64) == 0
     x, y, cu, ws = ctypes.c_void_p(256), ctypes.c_void_p(512), ctypes.c_void_p(768), ctypes.c_void_p(1024)
     call = lambda L, T=100, ws_=ws, nbytes=n, y_=y: lib.bt_encoder_layer_fwd(
@@ -93,8 +93,15 @@ def test_layer_checks(lib):
     assert call(bt.bt_layer(768, 12, 64, 3072, 1e-12, 5, *[one] * 12)) == 1      # gelu kind
     assert call(bt.bt_layer(768, 12, 64, 3072, 1e-12, 0, *([one] * 11 + [0]))) == 1  # null parameter
     arr = (bt.bt_layer * 2)(good, bt.bt_layer(1024, 16, 64, 4096, 1e-12, 0, *[one] * 12))
-    assert lib.bt_encoder_fwd(arr, 2, x, cu, 4, 100, 64, y, ws, n, None) == 1  # mixed shapes
-    assert lib.bt_encoder_fwd(arr, 0, x, cu, 4, 100, 64, y, ws, n, None) == 1
+    assert lib.bt_encoder_fwd(arr, 2, None, x, cu, 4, 100, 64, y, ws, n, None) == 1  # mixed shapes
+    assert lib.bt_encoder_fwd(arr, 0, None, x, cu, 4, 100, 64, y, ws, n, None) == 1
+    same = (bt.bt_layer * 2)(good, good)
+    fb = lib.bt_encoder_fold_bytes(same, 2)
+    assert fb == 2 * (6 * 768 + 2 * 3072) * 4
+    assert lib.bt_encoder_prepare(same, 2, None, fb, None) == 1            # null fold buffer
+    assert lib.bt_encoder_prepare(same, 2, ctypes.c_void_p(256), fb - 4, None) == 3   # too small
+    assert lib.bt_encoder_prepare(arr, 2, ctypes.c_void_p(256), fb, None) == 1        # mixed shapes
+    assert lib.bt_encoder_fwd(same, 2, ctypes.c_void_p(4), x, cu, 4, 100, 64, y, ws, n, None) == 1  # misaligned fold
 
 
 def test_no_fallback_when_library_missing(tmp_path):

@@ -295,18 +295,20 @@ def test_stack_bert_base_b16_s256(bt):
     assert err <= TOL_12, err
 
 
-def _sampled_stack(bt, name, tol_mid, tol_end):
+def _sampled_stack(bt, name, tol_mid, tol_end, folded):
     wl = I.WORKLOADS[name]
     layers, L, x, cu = _run_stack(bt, wl, wl.layers)
+    fold = bt.encoder_prepare(layers) if folded else None
     order = np.argsort(L)
     seqs = sorted({int(order[0]), int(order[len(order) // 2]), int(order[-1])})
-    full = host(bt.encoder_fwd(layers, dev(x), cu, wl.S)).astype(np.float64)
+    full = host(bt.encoder_fwd(layers, dev(x), cu, wl.S, fold=fold)).astype(np.float64)
     ow = oracle_layers(wl, wl.layers)
     ref, cuh = _oracle_on(wl, L, x, ow, seqs)
     err = max(np.abs(full[cuh[b]: cuh[b + 1]] - ref[i]).max() for i, b in enumerate(seqs))
     assert err <= tol_end, err
     if wl.layers > 12:
-        mid = host(bt.encoder_fwd(layers[:12], dev(x), cu, wl.S)).astype(np.float64)
+        fold12 = bt.encoder_prepare(layers[:12]) if folded else None
+        mid = host(bt.encoder_fwd(layers[:12], dev(x), cu, wl.S, fold=fold12)).astype(np.float64)
         refm, _ = _oracle_on(wl, L, x, ow[:12], seqs)
         errm = max(np.abs(mid[cuh[b]: cuh[b + 1]] - refm[i]).max() for i, b in enumerate(seqs))
         assert errm <= tol_mid, errm
@@ -314,12 +316,62 @@ def _sampled_stack(bt, name, tol_mid, tol_end):
     assert np.abs(full.mean(axis=1)).max() < 5e-3 and np.abs(full.var(axis=1) - 1).max() < 2e-2
 
 
-def test_stack_bert_base_b16_s1024_sampled(bt):
+@pytest.mark.parametrize("folded", [False, True])
+def test_stack_bert_base_b16_s1024_sampled(bt, folded):
     """12 layers, batch 16, max 1024: shortest / median / longest sequence through
     the fp64 oracle (sequences are independent), plus a property on all rows."""
-    _sampled_stack(bt, "bert_base_b16_s1024", TOL_12, TOL_12)
+    _sampled_stack(bt, "bert_base_b16_s1024", TOL_12, TOL_12, folded)
 
 
-def test_stack_bert_large_b32_s512_sampled(bt):
+@pytest.mark.parametrize("folded", [False, True])
+def test_stack_bert_large_b32_s512_sampled(bt, folded):
     """24 layers of the large shape, skewed lengths: 5e-2 at layer 12, 1e-1 at 24."""
-    _sampled_stack(bt, "bert_large_b32_s512", TOL_12, TOL_24)
+    _sampled_stack(bt, "bert_large_b32_s512", TOL_12, TOL_24, folded)
+
+
+# ------------------------------------------------------------------ LayerNorm folded into the GEMM epilogues
+def test_fold_vectors(bt):
+    """bt_encoder_prepare: c = W gamma, d = W beta + bias (fp32), per layer [c_qkv|d_qkv|c_1|d_1]."""
+    wl = I.WORKLOADS["layer_b4_s64"]
+    params = [I.make_layer_params(wl, i, stress=True) for i in range(3)]
+    layers = [bt.Layer(p) for p in params]
+    fold = host(bt.encoder_prepare(layers)).astype(np.float64).reshape(3, -1)
+    H, F = wl.H, wl.F
+    f64 = lambda a: a.astype(np.float64)
+    for i, p in enumerate(params):
+        c1 = f64(p["w_1"]) @ f64(p["ln0_g"]); d1 = f64(p["w_1"]) @ f64(p["ln0_b"]) + f64(p["b_1"])
+        assert np.abs(fold[i, 6 * H: 6 * H + F] - c1).max() < 1e-4
+        assert np.abs(fold[i, 6 * H + F: 6 * H + 2 * F] - d1).max() < 1e-4
+        if i > 0:
+            q = params[i - 1]
+            cq = f64(p["w_qkv"]) @ f64(q["ln1_g"]); dq = f64(p["w_qkv"]) @ f64(q["ln1_b"]) + f64(p["b_qkv"])
+            assert np.abs(fold[i, : 3 * H] - cq).max() < 1e-4
+            assert np.abs(fold[i, 3 * H: 6 * H] - dq).max() < 1e-4
+
+
+@pytest.mark.parametrize("name,n_layers,stress", [("layer_b4_s64", 1, True), ("layer_b4_s64", 3, True),
+                                                  ("bert_base_b16_s256", 12, False),
+                                                  ("bert_base_b16_s256", 12, True)])
+def test_folded_stack_vs_oracle(bt, name, n_layers, stress):
+    """The LayerNorm-folded pipeline against the oracle on every sequence, and against the plain
+    pipeline (same function, different fp16 rounding points)."""
+    wl = I.WORKLOADS[name]
+    layers, L, x, cu = _run_stack(bt, wl, n_layers, stress)
+    fold = bt.encoder_prepare(layers)
+    got = host(bt.encoder_fwd(layers, dev(x), cu, wl.S, fold=fold)).astype(np.float64)
+    plain = host(bt.encoder_fwd(layers, dev(x), cu, wl.S)).astype(np.float64)
+    seqs = list(range(wl.B))
+    ref, cuh = _oracle_on(wl, L, x, oracle_layers(wl, n_layers, stress), seqs)
+    err = max(np.abs(got[cuh[b]: cuh[b + 1]] - ref[b]).max() for b in seqs)
+    tol = TOL_LAYER if n_layers == 1 else TOL_12
+    assert err <= tol, err
+    assert np.abs(got - plain).max() <= tol
+    # running it again on the same workspace works (the row sums are re-zeroed inside the pipeline); the
+    # sums are accumulated with floating-point atomics in no fixed order, so two runs may differ by fp16
+    # roundings, which later layers carry along: the two runs are held to the bar each meets on its own
+    import torch
+    ws = torch.empty(bt.layer_workspace_bytes(layers[0], x.shape[0], wl.B, wl.S), dtype=torch.uint8, device="cuda:0")
+    a = host(bt.encoder_fwd(layers, dev(x), cu, wl.S, fold=fold, ws=ws)).astype(np.float64)
+    b = host(bt.encoder_fwd(layers, dev(x), cu, wl.S, fold=fold, ws=ws)).astype(np.float64)
+    assert np.abs(a - b).max() <= tol
+    assert max(np.abs(b[cuh[i]: cuh[i + 1]] - ref[i]).max() for i in seqs) <= tol
