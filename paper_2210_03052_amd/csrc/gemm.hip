@@ -70,6 +70,15 @@ __device__ __forceinline__ void wait_vmcnt() {
   __builtin_amdgcn_s_waitcnt((N & 15) | ((N >> 4) << 14) | (7 << 4) | (15 << 8));
 }
 
+// Calls f(integral_constant<int, 0>) ... f(integral_constant<int, N-1>).
+template <int N, int I = 0, class F>
+__device__ __forceinline__ void static_for(F&& f) {
+  if constexpr (I < N) {
+    f(std::integral_constant<int, I>{});
+    static_for<N, I + 1>(f);
+  }
+}
+
 // Shared epilogue.  acc[i][j][4g+t] = C[m][n] with m = m_base + i*32 + l32, n = n_base + j*32 + 8g + 4hf + t.
 // Three forms, all on the fp32 accumulators, one rounding to fp16:
 //   EPI_PLAIN  C = act(acc + bias)                                         (Sec. III-C2)
@@ -284,26 +293,39 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_pipe_kernel(const half_t* 
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-  const int nk = K / BK;
+  // Slab schedule.  Slab kt lives in stage (kt - pre) mod NS, with pre = (nk - (NS-1)) mod NS, so that
+  // the nk slabs split into `pre` leading slabs (stage known at run time only), a steady state of
+  // whole rounds of NS slabs whose stages are compile-time constants, and the last NS-1 slabs, which
+  // fetch nothing.  In the steady state and the tail every LDS offset is an immediate, every DMA
+  // target a constant and every wait count exact: no branches, no address arithmetic in the loop.
+  const int nk = K / BK;  // >= NS - 1 (checked by the launcher)
+  const int pre = (nk - (NS - 1)) % NS;
+  const int rounds = (nk - (NS - 1) - pre) / NS;
+  {
+    int st = pre == 0 ? 0 : NS - pre;
 #pragma unroll
-  for (int s = 0; s < NS - 1; ++s)
-    if (s < nk) {
+    for (int s = 0; s < NS - 1; ++s) {
 #pragma unroll
-      for (int q = 0; q < TOT; ++q) issue_one(q, s, s);
+      for (int q = 0; q < TOT; ++q) issue_one(q, s, st);
+      st = st + 1 == NS ? 0 : st + 1;
     }
+  }
 
   // operand read offsets (halves): row*BK + ((2ks+hf) ^ swz(row))*8 ; swz depends on l32 only
   const int swz = (l32 >> 1) & (CPR - 1);
-  const int a_row = (wm * WM + l32) * BK, b_row = (wn * WN + l32) * BK;
+  const half_t* const pa0 = sA + (wm * WM + l32) * BK;
+  const half_t* const pb0 = sB + (wn * WN + l32) * BK;
+  int co[KS];
+#pragma unroll
+  for (int ks = 0; ks < KS; ++ks) co[ks] = ((2 * ks + hf) ^ swz) * 8;
   half8_t fa[2][MI], fb[2][NI];
-  auto read_frags = [&](int stage, int ks, int slot) {
-    const int co = ((2 * ks + hf) ^ swz) * 8;
-    const half_t* pa = sA + stage * (BM * BK) + a_row + co;
-    const half_t* pb = sB + stage * (BN * BK) + b_row + co;
+  auto read_frags = [&](auto stage, int ks, int slot) {
 #pragma unroll
-    for (int i = 0; i < MI; ++i) fa[slot][i] = *reinterpret_cast<const half8_t*>(pa + i * 32 * BK);
+    for (int i = 0; i < MI; ++i)
+      fa[slot][i] = *reinterpret_cast<const half8_t*>(pa0 + co[ks] + stage * (BM * BK) + i * 32 * BK);
 #pragma unroll
-    for (int j = 0; j < NI; ++j) fb[slot][j] = *reinterpret_cast<const half8_t*>(pb + j * 32 * BK);
+    for (int j = 0; j < NI; ++j)
+      fb[slot][j] = *reinterpret_cast<const half8_t*>(pb0 + co[ks] + stage * (BN * BK) + j * 32 * BK);
   };
   auto mfmas = [&](int slot) {
 #pragma unroll
@@ -313,49 +335,58 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_pipe_kernel(const half_t* 
         // transposed product: D[n][m] += W[n][k] * A[m][k]
         acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fb[slot][j], fa[slot][i], acc[i][j], 0, 0, 0);
   };
-  // Wait until this wave's share of slab kt has landed (at most min(nk-1-kt, NS-2) younger slabs of
-  // TOT instructions each may stay in flight), then publish it to the block.  The barrier also
-  // tells everyone that slab kt-1 is no longer being read, so its stage may be refilled.
-  auto acquire = [&](int kt) {
-    const int younger = min(nk - 1 - kt, NS - 2);
-    if (NS >= 4 && younger >= 2) wait_vmcnt<(NS >= 4 ? 2 : 0) * TOT>();
-    else if (NS >= 3 && younger == 1) wait_vmcnt<(NS >= 3 ? 1 : 0) * TOT>();
-    else wait_vmcnt<0>();
-    __builtin_amdgcn_s_barrier();
-  };
-
-  // Software pipeline.  The fragments of k-step ks+1 are read from LDS while the MFMAs of k-step ks
-  // run; the hand-over to the next slab (acquire + its first fragment read) sits in front of the
-  // last k-step's MFMAs, so neither the LDS latency nor the DMA issue is exposed at a slab boundary.
-  // The DMA instructions for slab kt+NS-1 are spread over the first KS-1 k-steps: a burst would
-  // stall the wave behind its own address FIFO.
-  acquire(0);
-  read_frags(0, 0, 0);
-  int stage = 0;
-  for (int kt = 0; kt < nk; ++kt) {
-    const bool fetch = kt + NS - 1 < nk;
-    const int fstage = stage == 0 ? NS - 1 : stage - 1;  // (kt + NS - 1) % NS
+  // One slab.  The fragments of k-step ks+1 are read from LDS while the MFMAs of k-step ks run; the
+  // DMA instructions for slab kt+NS-1 (FETCH) are spread over the first KS-1 k-steps into the stage
+  // that the previous hand-over freed.  The hand-over to the next slab sits in front of the last
+  // k-step's MFMAs: every fragment of this slab is in registers (lgkmcnt 0), this wave's share of
+  // the next slab has landed (at most YOUNGER later slabs of TOT instructions stay in flight), and
+  // the barrier publishes both facts, so the next slab may be read and this stage refilled.
+  auto slab = [&](int kt, auto stage, auto fetch_c, auto last_c, auto younger_c) {
+    constexpr bool FETCH = decltype(fetch_c)::value, LAST = decltype(last_c)::value;
+    constexpr int YOUNGER = decltype(younger_c)::value;
+    const auto fstage = (stage + (NS - 1)) % NS, nstage = (stage + 1) % NS;
 #pragma unroll
     for (int ks = 0; ks < KS - 1; ++ks) {
       read_frags(stage, ks + 1, (ks + 1) & 1);
-      if (fetch) {
+      if (FETCH) {
 #pragma unroll
         for (int q = ks * TOT / (KS - 1); q < (ks + 1) * TOT / (KS - 1); ++q) issue_one(q, kt + NS - 1, fstage);
       }
       mfmas(ks & 1);
       __builtin_amdgcn_sched_barrier(0);
     }
-    const int nstage = stage + 1 == NS ? 0 : stage + 1;
-    if (kt + 1 < nk) {
-      // all of this wave's reads of slab kt are in registers before anyone may refill its stage
-      asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-      acquire(kt + 1);
+    if (!LAST) {
+      __builtin_amdgcn_s_waitcnt(0xc07f);  // lgkmcnt(0), other counters untouched
+      wait_vmcnt<YOUNGER * TOT>();
+      __builtin_amdgcn_s_barrier();
       read_frags(nstage, 0, 0);
     }
     mfmas((KS - 1) & 1);
     __builtin_amdgcn_sched_barrier(0);
-    stage = nstage;
+  };
+  using std::integral_constant;
+  using yes = std::true_type;
+  using no = std::false_type;
+
+  wait_vmcnt<(NS - 2) * TOT>();  // slab 0 has landed
+  __builtin_amdgcn_s_barrier();
+  int kt = 0;
+  {
+    int st = pre == 0 ? 0 : NS - pre;
+    read_frags(st, 0, 0);
+    for (; kt < pre; ++kt) {  // leading slabs: run-time stage
+      slab(kt, st, yes{}, no{}, integral_constant<int, NS - 2>{});
+      st = st + 1 == NS ? 0 : st + 1;
+    }
   }
+  for (int r = 0; r < rounds; ++r) {  // steady state: compile-time stages
+    static_for<NS>([&](auto s) { slab(kt + decltype(s)::value, s, yes{}, no{}, integral_constant<int, NS - 2>{}); });
+    kt += NS;
+  }
+  static_for<NS - 1>([&](auto j) {  // last NS-1 slabs: everything is already in flight
+    constexpr int J = decltype(j)::value;
+    slab(kt + J, j, no{}, integral_constant<bool, J == NS - 2>{}, integral_constant<int, (NS - 3 - J > 0 ? NS - 3 - J : 0)>{});
+  });
   __builtin_amdgcn_s_barrier();  // every wave is done reading the last slab: LDS becomes staging space
   store_tile<MI, NI, ACT, EPI>(acc, ep, C, M, N, m0 + wm * WM, n0 + wn * WN, lane, smem + wave * STAGE_HALVES);
 }
@@ -415,9 +446,13 @@ int g_gemm_cfg = -1;
 #endif
 
 // act x epilogue combinations that exist: PLAIN and FOLD with any activation, RESID without one.
+static bt_status launch_simple(const half_t* A, const half_t* W, half_t* C, int M, int N, int K, bt_act act, int epi,
+                               const GemmEpi& ep, hipStream_t st);
+
 template <int BM, int BN, int WGM, int WGN, int NS>
 static bt_status launch_pipe(const half_t* A, const half_t* W, half_t* C, int M, int N, int K, bt_act act, int epi,
                              const GemmEpi& ep, hipStream_t st) {
+  if (K / 64 < NS - 1) return launch_simple(A, W, C, M, N, K, act, epi, ep, st);  // pipeline deeper than K
   const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
   const long long n_tiles = (long long)tiles_m * tiles_n;
   if (n_tiles > 0x7fffffffLL) return BT_ERR_UNSUPPORTED;
