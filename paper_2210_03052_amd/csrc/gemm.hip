@@ -526,16 +526,36 @@ bt_status gemm_dispatch(const bt_half* A, const bt_half* W, int M, int N, int K,
     case 5: return BT_PIPE(64, 64, 2, 2, 4);
     case 11: return BT_PIPE(256, 128, 4, 2, 3);
     case 16: return BT_PIPE(128, 64, 4, 2, 4);
+    case 20: return BT_PIPE(128, 64, 4, 2, 5);
+    case 25: return BT_PIPE(192, 128, 2, 4, 3);
+    case 26: return BT_PIPE(128, 256, 2, 4, 3);
+    case 27: return BT_PIPE(128, 128, 2, 4, 4);
+    case 28: return BT_PIPE(64, 128, 2, 4, 4);
     case 99: return launch_simple(a, w, c, M, N, K, act, epi, ep, st);
     default: break;
   }
 #endif
-  // Tile choice.  A compute unit ingests operands at ~50 B/clk, so big tiles (more flops per byte
-  // staged) win as long as there are enough of them to occupy most of the 256 compute units:
-  // 256x128 on 8 waves (64x64 each), else 128x64 on 8 waves (32x32 each), else 64x64 on 4 waves.
-  if (tiles(256, 128) >= 150) return BT_PIPE(256, 128, 4, 2, 3);
-  if (tiles(128, 64) >= 150) return BT_PIPE(128, 64, 4, 2, 4);
-  return BT_PIPE(64, 64, 2, 2, 4);
+  // Tile choice by a small cost model.  Every tile shape is bound by how fast a compute unit ingests
+  // operand slabs (~85 GB/s here whatever the shape), so one 64-deep slab costs a time proportional to
+  // BM+BN, and the grid runs in ceil(tiles / 256) rounds of one tile per compute unit.  slab_us and
+  // epi_us (epilogue + pipeline fill) were measured per shape on MI355X; GELU adds to the epilogue.
+  struct Cand { int bm, bn; float slab_us, epi_us; };
+  static const Cand cands[4] = {{256, 128, 0.607f, 2.2f}, {192, 128, 0.482f, 1.5f}, {128, 64, 0.298f, 0.78f},
+                                {64, 64, 0.183f, 0.4f}};
+  int best = 0;
+  float best_us = 0.f;
+  for (int c = 0; c < 4; ++c) {
+    const long long rounds = (tiles(cands[c].bm, cands[c].bn) + 255) / 256;
+    const float act_us = act != BT_ACT_NONE ? 9e-5f * cands[c].bm * cands[c].bn : 0.f;
+    const float us = (float)rounds * ((float)(K / 64) * cands[c].slab_us + cands[c].epi_us + act_us);
+    if (c == 0 || us < best_us) { best = c; best_us = us; }
+  }
+  switch (best) {
+    case 0: return BT_PIPE(256, 128, 4, 2, 3);
+    case 1: return BT_PIPE(192, 128, 2, 4, 3);
+    case 2: return BT_PIPE(128, 64, 4, 2, 4);
+    default: return BT_PIPE(64, 64, 2, 2, 4);
+  }
 #undef BT_PIPE
 }
 
