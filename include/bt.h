@@ -59,11 +59,17 @@ const char* bt_status_string(bt_status s);
  *                             token_idx[i] = b*S + t of the i-th valid token in
  *                             row-major order
  *   h_total      host int32   T = number of valid tokens
- * This is the one call that synchronises: it waits for `stream` once so that
- * *h_total is valid on return.  A length outside [0,S] or a mask entry outside
- * {0,1} is detected on the device and reported as BT_ERR_INVALID_ARG after that
- * wait (the outputs are then unspecified).  Requires 1 <= S <= BT_MAX_SEQ,
- * B*S < 2^31.
+ * This is the one call that blocks the host: *h_total is valid on return.
+ *   - h_total in ordinary host memory: the total is copied back and `stream` is
+ *     synchronised once.
+ *   - h_total in pinned, device-visible host memory (hipHostMalloc): the kernel stores
+ *     the total there as soon as it is known and the host polls for it; the stream is
+ *     NOT synchronised (d_cu_seqlens / d_token_idx are ready for later work on the same
+ *     stream, as for any other call).  About 20 us less host latency per batch.  Each
+ *     thread that calls concurrently needs its own h_total.
+ * A length outside [0,S] or a mask entry outside {0,1} is detected on the device and
+ * reported as BT_ERR_INVALID_ARG (*h_total = 0, the other outputs are then
+ * unspecified).  Requires 1 <= S <= BT_MAX_SEQ, B*S < 2^31.
  */
 bt_status bt_build_offsets(const int32_t* d_mask, const int32_t* d_lengths, int B, int S,
                            int32_t* d_cu_seqlens, int32_t* d_token_idx, int32_t* h_total,

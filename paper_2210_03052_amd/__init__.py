@@ -10,6 +10,7 @@ from __future__ import annotations
 
 import ctypes
 import os
+import threading as _threading
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_PKG, "libbt.so")
@@ -108,8 +109,21 @@ def _call(name, *args):
 
 
 # ------------------------------------------------------------------ entry points
-def build_offsets(mask=None, lengths=None, S=None):
-    """bt_build_offsets.  Returns (cu_seqlens int32[B+1], token_idx int32[T], T)."""
+_tls = _threading.local()
+
+
+def _pinned_total():
+    """One pinned int32 per host thread: the device writes the token count there and the host polls it."""
+    t = getattr(_tls, "total", None)
+    if t is None:
+        t = _tls.total = _torch().empty(1, dtype=_torch().int32, pin_memory=True)
+    return t
+
+
+def build_offsets(mask=None, lengths=None, S=None, pinned=True):
+    """bt_build_offsets.  Returns (cu_seqlens int32[B+1], token_idx int32[T], T).
+    pinned=True hands the library a pinned host word for T (no stream synchronisation);
+    pinned=False passes ordinary host memory (copy + one synchronisation)."""
     torch = _torch()
     if (mask is None) == (lengths is None):
         raise ValueError("give exactly one of mask / lengths")
@@ -124,9 +138,16 @@ def build_offsets(mask=None, lengths=None, S=None):
         B, dev = lengths.shape[0], lengths.device
     cu = torch.empty(B + 1, dtype=torch.int32, device=dev)
     tok = torch.empty(max(1, B * S), dtype=torch.int32, device=dev)
-    total = _c.c_int32(-1)
-    _call("bt_build_offsets", _ptr(mask), _ptr(lengths), B, int(S), _ptr(cu), _ptr(tok), _c.byref(total), _stream())
-    T = int(total.value)
+    if pinned:
+        slot = _pinned_total()
+        _call("bt_build_offsets", _ptr(mask), _ptr(lengths), B, int(S), _ptr(cu), _ptr(tok),
+              _c.cast(slot.data_ptr(), _c.POINTER(_c.c_int32)), _stream())
+        T = int(slot[0])
+    else:
+        total = _c.c_int32(-1)
+        _call("bt_build_offsets", _ptr(mask), _ptr(lengths), B, int(S), _ptr(cu), _ptr(tok), _c.byref(total),
+              _stream())
+        T = int(total.value)
     return cu, tok[:T], T
 
 

@@ -1,5 +1,7 @@
 // Zero-padding algorithm (Sec. III-D, Fig. 4): prefix sum of the mask matrix,
 // position array, pack and unpack.  Integer / byte work: bit-exact.
+#include <chrono>
+
 #include "common.h"
 
 namespace bt {
@@ -13,10 +15,13 @@ constexpr int kOffsetsThreads = 1024;  // 16 wavefronts, one per sentence at a t
 //   phase 3: per sentence, ballot/mbcnt ranks every valid token and writes
 //            token_idx[cu[b] + rank] = b*S + t
 // A length outside [0,S] or a mask entry outside {0,1} sets cu[B] = -1.
+// host_total (optional): device-visible host memory that receives the total (or -1) as soon as it
+// is known, before the position array is written, so that the host can go on without a stream sync.
 __global__ __launch_bounds__(kOffsetsThreads) void offsets_kernel(const int32_t* __restrict__ mask,
                                                                  const int32_t* __restrict__ lengths, int B, int S,
                                                                  int32_t* __restrict__ cu,
-                                                                 int32_t* __restrict__ token_idx) {
+                                                                 int32_t* __restrict__ token_idx,
+                                                                 int32_t* host_total) {
   __shared__ int s_bad;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nwave = kOffsetsThreads / kWave;
   if (threadIdx.x == 0) s_bad = 0;
@@ -60,6 +65,8 @@ __global__ __launch_bounds__(kOffsetsThreads) void offsets_kernel(const int32_t*
     if (lane == 0) cu[0] = 0;
   }
   __syncthreads();
+  if (threadIdx.x == 0 && host_total)
+    __hip_atomic_store(host_total, s_bad ? -1 : cu[B], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
 
   for (int b = wave; b < B; b += nwave) {
     const int base = cu[b];
@@ -125,15 +132,35 @@ extern "C" bt_status bt_build_offsets(const int32_t* d_mask, const int32_t* d_le
     if (hipMemsetAsync(d_cu_seqlens, 0, sizeof(int32_t), st) != hipSuccess) return BT_ERR_HIP;
     return hipStreamSynchronize(st) == hipSuccess ? BT_OK : BT_ERR_HIP;
   }
-  offsets_kernel<<<1, kOffsetsThreads, 0, st>>>(d_mask, d_lengths, B, S, d_cu_seqlens, d_token_idx);
+  // Fast path: h_total lies in pinned host memory that the device can write (hipHostMalloc).  The
+  // kernel stores the total there the moment it is known and the host polls for it: no copy, no
+  // stream synchronisation, and later launches on the stream are ordered after the kernel anyway.
+  hipPointerAttribute_t attr;
+  int32_t* h_dev = nullptr;
+  if (hipPointerGetAttributes(&attr, h_total) == hipSuccess && attr.type == hipMemoryTypeHost && attr.devicePointer)
+    h_dev = static_cast<int32_t*>(attr.devicePointer);
+  else
+    (void)hipGetLastError();  // ordinary host memory: not an error
+  constexpr int32_t kPending = INT32_MIN;
+  volatile int32_t* slot = h_total;
+  if (h_dev) *slot = kPending;
+  offsets_kernel<<<1, kOffsetsThreads, 0, st>>>(d_mask, d_lengths, B, S, d_cu_seqlens, d_token_idx, h_dev);
   if (hipGetLastError() != hipSuccess) return BT_ERR_HIP;
-  int32_t total = 0;
-  if (hipMemcpyAsync(&total, d_cu_seqlens + B, sizeof(int32_t), hipMemcpyDeviceToHost, st) != hipSuccess)
-    return BT_ERR_HIP;
-  if (hipStreamSynchronize(st) != hipSuccess) return BT_ERR_HIP;
-  if (total < 0) return BT_ERR_INVALID_ARG;
-  *h_total = total;
-  return BT_OK;
+  int32_t total = kPending;
+  if (h_dev) {
+    const auto t0 = std::chrono::steady_clock::now();
+    for (long spin = 0; (total = *slot) == kPending; ++spin) {
+      if ((spin & 1023) == 1023 && std::chrono::steady_clock::now() - t0 > std::chrono::milliseconds(200)) break;
+      __builtin_ia32_pause();
+    }
+  }
+  if (total == kPending) {  // pageable h_total, or the store has not shown up: copy and synchronise
+    if (hipMemcpyAsync(&total, d_cu_seqlens + B, sizeof(int32_t), hipMemcpyDeviceToHost, st) != hipSuccess)
+      return BT_ERR_HIP;
+    if (hipStreamSynchronize(st) != hipSuccess) return BT_ERR_HIP;
+  }
+  *h_total = total < 0 ? 0 : total;
+  return total < 0 ? BT_ERR_INVALID_ARG : BT_OK;
 }
 
 extern "C" bt_status bt_pack(const bt_half* d_padded, const int32_t* d_token_idx, int T, int H,

@@ -7,7 +7,9 @@ library (tests, bench, smoke) use, so that both sides see identical numbers.
 
 Workloads follow the evaluation protocol of Sec. IV: fp16 tensors, sequence
 lengths drawn uniformly at random, standard BERT shapes (12 heads x 64,
-hidden 768, FFN 3072; the "large" shape is 16 x 64, hidden 1024, FFN 4096).
+hidden 768, FFN 3072; the "large" shape is 16 x 64, hidden 1024, FFN 4096),
+plus two of the stack variants of Table IV (cross-layer weight sharing with 16
+heads, and a 6-layer stack).
 The paper uses synthetic random lengths itself, so no dataset is stood in for.
 """
 from __future__ import annotations
@@ -32,6 +34,7 @@ class Workload:
     layers: int          # 0 = attention alone
     length_law: str
     ln_eps: float = 1e-12
+    shared_weights: bool = False   # every layer uses layer 0's parameters (cross-layer sharing, Table IV)
 
     @property
     def seed_lengths(self):
@@ -49,6 +52,10 @@ WORKLOADS = {
     "bert_base_b16_s1024": Workload("bert_base_b16_s1024", 4, 16, 1024, 768, 12, 64, 3072, 12, "U[128,1024]"),
     "bert_large_b32_s512": Workload("bert_large_b32_s512", 5, 32, 512, 1024, 16, 64, 4096, 24,
                                     "80% U[16,128] + 20% U[384,512], shuffled"),
+    # Shape variants of Table IV (layers / heads / head size): same kernels, different stacks.
+    "albert_b16_s256": Workload("albert_b16_s256", 6, 16, 256, 1024, 16, 64, 4096, 12, "U[51,256]",
+                                shared_weights=True),                                        # 12 / 16 / 64, shared
+    "distilbert_b16_s256": Workload("distilbert_b16_s256", 7, 16, 256, 768, 12, 64, 3072, 6, "U[51,256]"),  # 6 / 12 / 64
 }
 
 
@@ -59,7 +66,7 @@ def draw_lengths(wl: Workload) -> np.ndarray:
         L = rng.integers(8, 64 + 1, wl.B)
     elif wl.index == 2:
         L = rng.integers(1, 256 + 1, wl.B)
-    elif wl.index == 3:
+    elif wl.index in (3, 6, 7):
         L = rng.integers(51, 256 + 1, wl.B)         # mean 153.5 = 0.6 * 256
     elif wl.index == 4:
         L = rng.integers(128, 1024 + 1, wl.B)
@@ -89,6 +96,8 @@ def make_layer_params(wl: Workload, layer: int, stress: bool = False) -> dict:
     initialisation).  ``stress=True`` draws non-trivial biases and LN affine
     parameters as well, so that a dropped bias or affine term cannot hide.
     """
+    if wl.shared_weights:
+        layer = 0
     rng = np.random.default_rng([wl.seed_tensors, layer, 1 if stress else 0])
     H, F = wl.H, wl.F
     p = {

@@ -57,6 +57,20 @@ def test_offsets_from_lengths_workloads(bt, name):
     assert np.array_equal(host(cu), rcu) and np.array_equal(host(tok), rtok)
 
 
+def test_offsets_pinned_and_pageable_total(bt):
+    """The token count comes back through pinned memory (polled, no stream sync) or through ordinary
+    host memory (copy + sync): same outputs either way, and an invalid length is reported on both."""
+    L = np.array([5, 0, 64, 17], np.int32)
+    a = bt.build_offsets(lengths=dev(L), S=64, pinned=True)
+    b = bt.build_offsets(lengths=dev(L), S=64, pinned=False)
+    assert a[2] == b[2] == int(L.sum())
+    assert np.array_equal(host(a[0]), host(b[0])) and np.array_equal(host(a[1]), host(b[1]))
+    for pinned in (True, False):
+        with pytest.raises(bt.BtError):
+            bt.build_offsets(lengths=dev(np.array([3, 65], np.int32)), S=64, pinned=pinned)
+    assert bt.build_offsets(lengths=dev(L), S=64, pinned=True)[2] == int(L.sum())   # usable again after an error
+
+
 def test_offsets_lengths_edge_cases(bt):
     for L, S in (([0, 0, 0], 8), ([8, 0, 8], 8), ([64] * 20, 64), ([1] * 130, 3), ([0, 5, 0, 1, 128], 128)):
         L = np.array(L, np.int32)
@@ -327,6 +341,17 @@ def test_stack_bert_base_b16_s1024_sampled(bt, folded):
 def test_stack_bert_large_b32_s512_sampled(bt, folded):
     """24 layers of the large shape, skewed lengths: 5e-2 at layer 12, 1e-1 at 24."""
     _sampled_stack(bt, "bert_large_b32_s512", TOL_12, TOL_24, folded)
+
+
+@pytest.mark.parametrize("name", ["albert_b16_s256", "distilbert_b16_s256"])
+def test_stack_table4_shape_variants_sampled(bt, name):
+    """Stack variants of Table IV: 12 layers sharing one parameter set (16 heads, hidden 1024) and a
+    6-layer BERT-base-shaped stack; shortest / median / longest sequence through the oracle."""
+    wl = I.WORKLOADS[name]
+    if wl.shared_weights:
+        p0, p5 = I.make_layer_params(wl, 0), I.make_layer_params(wl, 5)
+        assert all(np.array_equal(p0[k], p5[k]) for k in ("w_qkv", "w_o", "w_1", "w_2"))
+    _sampled_stack(bt, name, TOL_12, TOL_12, False)
 
 
 # ------------------------------------------------------------------ LayerNorm folded into the GEMM epilogues
