@@ -31,13 +31,13 @@ PEAK_HBM = 8000.0        # GB/s, published
 # HBM bytes per launch (fetched + written) from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this
 # script, scaled by the same counters' reading of a 1 GiB copy; see profiles/ for the runs.
 MEASURED_TRAFFIC = {
-    ("bert_base_b16_s256", "gemm0_qkv_bias"): 36420 * 1024,
-    ("bert_base_b16_s256", "varlen_mha"): 20570 * 1024,
-    ("bert_base_b16_s256", "gemm1_proj"): 17358 * 1024,
-    ("bert_base_b16_s256", "bias_residual_ln0"): 10468 * 1024,
-    ("bert_base_b16_s256", "gemm2_bias_gelu"): 41535 * 1024,
-    ("bert_base_b16_s256", "gemm3_ffn_down"): 58866 * 1024,
-    ("bert_base_b16_s256", "bias_residual_ln1"): 10468 * 1024,
+    ("bert_base_b16_s256", "gemm0_qkv_bias"): 35950 * 1024,
+    ("bert_base_b16_s256", "varlen_mha"): 20585 * 1024,
+    ("bert_base_b16_s256", "gemm1_proj"): 17380 * 1024,
+    ("bert_base_b16_s256", "bias_residual_ln0"): 10455 * 1024,
+    ("bert_base_b16_s256", "gemm2_bias_gelu"): 41542 * 1024,
+    ("bert_base_b16_s256", "gemm3_ffn_down"): 58889 * 1024,
+    ("bert_base_b16_s256", "bias_residual_ln1"): 10455 * 1024,
 }
 
 
