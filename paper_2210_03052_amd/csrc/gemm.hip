@@ -2,18 +2,17 @@
 // A [M,K] and W [N,K] are both K-contiguous, which is exactly the operand order
 // the gfx950 MFMA wants: every lane feeds 8 consecutive K values of one row.
 //
-// Main kernel (K % BK == 0): 256 threads = 4 wavefronts in a 2x2 grid, block
-// tile BM x BN x BK, wave tile (BM/2) x (BN/2) of 32x32x16 fp16 MFMA blocks with
-// fp32 accumulators.  Operand slabs travel global memory -> LDS directly
-// (global_load_lds_dwordx4: no register staging), NS slabs deep, so that NS-1
-// slabs are in flight while one is multiplied; each wave waits only for its own
-// oldest slab (s_waitcnt vmcnt) and one s_barrier per slab publishes it.
-// LDS rows are unpadded (a DMA instruction fills 1 KB contiguously) and
-// XOR-swizzled at 16-byte granularity on the *global* side, so the 128-bit
-// operand reads of 16 consecutive rows still hit 64 distinct banks.
-// The product is computed transposed (W is the MFMA A operand): each lane ends
-// up with 4 consecutive output columns of one row and stores them with one
-// 8-byte write after bias/activation in fp32.
+// Main kernel (K % 64 == 0): WGM x WGN wavefronts, block tile BM x BN x 64, wave tile
+// (BM/WGM) x (BN/WGN) of 32x32x16 fp16 MFMA blocks with fp32 accumulators.
+// Operand slabs travel global memory -> LDS directly (global_load_lds_dwordx4: no
+// register staging), NS stages deep, so that NS-1 slabs are in flight while one is
+// multiplied; each wave waits only for its own oldest slab (s_waitcnt vmcnt) and one
+// s_barrier per slab publishes it.  LDS rows are unpadded (a DMA instruction fills
+// 1 KB contiguously) and XOR-swizzled at 16-byte granularity on the *global* side,
+// so the 128-bit operand reads of 16 consecutive rows still hit 64 distinct banks.
+// The product is computed transposed (W is the MFMA A operand): each lane ends up
+// with 4 consecutive output columns of one row; bias/activation run in fp32 and the
+// fp16 tile leaves through LDS with 16-byte stores.
 //
 // Fallback kernel (any K % 8 == 0): register-staged, zero-fills the K tail.
 #include <type_traits>
