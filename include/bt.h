@@ -192,10 +192,9 @@ bt_status bt_encoder_prepare(const bt_layer* layers, int n_layers, float* d_fold
  * d_fold == NULL: each layer runs as bt_encoder_layer_fwd does (7 launches per layer).
  * d_fold from bt_encoder_prepare: the LayerNorms are folded into the GEMM epilogues
  * (5 launches per layer plus one normalisation at the end); same function, the
- * results differ from the unfolded path only by fp16 rounding.  The row sums are
- * accumulated with floating-point atomics in no fixed order, so two folded runs on
- * the same input may differ in the last fp16 bit; the unfolded path is bit-reproducible
- * and, on the BERT shapes measured so far, just as fast: folding is opt-in.
+ * results differ from the unfolded path only by fp16 rounding.  Row statistics travel
+ * as per-tile partial sums that are added in a fixed order: bit-reproducible, like the
+ * unfolded path.
  */
 bt_status bt_encoder_fwd(const bt_layer* layers, int n_layers, const float* d_fold, const bt_half* d_x,
                          const int32_t* d_cu_seqlens, int B, int T, int max_len, bt_half* d_y,

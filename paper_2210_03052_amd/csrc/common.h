@@ -35,22 +35,27 @@ __device__ __forceinline__ int xcd_remap(int id, int n) {
 }
 
 // Epilogue forms of the packed GEMM (see store_tile in gemm.hip) and their operands.
+// Row statistics of a LayerNorm travel as partial sums: part[m][p] = (sum z, sum z^2) of row m over the
+// columns of column tile p of the producing GEMM, p < np.  They are written once each and added up
+// in a fixed order by whoever needs the mean and variance: no atomics, bit-reproducible.
 enum { EPI_PLAIN = 0, EPI_FOLD = 1, EPI_RESID = 2 };
 struct GemmEpi {
   const half_t* bias = nullptr;  // PLAIN / RESID: [N] or null
-  float* zero_stats = nullptr;   // any form: per-row sums [M][2] to clear for a later kernel, or null
-  // FOLD: the A operand is u = gamma (.) z of a LayerNorm whose row sums are ln_stats
-  const float* ln_stats = nullptr;  // [M][2] = (sum z, sum z^2)
+  // FOLD: the A operand is u = gamma (.) z of a LayerNorm whose row sums are ln_part
+  const float2* ln_part = nullptr;  // [M][ln_np]
+  int ln_np = 0;
   const float* fold_c = nullptr;    // [N]  W gamma
   const float* fold_d = nullptr;    // [N]  W beta + bias
   float inv_h = 0.f, eps = 0.f;     // 1/width and epsilon of that LayerNorm (also used by RESID)
-  // RESID: v = acc + bias + residual; C = out_gamma (.) v; stats_out += (sum v, sum v^2)
-  const half_t* resid = nullptr;        // [M][N]: plain residual, or u_r if resid_stats is set
-  const float* resid_stats = nullptr;   // [M][2] or null
-  const half_t* resid_gamma = nullptr;  // [N] (with resid_stats): residual = rstd (u_r - mu gamma) + beta
+  // RESID: v = acc + bias + residual; C = out_gamma (.) v; part_out[m][p] = (sum v, sum v^2) over column tile p
+  const half_t* resid = nullptr;        // [M][N]: plain residual, or u_r if resid_part is set
+  const float2* resid_part = nullptr;   // [M][resid_np] or null
+  int resid_np = 0;
+  const half_t* resid_gamma = nullptr;  // [N] (with resid_part): residual = rstd (u_r - mu gamma) + beta
   const half_t* resid_beta = nullptr;
   const half_t* out_gamma = nullptr;    // [N]
-  float* stats_out = nullptr;           // [M][2]
+  float2* part_out = nullptr;           // [M][part_np]
+  int part_np = 0;                      // set by the launcher: number of column tiles
 };
 
 // Butterfly reductions over the 64 lanes of a wavefront.

@@ -85,89 +85,88 @@ __device__ __forceinline__ void static_for(F&& f) {
 //              but NOT yet normalised input of a LayerNorm; since LN(z) W^T = rstd (u W^T - mu c) + d
 //              with c = W gamma, d = W beta + bias, the normalisation moves into this epilogue and the
 //              LayerNorm kernel in front of the GEMM disappears.  mu, rstd come from per-row sums.
-//   EPI_RESID  v = acc + bias + residual, C = u = gamma_out (.) v, and the per-row sums of v and v^2
-//              are accumulated with atomics for the LayerNorm that follows (add-bias + residual of
+//   EPI_RESID  v = acc + bias + residual, C = u = gamma_out (.) v, and this wave's partial row sums of
+//              v and v^2 are stored for the LayerNorm that follows (add-bias + residual of
 //              Sec. III-C1 fused here; the normalisation itself is folded into the next GEMM).  The
 //              residual is either a plain tensor or itself a folded LayerNorm output
 //              rstd (u_r - mu gamma_r) + beta_r.
+// mu, rstd (FOLD: of the A operand's rows; RESID: of the residual's rows) and the residual tile are
+// fetched by the caller before the K loop so that their latency is not exposed here.
 // The fp16 tile of this wave is then transposed through a private LDS region (rows padded to WN+8
 // halves) so that global memory is written with 16-byte-per-lane stores, 8 lanes covering 128
 // contiguous bytes of an output row.
-template <int MI, int NI, int ACT, int EPI>
-__device__ __forceinline__ void store_tile(const float16_t (&acc)[MI][NI], const GemmEpi& ep, half_t* __restrict__ C,
-                                           int M, int N, int m_base, int n_base, int lane,
+template <int MI, int NI, int WGN, int ACT, int EPI>
+__device__ __forceinline__ void store_tile(const float16_t (&acc)[MI][NI], const GemmEpi& ep, const float (&mu)[MI],
+                                           const float (&rstd)[MI], const half4_t (&rres)[MI][NI][4], int tile_n,
+                                           int wn, int row_in_tile, float2* red /* LDS [WGN][rows of the tile] */,
+                                           int tile_rows, half_t* __restrict__ C, int M, int N, int m_base,
+                                           int n_base, int lane,
                                            half_t* stage /* this wave's LDS region: MI*32 x (NI*32+8) halves */) {
   constexpr int WN = NI * 32, LD = WN + 8;
   const int l32 = lane & 31, hf = lane >> 5;
-  // per-row LayerNorm statistics of the A operand (FOLD) / of the residual source (RESID)
-  float mu[MI], rstd[MI], s0[MI], s1[MI];
-  const float* row_stats = EPI == EPI_FOLD ? ep.ln_stats : (EPI == EPI_RESID ? ep.resid_stats : nullptr);
+  // Per-column operands of this lane's 4*NI column groups, all requested at once (one memory latency
+  // instead of one per group); columns past N are clamped for the load and never stored.
+  float bv[NI][4][4], cv[EPI == EPI_FOLD ? NI : 1][4][4];
+  half4_t og[EPI == EPI_RESID ? NI : 1][4], rg[EPI == EPI_RESID ? NI : 1][4], rb[EPI == EPI_RESID ? NI : 1][4];
+  const bool folded_resid = EPI == EPI_RESID && ep.resid_part != nullptr;
 #pragma unroll
-  for (int i = 0; i < MI; ++i) {
-    mu[i] = 0.f; rstd[i] = 1.f; s0[i] = 0.f; s1[i] = 0.f;
-    const int m = m_base + i * 32 + l32;
-    if (EPI != EPI_PLAIN && row_stats && m < M) {
-      const float2 st = *reinterpret_cast<const float2*>(row_stats + 2 * (size_t)m);
-      mu[i] = st.x * ep.inv_h;
-      rstd[i] = rsqrtf(fmaxf(st.y * ep.inv_h - mu[i] * mu[i], 0.f) + ep.eps);
+  for (int j = 0; j < NI; ++j)
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+      const int nc = min(n_base + j * 32 + 8 * g + 4 * hf, N - 4);
+      if constexpr (EPI == EPI_FOLD) {
+        const float4_t c4 = *reinterpret_cast<const float4_t*>(ep.fold_c + nc);
+        const float4_t d4 = *reinterpret_cast<const float4_t*>(ep.fold_d + nc);
+#pragma unroll
+        for (int t = 0; t < 4; ++t) { cv[j][g][t] = c4[t]; bv[j][g][t] = d4[t]; }
+      } else {
+        half4_t b4 = {(half_t)0.f, (half_t)0.f, (half_t)0.f, (half_t)0.f};
+        if (ep.bias) b4 = *reinterpret_cast<const half4_t*>(ep.bias + nc);
+#pragma unroll
+        for (int t = 0; t < 4; ++t) bv[j][g][t] = (float)b4[t];
+      }
+      if constexpr (EPI == EPI_RESID) {
+        og[j][g] = *reinterpret_cast<const half4_t*>(ep.out_gamma + nc);
+        if (folded_resid) {
+          rg[j][g] = *reinterpret_cast<const half4_t*>(ep.resid_gamma + nc);
+          rb[j][g] = *reinterpret_cast<const half4_t*>(ep.resid_beta + nc);
+        }
+      }
     }
-  }
+  float s0[MI], s1[MI];
+#pragma unroll
+  for (int i = 0; i < MI; ++i) s0[i] = s1[i] = 0.f;
 #pragma unroll
   for (int j = 0; j < NI; ++j) {
 #pragma unroll
     for (int g = 0; g < 4; ++g) {
       const int nl = j * 32 + 8 * g + 4 * hf;
-      const int n = n_base + nl;
-      const bool n_ok = n < N;  // N % 8 == 0: the 4 columns are all in or all out
-      float bv[4] = {0.f, 0.f, 0.f, 0.f}, cv[4] = {0.f, 0.f, 0.f, 0.f};
-      float rg[4] = {0.f, 0.f, 0.f, 0.f}, rb[4] = {0.f, 0.f, 0.f, 0.f}, og[4] = {1.f, 1.f, 1.f, 1.f};
-      if (n_ok) {
-        if (EPI == EPI_FOLD) {
-          const float4_t c4 = *reinterpret_cast<const float4_t*>(ep.fold_c + n);
-          const float4_t d4 = *reinterpret_cast<const float4_t*>(ep.fold_d + n);
-#pragma unroll
-          for (int t = 0; t < 4; ++t) { cv[t] = c4[t]; bv[t] = d4[t]; }
-        } else if (ep.bias) {
-          const half4_t b4 = *reinterpret_cast<const half4_t*>(ep.bias + n);
-#pragma unroll
-          for (int t = 0; t < 4; ++t) bv[t] = (float)b4[t];
-        }
-        if (EPI == EPI_RESID) {
-          const half4_t g4 = *reinterpret_cast<const half4_t*>(ep.out_gamma + n);
-#pragma unroll
-          for (int t = 0; t < 4; ++t) og[t] = (float)g4[t];
-          if (ep.resid_stats) {
-            const half4_t a4 = *reinterpret_cast<const half4_t*>(ep.resid_gamma + n);
-            const half4_t b4 = *reinterpret_cast<const half4_t*>(ep.resid_beta + n);
-#pragma unroll
-            for (int t = 0; t < 4; ++t) { rg[t] = (float)a4[t]; rb[t] = (float)b4[t]; }
-          }
-        }
-      }
+      const bool n_ok = n_base + nl < N;  // N % 8 == 0: the 4 columns are all in or all out
 #pragma unroll
       for (int i = 0; i < MI; ++i) {
         const int m = m_base + i * 32 + l32;
         float v[4];
 #pragma unroll
         for (int t = 0; t < 4; ++t) v[t] = acc[i][j][4 * g + t];
-        if (EPI == EPI_FOLD) {
+        if constexpr (EPI == EPI_FOLD) {
 #pragma unroll
-          for (int t = 0; t < 4; ++t) v[t] = __builtin_fmaf(rstd[i], v[t] - mu[i] * cv[t], bv[t]);
+          for (int t = 0; t < 4; ++t) v[t] = __builtin_fmaf(rstd[i], v[t] - mu[i] * cv[j][g][t], bv[j][g][t]);
         } else {
 #pragma unroll
-          for (int t = 0; t < 4; ++t) v[t] += bv[t];
+          for (int t = 0; t < 4; ++t) v[t] += bv[j][g][t];
         }
-        if (EPI == EPI_RESID) {
-          if (n_ok && m < M) {
-            const half4_t r4 = *reinterpret_cast<const half4_t*>(ep.resid + (size_t)m * N + n);
+        if constexpr (EPI == EPI_RESID) {
+          const half4_t r4 = rres[i][j][g];
+          const bool ok = n_ok && m < M;
 #pragma unroll
-            for (int t = 0; t < 4; ++t) {
-              const float r = ep.resid_stats ? __builtin_fmaf(rstd[i], (float)r4[t] - mu[i] * rg[t], rb[t]) : (float)r4[t];
-              v[t] += r;
-              s0[i] += v[t];
-              s1[i] = __builtin_fmaf(v[t], v[t], s1[i]);
-              v[t] *= og[t];
-            }
+          for (int t = 0; t < 4; ++t) {
+            const float r = folded_resid
+                                ? __builtin_fmaf(rstd[i], (float)r4[t] - mu[i] * (float)rg[j][g][t], (float)rb[j][g][t])
+                                : (float)r4[t];
+            v[t] = ok ? v[t] + r : 0.f;
+            s0[i] += v[t];
+            s1[i] = __builtin_fmaf(v[t], v[t], s1[i]);
+            v[t] *= (float)og[j][g][t];
           }
         } else {
 #pragma unroll
@@ -183,14 +182,27 @@ __device__ __forceinline__ void store_tile(const float16_t (&acc)[MI][NI], const
       }
     }
   }
-  if (EPI == EPI_RESID) {
+  if constexpr (EPI == EPI_RESID) {
+    // Row sums of this wave's columns -> LDS; after the barrier the wavefronts of tile column 0 add the
+    // WGN contributions in order and store ONE partial per row and column tile.
 #pragma unroll
     for (int i = 0; i < MI; ++i) {  // the two 32-lane halves hold the two column halves of the same row
       const float t0 = s0[i] + __shfl_xor(s0[i], 32, kWave), t1 = s1[i] + __shfl_xor(s1[i], 32, kWave);
-      const int m = m_base + i * 32 + l32;
-      if (hf == 0 && m < M) {
-        atomicAdd(ep.stats_out + 2 * (size_t)m, t0);
-        atomicAdd(ep.stats_out + 2 * (size_t)m + 1, t1);
+      if (hf == 0) red[wn * tile_rows + row_in_tile + i * 32 + l32] = make_float2(t0, t1);
+    }
+    __syncthreads();
+    if (wn == 0 && hf == 0) {
+#pragma unroll
+      for (int i = 0; i < MI; ++i) {
+        const int r = row_in_tile + i * 32 + l32, m = m_base + i * 32 + l32;
+        float2 t = red[r];
+#pragma unroll
+        for (int w = 1; w < WGN; ++w) {
+          const float2 u = red[w * tile_rows + r];
+          t.x += u.x;
+          t.y += u.y;
+        }
+        if (m < M) ep.part_out[(size_t)m * ep.part_np + tile_n] = t;
       }
     }
   }
@@ -205,13 +217,75 @@ __device__ __forceinline__ void store_tile(const float16_t (&acc)[MI][NI], const
   }
 }
 
-// Rows [m0, m0+rows) of a per-row statistics buffer are cleared by the workgroups of tile column 0,
-// ahead of the later kernel that accumulates into it (saves a fill kernel per LayerNorm).
-__device__ __forceinline__ void clear_stats(float* stats, int m0, int rows, int M, int tid) {
-  if (stats && tid < rows && m0 + tid < M) {
-    stats[2 * (size_t)(m0 + tid)] = 0.f;
-    stats[2 * (size_t)(m0 + tid) + 1] = 0.f;
+// Mean and 1/sigma of the rows m_base + i*32 + l32 from their partial sums, in two steps so that the
+// loads can be issued ahead of the operand slabs and collected after them:
+//   request_row_sums: the two 32-lane halves each request one half of a row's partials (up to
+//     kMaxHalfParts each, clamped indices, no branches).  Issued through inline assembly so that the
+//     compiler does not put a wait for ALL outstanding memory operations in front of their first use;
+//   finish_row_sums: after the caller has waited (s_waitcnt vmcnt), add them in index order,
+//     exchange the halves, derive mu and rstd.
+constexpr int kMaxHalfParts = 8;  // np <= 16: H <= 1024 at 64-wide column tiles; more falls back to a loop
+
+template <int MI>
+__device__ __forceinline__ void request_row_sums(const float2* __restrict__ part, int np, int M, int m_base, int l32,
+                                                 int hf, float2 (&v)[MI][kMaxHalfParts]) {
+  const int half_np = (np + 1) >> 1, p0 = hf * half_np, p1 = min(np, p0 + half_np);
+#pragma unroll
+  for (int i = 0; i < MI; ++i) {
+    const float2* row = part + (size_t)min(m_base + i * 32 + l32, M - 1) * np;
+#pragma unroll
+    for (int q = 0; q < kMaxHalfParts; ++q) {
+      const float2* src = row + min(p0 + q, max(p1 - 1, 0));
+      asm volatile("global_load_dwordx2 %0, %1, off" : "=v"(v[i][q]) : "v"(src) : "memory");
+    }
   }
+}
+
+template <int MI>
+__device__ __forceinline__ void finish_row_sums(const float2* __restrict__ part, int np, int M, int m_base, int l32,
+                                                int hf, float inv_h, float eps, float2 (&v)[MI][kMaxHalfParts],
+                                                float (&mu)[MI], float (&rstd)[MI]) {
+  const int half_np = (np + 1) >> 1, p0 = hf * half_np, p1 = min(np, p0 + half_np);
+#pragma unroll
+  for (int i = 0; i < MI; ++i) {
+    float a = 0.f, b = 0.f;
+#pragma unroll
+    for (int q = 0; q < kMaxHalfParts; ++q) {
+      asm volatile("" : "+v"(v[i][q]));  // ordered after the caller's wait
+      if (p0 + q < p1) {
+        a += v[i][q].x;
+        b += v[i][q].y;
+      }
+    }
+    if (half_np > kMaxHalfParts) {  // wide rows: the rest with ordinary loads
+      const float2* row = part + (size_t)min(m_base + i * 32 + l32, M - 1) * np;
+      for (int p = p0 + kMaxHalfParts; p < p1; ++p) {
+        const float2 u = row[p];
+        a += u.x;
+        b += u.y;
+      }
+    }
+    a += __shfl_xor(a, 32, kWave);
+    b += __shfl_xor(b, 32, kWave);
+    mu[i] = a * inv_h;
+    rstd[i] = rsqrtf(fmaxf(b * inv_h - mu[i] * mu[i], 0.f) + eps);
+  }
+}
+
+// The residual tile of EPI_RESID in accumulator layout (zero outside the matrix).
+template <int MI, int NI>
+__device__ __forceinline__ void load_resid(const half_t* __restrict__ resid, int M, int N, int m_base, int n_base,
+                                           int l32, int hf, half4_t (&rres)[MI][NI][4]) {
+  const half4_t zero = {(half_t)0.f, (half_t)0.f, (half_t)0.f, (half_t)0.f};
+#pragma unroll
+  for (int i = 0; i < MI; ++i)
+#pragma unroll
+    for (int j = 0; j < NI; ++j)
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        const int m = m_base + i * 32 + l32, n = n_base + j * 32 + 8 * g + 4 * hf;
+        rres[i][j][g] = (m < M && n < N) ? *reinterpret_cast<const half4_t*>(resid + (size_t)m * N + n) : zero;
+      }
 }
 
 // ---------------------------------------------------------------------------
@@ -257,7 +331,17 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_pipe_kernel(const half_t* 
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform: LDS DMA bases live in M0
   const int wm = wave / WGN, wn = wave % WGN;
   const int l32 = lane & 31, hf = lane >> 5;
-  if (tn == 0) clear_stats(ep.zero_stats, m0, BM, M, tid);
+
+  // Epilogue operands that do not depend on the product are requested now, ahead of the operand
+  // slabs, so that their latency hides behind the K loop: the residual tile (EPI_RESID) and the partial
+  // row sums behind mu / rstd (EPI_FOLD: rows of A; EPI_RESID: rows of a folded residual).
+  half4_t rres[MI][NI][4];  // dead (and removed by the compiler) in the other epilogue forms
+  if constexpr (EPI == EPI_RESID) load_resid<MI, NI>(ep.resid, M, N, m0 + wm * WM, n0 + wn * WN, l32, hf, rres);
+  __shared__ float2 red[EPI == EPI_RESID ? WGN * BM : 1];
+  float2 psum[MI][kMaxHalfParts];
+  const float2* const stat_part = EPI == EPI_FOLD ? ep.ln_part : (EPI == EPI_RESID ? ep.resid_part : nullptr);
+  const int stat_np = EPI == EPI_FOLD ? ep.ln_np : ep.resid_np;
+  if (EPI != EPI_PLAIN && stat_part) request_row_sums<MI>(stat_part, stat_np, M, m0 + wm * WM, l32, hf, psum);
 
   // DMA source pointers.  Instruction q of this wave fills LDS rows [r0, r0+8) of the slab; lane i
   // lands at row r0 + i/8, physical chunk i%8, and therefore fetches logical chunk
@@ -367,6 +451,13 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_pipe_kernel(const half_t* 
   using yes = std::true_type;
   using no = std::false_type;
 
+  float mu[MI], rstd[MI];
+#pragma unroll
+  for (int i = 0; i < MI; ++i) { mu[i] = 0.f; rstd[i] = 1.f; }
+  if (EPI != EPI_PLAIN && stat_part) {
+    wait_vmcnt<(NS - 1) * TOT>();  // everything older than the NS-1 slabs just requested has arrived
+    finish_row_sums<MI>(stat_part, stat_np, M, m0 + wm * WM, l32, hf, ep.inv_h, ep.eps, psum, mu, rstd);
+  }
   wait_vmcnt<(NS - 2) * TOT>();  // slab 0 has landed
   __builtin_amdgcn_s_barrier();
   int kt = 0;
@@ -387,7 +478,8 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_pipe_kernel(const half_t* 
     slab(kt + J, j, no{}, integral_constant<bool, J == NS - 2>{}, integral_constant<int, (NS - 3 - J > 0 ? NS - 3 - J : 0)>{});
   });
   __builtin_amdgcn_s_barrier();  // every wave is done reading the last slab: LDS becomes staging space
-  store_tile<MI, NI, ACT, EPI>(acc, ep, C, M, N, m0 + wm * WM, n0 + wn * WN, lane, smem + wave * STAGE_HALVES);
+  store_tile<MI, NI, WGN, ACT, EPI>(acc, ep, mu, rstd, rres, tn, wn, wm * WM, red, BM, C, M, N, m0 + wm * WM,
+                                    n0 + wn * WN, lane, smem + wave * STAGE_HALVES);
 }
 
 // ---------------------------------------------------------------------------
@@ -406,7 +498,6 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_simple_kernel(const half_t*
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave >> 1, wn = wave & 1, l32 = lane & 31, hf = lane >> 5;
   const int kc = (tid & 7) * 8;
-  if (tn == 0) clear_stats(ep.zero_stats, m0, BM, M, tid);
   float16_t acc[1][1];
 #pragma unroll
   for (int r = 0; r < 16; ++r) acc[0][0][r] = 0.f;
@@ -436,7 +527,20 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_simple_kernel(const half_t*
     }
   }
   __syncthreads();  // operand tiles are dead: reuse them as per-wave staging space (32 x 40 halves each)
-  store_tile<1, 1, ACT, EPI>(acc, ep, C, M, N, m0 + wm * 32, n0 + wn * 32, lane, (wave < 2 ? sA : sB) + (wave & 1) * 32 * 40);
+  float mu[1] = {0.f}, rstd[1] = {1.f};
+  half4_t rres[1][1][4];
+  __shared__ float2 red[EPI == EPI_RESID ? 2 * BM : 1];
+  const float2* const stat_part = EPI == EPI_FOLD ? ep.ln_part : (EPI == EPI_RESID ? ep.resid_part : nullptr);
+  const int stat_np = EPI == EPI_FOLD ? ep.ln_np : ep.resid_np;
+  if (EPI != EPI_PLAIN && stat_part) {
+    float2 psum[1][kMaxHalfParts];
+    request_row_sums<1>(stat_part, stat_np, M, m0 + wm * 32, l32, hf, psum);
+    wait_vmcnt<0>();
+    finish_row_sums<1>(stat_part, stat_np, M, m0 + wm * 32, l32, hf, ep.inv_h, ep.eps, psum, mu, rstd);
+  }
+  if constexpr (EPI == EPI_RESID) load_resid<1, 1>(ep.resid, M, N, m0 + wm * 32, n0 + wn * 32, l32, hf, rres);
+  store_tile<1, 1, 2, ACT, EPI>(acc, ep, mu, rstd, rres, tn, wn, wm * 32, red, BM, C, M, N, m0 + wm * 32, n0 + wn * 32,
+                                lane, (wave < 2 ? sA : sB) + (wave & 1) * 32 * 40);
 }
 
 #ifdef BT_TUNING
@@ -446,13 +550,15 @@ int g_gemm_cfg = -1;
 
 // act x epilogue combinations that exist: PLAIN and FOLD with any activation, RESID without one.
 static bt_status launch_simple(const half_t* A, const half_t* W, half_t* C, int M, int N, int K, bt_act act, int epi,
-                               const GemmEpi& ep, hipStream_t st);
+                               GemmEpi ep, hipStream_t st, int* np_out);
 
 template <int BM, int BN, int WGM, int WGN, int NS>
 static bt_status launch_pipe(const half_t* A, const half_t* W, half_t* C, int M, int N, int K, bt_act act, int epi,
-                             const GemmEpi& ep, hipStream_t st) {
-  if (K / 64 < NS - 1) return launch_simple(A, W, C, M, N, K, act, epi, ep, st);  // pipeline deeper than K
+                             GemmEpi ep, hipStream_t st, int* np_out) {
+  if (K / 64 < NS - 1) return launch_simple(A, W, C, M, N, K, act, epi, ep, st, np_out);  // pipeline deeper than K
   const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
+  ep.part_np = tiles_n;
+  if (np_out) *np_out = ep.part_np;
   const long long n_tiles = (long long)tiles_m * tiles_n;
   if (n_tiles > 0x7fffffffLL) return BT_ERR_UNSUPPORTED;
   dim3 grid((unsigned)n_tiles), block(WGM * WGN * 64);
@@ -480,8 +586,10 @@ static bt_status launch_pipe(const half_t* A, const half_t* W, half_t* C, int M,
 }
 
 static bt_status launch_simple(const half_t* A, const half_t* W, half_t* C, int M, int N, int K, bt_act act, int epi,
-                               const GemmEpi& ep, hipStream_t st) {
+                               GemmEpi ep, hipStream_t st, int* np_out) {
   const int tiles_n = (N + 63) / 64;
+  ep.part_np = tiles_n;
+  if (np_out) *np_out = ep.part_np;
   const long long n_tiles = (long long)((M + 63) / 64) * tiles_n;
   if (n_tiles > 0x7fffffffLL) return BT_ERR_UNSUPPORTED;
   dim3 grid((unsigned)n_tiles), block(kGemmThreads);
@@ -502,14 +610,14 @@ static bt_status launch_simple(const half_t* A, const half_t* W, half_t* C, int 
 }
 
 bt_status gemm_dispatch(const bt_half* A, const bt_half* W, int M, int N, int K, bt_act act, int epi,
-                        const GemmEpi& ep, bt_half* C, hipStream_t st) {
+                        const GemmEpi& ep, bt_half* C, hipStream_t st, int* np_out) {
   const half_t* a = reinterpret_cast<const half_t*>(A);
   const half_t* w = reinterpret_cast<const half_t*>(W);
   half_t* c = reinterpret_cast<half_t*>(C);
   if (epi == EPI_RESID && act != BT_ACT_NONE) return BT_ERR_INVALID_ARG;
-  if ((K % 64) != 0) return launch_simple(a, w, c, M, N, K, act, epi, ep, st);
+  if ((K % 64) != 0) return launch_simple(a, w, c, M, N, K, act, epi, ep, st, np_out);
   auto tiles = [&](int bm, int bn) { return (long long)((M + bm - 1) / bm) * ((N + bn - 1) / bn); };
-#define BT_PIPE(BM, BN, WGM, WGN, NS) launch_pipe<BM, BN, WGM, WGN, NS>(a, w, c, M, N, K, act, epi, ep, st)
+#define BT_PIPE(BM, BN, WGM, WGN, NS) launch_pipe<BM, BN, WGM, WGN, NS>(a, w, c, M, N, K, act, epi, ep, st, np_out)
 #ifdef BT_TUNING
   switch (g_gemm_cfg) {  // tile shapes the sweeps compared
     case 0: return BT_PIPE(128, 128, 2, 2, 4);
@@ -530,7 +638,7 @@ bt_status gemm_dispatch(const bt_half* A, const bt_half* W, int M, int N, int K,
     case 26: return BT_PIPE(128, 256, 2, 4, 3);
     case 27: return BT_PIPE(128, 128, 2, 4, 4);
     case 28: return BT_PIPE(64, 128, 2, 4, 4);
-    case 99: return launch_simple(a, w, c, M, N, K, act, epi, ep, st);
+    case 99: return launch_simple(a, w, c, M, N, K, act, epi, ep, st, np_out);
     default: break;
   }
 #endif
@@ -575,5 +683,5 @@ extern "C" bt_status bt_gemm_bias_act(const bt_half* d_A, const bt_half* d_W, co
   if (d_bias && (reinterpret_cast<uintptr_t>(d_bias) & 7u)) return BT_ERR_INVALID_ARG;
   bt::GemmEpi ep;
   ep.bias = reinterpret_cast<const bt::half_t*>(d_bias);
-  return bt::gemm_dispatch(d_A, d_W, M, N, K, act, bt::EPI_PLAIN, ep, d_C, static_cast<hipStream_t>(stream));
+  return bt::gemm_dispatch(d_A, d_W, M, N, K, act, bt::EPI_PLAIN, ep, d_C, static_cast<hipStream_t>(stream), nullptr);
 }

@@ -6,7 +6,7 @@
 //   -> GEMM2 (+bias, GELU in the epilogue) -> GEMM3 -> bias+residual+LN
 //
 // Folded pipeline (bt_encoder_fwd with fold vectors, 5 launches per layer): the add-bias + residual
-// of Sec. III-C1 moves into the epilogue of GEMM1 / GEMM3, which also accumulates the row sums of
+// of Sec. III-C1 moves into the epilogue of GEMM1 / GEMM3, which also stores partial row sums of
 // the LayerNorm input and writes u = gamma (.) z; the normalisation itself moves into the epilogue
 // of the GEMM that consumes the LayerNorm output (GEMM2, next layer's GEMM0) through
 //   LN(z) W^T + b = rstd (u W^T - mu c) + d,   c = W gamma,  d = W beta + b,
@@ -16,11 +16,11 @@
 
 namespace bt {
 bt_status gemm_dispatch(const bt_half* A, const bt_half* W, int M, int N, int K, bt_act act, int epi,
-                        const GemmEpi& ep, bt_half* C, hipStream_t st);
+                        const GemmEpi& ep, bt_half* C, hipStream_t st, int* np_out);
 bt_status layernorm_dispatch(const bt_half* x, const bt_half* bias, const bt_half* residual, const bt_half* gamma,
                              const bt_half* beta, float eps, int T, int H, bt_half* y, hipStream_t st);
-bt_status ln_finalize_dispatch(const bt_half* u, const float* stats, const bt_half* gamma, const bt_half* beta,
-                               float eps, int T, int H, bt_half* y, hipStream_t st);
+bt_status ln_finalize_dispatch(const bt_half* u, const float2* part, int np, const bt_half* gamma,
+                               const bt_half* beta, float eps, int T, int H, bt_half* y, hipStream_t st);
 bt_status fold_vectors_dispatch(const bt_half* W, const bt_half* gamma, const bt_half* beta, const bt_half* bias,
                                 int N, int K, float* c, float* d, hipStream_t st);
 bt_status mha_dispatch(const bt_half* q, const bt_half* k, const bt_half* v, int64_t row_stride, const bt_half* bq,
@@ -32,12 +32,14 @@ static inline const half_t* hp(const bt_half* p) { return reinterpret_cast<const
 
 // Workspace layout for T tokens (every region 256-byte aligned):
 //   qkv [T,3H] | attn [T,H] | proj [T,H] (GEMM1 and GEMM3 output) | y1 [T,H] | g [T,F] | ping [T,H] |
-//   pong [T,H] | stats1 [T,2] fp32 | stats2 [T,2] fp32
+//   pong [T,H] | part1 [T, H/64] float2 | part2 [T, H/64] float2   (partial row sums of the two LayerNorms;
+//   a column tile of the producing GEMM is at least 64 wide, so H/64 slots per row always suffice)
 struct Workspace {
   bt_half *qkv, *attn, *proj, *y1, *g, *ping, *pong;
-  float *stats1, *stats2;
+  float2 *part1, *part2;
   size_t bytes;
 };
+static inline size_t part_slots(int H) { return (size_t)(H + 63) / 64; }
 
 static Workspace carve(void* ws, int T, int H, int F) {
   Workspace w;
@@ -56,8 +58,8 @@ static Workspace carve(void* ws, int T, int H, int F) {
   w.g = static_cast<bt_half*>(take(t * F * 2));
   w.ping = static_cast<bt_half*>(take(t * H * 2));
   w.pong = static_cast<bt_half*>(take(t * H * 2));
-  w.stats1 = static_cast<float*>(take(t * 2 * sizeof(float)));
-  w.stats2 = static_cast<float*>(take(t * 2 * sizeof(float)));
+  w.part1 = static_cast<float2*>(take(t * part_slots(H) * sizeof(float2)));
+  w.part2 = static_cast<float2*>(take(t * part_slots(H) * sizeof(float2)));
   w.bytes = off;
   return w;
 }
@@ -96,25 +98,25 @@ static bt_status layer_fwd(const bt_layer* l, const bt_half* x, const int32_t* c
   bt_status s;
   GemmEpi ep;
   ep.bias = hp(l->b_qkv);
-  if ((s = gemm_dispatch(x, l->w_qkv, T, 3 * H, H, BT_ACT_NONE, EPI_PLAIN, ep, w.qkv, st)) != BT_OK) return s;
+  if ((s = gemm_dispatch(x, l->w_qkv, T, 3 * H, H, BT_ACT_NONE, EPI_PLAIN, ep, w.qkv, st, nullptr)) != BT_OK) return s;
   const float scale = 1.0f / sqrtf((float)l->head_dim);
   if ((s = mha_dispatch(w.qkv, w.qkv + H, w.qkv + 2 * H, 3 * (int64_t)H, nullptr, nullptr, nullptr, cu, B, T,
                         max_len, l->heads, scale, w.attn, st)) != BT_OK)
     return s;
   ep.bias = nullptr;
-  if ((s = gemm_dispatch(w.attn, l->w_o, T, H, H, BT_ACT_NONE, EPI_PLAIN, ep, w.proj, st)) != BT_OK) return s;
+  if ((s = gemm_dispatch(w.attn, l->w_o, T, H, H, BT_ACT_NONE, EPI_PLAIN, ep, w.proj, st, nullptr)) != BT_OK) return s;
   if ((s = layernorm_dispatch(w.proj, l->b_o, x, l->ln0_g, l->ln0_b, l->ln_eps, T, H, w.y1, st)) != BT_OK) return s;
   const bt_act act = l->gelu_kind == 0 ? BT_ACT_GELU_ERF : BT_ACT_GELU_TANH;
   ep.bias = hp(l->b_1);
-  if ((s = gemm_dispatch(w.y1, l->w_1, T, F, H, act, EPI_PLAIN, ep, w.g, st)) != BT_OK) return s;
+  if ((s = gemm_dispatch(w.y1, l->w_1, T, F, H, act, EPI_PLAIN, ep, w.g, st, nullptr)) != BT_OK) return s;
   ep.bias = nullptr;
-  if ((s = gemm_dispatch(w.g, l->w_2, T, H, F, BT_ACT_NONE, EPI_PLAIN, ep, w.proj, st)) != BT_OK) return s;
+  if ((s = gemm_dispatch(w.g, l->w_2, T, H, F, BT_ACT_NONE, EPI_PLAIN, ep, w.proj, st, nullptr)) != BT_OK) return s;
   return layernorm_dispatch(w.proj, l->b_2, w.y1, l->ln1_g, l->ln1_b, l->ln_eps, T, H, y, st);
 }
 
-// Folded stack.  Between layers the activation lives as (u2 = gamma1 (.) z2, stats2); inside a layer
-// as (u1 = gamma0 (.) z1, stats1).  stats1 is cleared by GEMM0's tile column 0 (its last reader was
-// the previous layer's GEMM3), stats2 by GEMM2's (last readers: this layer's GEMM0 and GEMM1).
+// Folded stack.  Between layers the activation lives as (u2 = gamma1 (.) z2, part2); inside a layer
+// as (u1 = gamma0 (.) z1, part1).  Each part buffer is rewritten in full by the GEMM that produces it
+// (one slot per row and producing wavefront), after its last reader has run: nothing to clear.
 static bt_status stack_fwd_folded(const bt_layer* layers, int n_layers, const float* fold, const bt_half* x,
                                   const int32_t* cu, int B, int T, int max_len, bt_half* y, const Workspace& w,
                                   hipStream_t st) {
@@ -124,6 +126,7 @@ static bt_status stack_fwd_folded(const bt_layer* layers, int n_layers, const fl
   const size_t per_layer = fold_floats(H, F);
   bt_status s;
   const bt_half* in = x;  // layer input: plain x for layer 0, u2 of the previous layer afterwards
+  int np1 = 0, np2 = 0;   // partial sums per row in part1 (LN0 of this layer) / part2 (LN1 of the previous layer)
   for (int i = 0; i < n_layers; ++i) {
     const bt_layer* l = &layers[i];
     const bt_layer* prev = i > 0 ? &layers[i - 1] : nullptr;
@@ -131,45 +134,47 @@ static bt_status stack_fwd_folded(const bt_layer* layers, int n_layers, const fl
     bt_half* u2 = (i & 1) ? w.pong : w.ping;
     {  // GEMM0: QKV projection of LN1_{i-1}(z2) (folded) or of the plain input
       GemmEpi ep;
-      ep.zero_stats = w.stats1;
       if (prev) {
-        ep.ln_stats = w.stats2; ep.fold_c = fv; ep.fold_d = fv + 3 * H; ep.inv_h = inv_h; ep.eps = eps;
+        ep.ln_part = w.part2; ep.ln_np = np2; ep.fold_c = fv; ep.fold_d = fv + 3 * H; ep.inv_h = inv_h; ep.eps = eps;
       } else {
         ep.bias = hp(l->b_qkv);
       }
-      if ((s = gemm_dispatch(in, l->w_qkv, T, 3 * H, H, BT_ACT_NONE, prev ? EPI_FOLD : EPI_PLAIN, ep, w.qkv, st)) !=
-          BT_OK)
+      if ((s = gemm_dispatch(in, l->w_qkv, T, 3 * H, H, BT_ACT_NONE, prev ? EPI_FOLD : EPI_PLAIN, ep, w.qkv, st,
+                             nullptr)) != BT_OK)
         return s;
     }
     if ((s = mha_dispatch(w.qkv, w.qkv + H, w.qkv + 2 * H, 3 * (int64_t)H, nullptr, nullptr, nullptr, cu, B, T,
                           max_len, l->heads, scale, w.attn, st)) != BT_OK)
       return s;
-    {  // GEMM1: z1 = attn W_o^T + b_o + layer input;  u1 = gamma0 (.) z1, stats1 += sums of z1
+    {  // GEMM1: z1 = attn W_o^T + b_o + layer input;  u1 = gamma0 (.) z1, part1 = partial row sums of z1
       GemmEpi ep;
       ep.bias = hp(l->b_o); ep.inv_h = inv_h; ep.eps = eps;
       ep.resid = hp(in);
-      if (prev) { ep.resid_stats = w.stats2; ep.resid_gamma = hp(prev->ln1_g); ep.resid_beta = hp(prev->ln1_b); }
-      ep.out_gamma = hp(l->ln0_g); ep.stats_out = w.stats1;
-      if ((s = gemm_dispatch(w.attn, l->w_o, T, H, H, BT_ACT_NONE, EPI_RESID, ep, w.y1, st)) != BT_OK) return s;
+      if (prev) {
+        ep.resid_part = w.part2; ep.resid_np = np2; ep.resid_gamma = hp(prev->ln1_g); ep.resid_beta = hp(prev->ln1_b);
+      }
+      ep.out_gamma = hp(l->ln0_g); ep.part_out = w.part1;
+      if ((s = gemm_dispatch(w.attn, l->w_o, T, H, H, BT_ACT_NONE, EPI_RESID, ep, w.y1, st, &np1)) != BT_OK) return s;
     }
     {  // GEMM2: GELU(LN0(z1) W_1^T + b_1), LayerNorm folded
       GemmEpi ep;
-      ep.zero_stats = w.stats2;
-      ep.ln_stats = w.stats1; ep.fold_c = fv + 6 * H; ep.fold_d = fv + 6 * H + F; ep.inv_h = inv_h; ep.eps = eps;
+      ep.ln_part = w.part1; ep.ln_np = np1; ep.fold_c = fv + 6 * H; ep.fold_d = fv + 6 * H + F;
+      ep.inv_h = inv_h; ep.eps = eps;
       const bt_act act = l->gelu_kind == 0 ? BT_ACT_GELU_ERF : BT_ACT_GELU_TANH;
-      if ((s = gemm_dispatch(w.y1, l->w_1, T, F, H, act, EPI_FOLD, ep, w.g, st)) != BT_OK) return s;
+      if ((s = gemm_dispatch(w.y1, l->w_1, T, F, H, act, EPI_FOLD, ep, w.g, st, nullptr)) != BT_OK) return s;
     }
-    {  // GEMM3: z2 = g W_2^T + b_2 + LN0(z1);  u2 = gamma1 (.) z2, stats2 += sums of z2
+    {  // GEMM3: z2 = g W_2^T + b_2 + LN0(z1);  u2 = gamma1 (.) z2, part2 = partial row sums of z2
       GemmEpi ep;
       ep.bias = hp(l->b_2); ep.inv_h = inv_h; ep.eps = eps;
-      ep.resid = hp(w.y1); ep.resid_stats = w.stats1; ep.resid_gamma = hp(l->ln0_g); ep.resid_beta = hp(l->ln0_b);
-      ep.out_gamma = hp(l->ln1_g); ep.stats_out = w.stats2;
-      if ((s = gemm_dispatch(w.g, l->w_2, T, H, F, BT_ACT_NONE, EPI_RESID, ep, u2, st)) != BT_OK) return s;
+      ep.resid = hp(w.y1); ep.resid_part = w.part1; ep.resid_np = np1;
+      ep.resid_gamma = hp(l->ln0_g); ep.resid_beta = hp(l->ln0_b);
+      ep.out_gamma = hp(l->ln1_g); ep.part_out = w.part2;
+      if ((s = gemm_dispatch(w.g, l->w_2, T, H, F, BT_ACT_NONE, EPI_RESID, ep, u2, st, &np2)) != BT_OK) return s;
     }
     in = u2;
   }
   const bt_layer* last = &layers[n_layers - 1];
-  return ln_finalize_dispatch(in, w.stats2, last->ln1_g, last->ln1_b, eps, T, H, y, st);
+  return ln_finalize_dispatch(in, w.part2, np2, last->ln1_g, last->ln1_b, eps, T, H, y, st);
 }
 
 static bt_status check_io(const bt_half* x, const int32_t* cu, int B, int T, int max_len, bt_half* y, void* ws) {

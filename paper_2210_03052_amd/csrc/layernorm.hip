@@ -70,19 +70,31 @@ __global__ __launch_bounds__(256) void bias_residual_ln_kernel(const half_t* x,
   }
 }
 
-// Normalisation of a row whose scaled values u = gamma (.) z and sums (sum z, sum z^2) were produced by
-// a GEMM epilogue (EPI_RESID): y = rstd (u - mu gamma) + beta.  Used once, at the end of a stack whose
-// inner LayerNorms are folded into the GEMMs that follow them.
-__global__ __launch_bounds__(256) void ln_finalize_kernel(const half_t* __restrict__ u, const float* __restrict__ stats,
-                                                          const half_t* __restrict__ gamma,
+// Normalisation of a row whose scaled values u = gamma (.) z and partial sums (sum z, sum z^2) were
+// produced by a GEMM epilogue (EPI_RESID): y = rstd (u - mu gamma) + beta.  Used once, at the end of a
+// stack whose inner LayerNorms are folded into the GEMMs that follow them.  The partial sums are added
+// in the order the GEMMs add them (two halves in index order, then the two halves), so the statistics
+// are the ones the folded GEMMs used.
+__global__ __launch_bounds__(256) void ln_finalize_kernel(const half_t* __restrict__ u, const float2* __restrict__ part,
+                                                          int np, const half_t* __restrict__ gamma,
                                                           const half_t* __restrict__ beta, float eps, int T, int H,
                                                           half_t* __restrict__ y) {
   const int lane = threadIdx.x & 63;
   const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
   if (row >= T) return;
   const float inv_h = 1.0f / (float)H;
-  const float mu = stats[2 * (size_t)row] * inv_h;
-  const float rstd = rsqrtf(fmaxf(stats[2 * (size_t)row + 1] * inv_h - mu * mu, 0.f) + eps);
+  const int half_np = (np + 1) >> 1;
+  float a0 = 0.f, b0 = 0.f, a1 = 0.f, b1 = 0.f;
+  for (int q0 = 0; q0 < np; q0 += kWave) {  // lane q holds partial q0+q; added in index order via shuffles
+    const float2 v = q0 + lane < np ? part[(size_t)row * np + q0 + lane] : make_float2(0.f, 0.f);
+    const int n_here = min(np - q0, kWave);
+    for (int q = 0; q < n_here; ++q) {
+      const float x = __shfl(v.x, q, kWave), z = __shfl(v.y, q, kWave);
+      if (q0 + q < half_np) { a0 += x; b0 += z; } else { a1 += x; b1 += z; }
+    }
+  }
+  const float mu = (a0 + a1) * inv_h;
+  const float rstd = rsqrtf(fmaxf((b0 + b1) * inv_h - mu * mu, 0.f) + eps);
   const size_t base = (size_t)row * H;
   for (int c = lane; c < (H >> 3); c += kWave) {
     const half8_t a = *reinterpret_cast<const half8_t*>(u + base + c * 8);
@@ -124,9 +136,9 @@ __global__ __launch_bounds__(256) void fold_vectors_kernel(const half_t* __restr
   }
 }
 
-bt_status ln_finalize_dispatch(const bt_half* u, const float* stats, const bt_half* gamma, const bt_half* beta,
-                               float eps, int T, int H, bt_half* y, hipStream_t st) {
-  ln_finalize_kernel<<<(T + 3) / 4, 256, 0, st>>>(reinterpret_cast<const half_t*>(u), stats,
+bt_status ln_finalize_dispatch(const bt_half* u, const float2* part, int np, const bt_half* gamma,
+                               const bt_half* beta, float eps, int T, int H, bt_half* y, hipStream_t st) {
+  ln_finalize_kernel<<<(T + 3) / 4, 256, 0, st>>>(reinterpret_cast<const half_t*>(u), part, np,
                                                   reinterpret_cast<const half_t*>(gamma),
                                                   reinterpret_cast<const half_t*>(beta), eps, T, H,
                                                   reinterpret_cast<half_t*>(y));
