@@ -53,6 +53,10 @@ def parse():
     ap.add_argument("--fold", action="store_true",
                     help="LayerNorm folded into the GEMM epilogues (5 launches per layer) instead of the plain 7-launch layers")
     ap.add_argument("--no-pipelined", action="store_true", help="skip the two-batches-in-flight throughput point")
+    ap.add_argument("--sweep", action="store_true",
+                    help="instead of the headline run: BERT-base forward over batch {1,8,16} x max_seq 64..1024, "
+                         "packed (mean length 0.6 max) against the same kernels on the padded batch, and the "
+                         "single-layer batch-1 points of Table III; prints one JSON line")
     ap.add_argument("--calibrate-copy", action="store_true", help="also run one 1 GiB device copy (counter scaling)")
     return ap.parse_args()
 
@@ -72,6 +76,69 @@ def time_launches(torch, fn, iters, warm=10):
     return e0.elapsed_time(e1) * 1e3 / iters      # microseconds
 
 
+def sweep(args):
+    """Small-batch / variable-length regime (the axes of the end-to-end figure, Sec. IV-E) and Table III."""
+    import torch
+
+    import paper_2210_03052_amd as bt
+    from paper_2210_03052_amd import inputs as I
+
+    bt.load_library()
+    torch.cuda.set_device(0)
+    base = I.WORKLOADS["bert_base_b16_s256"]
+    layers = [bt.Layer(I.make_layer_params(base, i)) for i in range(base.layers)]
+    H = base.H
+    dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to("cuda:0")
+
+    def forward_ms(B, S, lengths, n_layers, iters):
+        T = int(lengths.sum())
+        x_padded = dev(I.pad_rows(I.make_hidden_packed(base, T), lengths, S))
+        ld = dev(lengths.astype(np.int32))
+        ws = torch.empty(bt.layer_workspace_bytes(layers[0], B * S, B, S), dtype=torch.uint8, device="cuda:0")
+        xp, yp = (torch.empty((B * S, H), dtype=torch.float16, device="cuda:0") for _ in range(2))
+        ypad = torch.empty((B, S, H), dtype=torch.float16, device="cuda:0")
+
+        def step():
+            cu, tok, t = bt.build_offsets(lengths=ld, S=S)
+            x = bt.pack(x_padded, tok, out=xp[:t])
+            y = bt.encoder_fwd(layers[:n_layers], x, cu, S, out=yp[:t], ws=ws)
+            bt.unpack(y, tok, B, S, out=ypad)
+
+        for _ in range(5):
+            step()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(iters):
+            step()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) * 1e3 / iters, T
+
+    rows = []
+    for B in (1, 8, 16):
+        for S in (64, 128, 256, 384, 512, 1024):
+            L = I.uniform_lengths(B, -(-S // 5), S, I.BASE_SEED + 1000 * B + S)       # mean 0.6 S
+            ms_packed, T = forward_ms(B, S, L, base.layers, 50)
+            ms_padded, _ = forward_ms(B, S, np.full(B, S, np.int32), base.layers, 50)
+            rows.append({"batch": B, "max_seq": S, "valid_tokens": T, "alpha": round(T / (B * S), 3),
+                         "ms_packed": round(ms_packed, 4), "ms_all_tokens_valid": round(ms_padded, 4),
+                         "speedup_from_removing_padding": round(ms_padded / ms_packed, 3)})
+    table3 = []
+    for S, paper_ms in ((256, 0.07), (1024, 0.09)):                                    # Table III (A100, FP16)
+        ms, _ = forward_ms(1, S, np.full(1, S, np.int32), 1, 200)
+        x = dev(I.make_hidden_packed(base, S))
+        cu = dev(np.array([0, S], np.int32))
+        y = torch.empty_like(x)
+        ws = torch.empty(bt.layer_workspace_bytes(layers[0], S, 1, S), dtype=torch.uint8, device="cuda:0")
+        us = time_launches(torch, lambda: bt.encoder_layer_fwd(layers[0], x, cu, S, out=y, ws=ws), 200)
+        table3.append({"batch": 1, "seq": S, "layers": 1, "ms_layer_only": round(us / 1e3, 4),
+                       "ms_whole_step": round(ms, 4), "paper_a100_ms": paper_ms,
+                       "note": "layer only = bt_encoder_layer_fwd (7 launches, HIP events); whole step adds "
+                               "build_offsets + pack + unpack"})
+    print(json.dumps({"metric": "ms per BERT-base forward (12 layers, fp16), packed vs all tokens valid",
+                      "unit": "ms", "n_gpus": 1, "dtype": "f16", "data": "synthetic", "higher_is_better": False,
+                      "length_law": "U[ceil(0.2 S), S] (mean 0.6 S)", "sweep": rows, "table3_single_layer": table3}))
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -86,6 +153,8 @@ def main():
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(2)
+    if args.sweep:
+        return sweep(args)
     bt.load_library()                      # raises if libbt.so is not built: no fallback
     torch.cuda.set_device(0)
     wl = I.WORKLOADS[args.workload]
