@@ -38,7 +38,7 @@ __device__ __forceinline__ int xcd_remap(int id, int n) {
 // Row statistics of a LayerNorm travel as partial sums: part[m][p] = (sum z, sum z^2) of row m over the
 // columns of column tile p of the producing GEMM, p < np.  They are written once each and added up
 // in a fixed order by whoever needs the mean and variance: no atomics, bit-reproducible.
-enum { EPI_PLAIN = 0, EPI_FOLD = 1, EPI_RESID = 2 };
+enum { EPI_PLAIN = 0, EPI_FOLD = 1, EPI_RESID = 2, EPI_PARTIAL = 3 };
 struct GemmEpi {
   const half_t* bias = nullptr;  // PLAIN / RESID: [N] or null
   // FOLD: the A operand is u = gamma (.) z of a LayerNorm whose row sums are ln_part
@@ -56,6 +56,10 @@ struct GemmEpi {
   const half_t* out_gamma = nullptr;    // [N]
   float2* part_out = nullptr;           // [M][part_np]
   int part_np = 0;                      // set by the launcher: number of column tiles
+  // PARTIAL (split-K): workgroup (tile, s) multiplies K range [s K/ksplit, (s+1) K/ksplit) and stores its
+  // fp32 accumulators to partial[s][M][N]; whoever consumes the product adds the ksplit slices in order.
+  float* partial = nullptr;
+  int ksplit = 1;
 };
 
 // Butterfly reductions over the 64 lanes of a wavefront.

@@ -217,6 +217,26 @@ __device__ __forceinline__ void store_tile(const float16_t (&acc)[MI][NI], const
   }
 }
 
+// Split-K epilogue: the fp32 accumulators as they are, 16 bytes per lane and column group.
+template <int MI, int NI>
+__device__ __forceinline__ void store_partial(const float16_t (&acc)[MI][NI], float* __restrict__ P, int M, int N,
+                                              int m_base, int n_base, int l32, int hf) {
+#pragma unroll
+  for (int i = 0; i < MI; ++i)
+#pragma unroll
+    for (int j = 0; j < NI; ++j)
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        const int m = m_base + i * 32 + l32, n = n_base + j * 32 + 8 * g + 4 * hf;
+        if (m < M && n < N) {
+          float4_t v;
+#pragma unroll
+          for (int t = 0; t < 4; ++t) v[t] = acc[i][j][4 * g + t];
+          *reinterpret_cast<float4_t*>(P + (size_t)m * N + n) = v;
+        }
+      }
+}
+
 // Mean and 1/sigma of the rows m_base + i*32 + l32 from their partial sums, in two steps so that the
 // loads can be issued ahead of the operand slabs and collected after them:
 //   request_row_sums: the two 32-lane halves each request one half of a row's partials (up to
@@ -319,7 +339,10 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_pipe_kernel(const half_t* 
   // contiguous run of the logical order, and the logical order walks strips of `group_m` tile rows
   // column by column, so the tiles an XCD works on together form a near-square patch of C whose A
   // and W panels fit its private L2 instead of streaming all of W through every L2.
-  const int lin = xcd_remap(blockIdx.x, n_tiles);
+  // split-K (EPI_PARTIAL): the grid holds ksplit copies of the tile grid, copy s works on K slice s
+  const int split = EPI == EPI_PARTIAL ? (int)blockIdx.x / n_tiles : 0;
+  const int k_len = EPI == EPI_PARTIAL ? K / ep.ksplit : K, k_off = split * k_len;
+  const int lin = xcd_remap((int)blockIdx.x - split * n_tiles, n_tiles);
   const int tiles_m = n_tiles / tiles_n;
   const int per_group = group_m * tiles_n;
   const int first_m = (lin / per_group) * group_m;
@@ -352,13 +375,13 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_pipe_kernel(const half_t* 
   for (int q = 0; q < LA; ++q) {
     const int r = (wave * LA + q) * RPI + lane / CPR;
     const int c = (lane % CPR) ^ ((r >> 1) & (CPR - 1));
-    ga[q] = A + (size_t)min(m0 + r, M - 1) * K + c * 8;  // rows past M: clamped reads, never stored
+    ga[q] = A + (size_t)min(m0 + r, M - 1) * K + k_off + c * 8;  // rows past M: clamped reads, never stored
   }
 #pragma unroll
   for (int q = 0; q < LB; ++q) {
     const int r = (wave * LB + q) * RPI + lane / CPR;
     const int c = (lane % CPR) ^ ((r >> 1) & (CPR - 1));
-    gb[q] = W + (size_t)min(n0 + r, N - 1) * K + c * 8;
+    gb[q] = W + (size_t)min(n0 + r, N - 1) * K + k_off + c * 8;
   }
   const uint32_t lds_a = lds_addr(sA) + wave * LA * RPI * BK * 2;  // bytes
   const uint32_t lds_b = lds_addr(sB) + wave * LB * RPI * BK * 2;
@@ -381,7 +404,7 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_pipe_kernel(const half_t* 
   // whole rounds of NS slabs whose stages are compile-time constants, and the last NS-1 slabs, which
   // fetch nothing.  In the steady state and the tail every LDS offset is an immediate, every DMA
   // target a constant and every wait count exact: no branches, no address arithmetic in the loop.
-  const int nk = K / BK;  // >= NS - 1 (checked by the launcher)
+  const int nk = k_len / BK;  // >= NS - 1 (checked by the launcher)
   const int pre = (nk - (NS - 1)) % NS;
   const int rounds = (nk - (NS - 1) - pre) / NS;
   {
@@ -477,9 +500,13 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_pipe_kernel(const half_t* 
     constexpr int J = decltype(j)::value;
     slab(kt + J, j, no{}, integral_constant<bool, J == NS - 2>{}, integral_constant<int, (NS - 3 - J > 0 ? NS - 3 - J : 0)>{});
   });
-  __builtin_amdgcn_s_barrier();  // every wave is done reading the last slab: LDS becomes staging space
-  store_tile<MI, NI, WGN, ACT, EPI>(acc, ep, mu, rstd, rres, tn, wn, wm * WM, red, BM, C, M, N, m0 + wm * WM,
-                                    n0 + wn * WN, lane, smem + wave * STAGE_HALVES);
+  if constexpr (EPI == EPI_PARTIAL) {
+    store_partial<MI, NI>(acc, ep.partial + (size_t)split * M * N, M, N, m0 + wm * WM, n0 + wn * WN, l32, hf);
+  } else {
+    __builtin_amdgcn_s_barrier();  // every wave is done reading the last slab: LDS becomes staging space
+    store_tile<MI, NI, WGN, ACT, EPI>(acc, ep, mu, rstd, rres, tn, wn, wm * WM, red, BM, C, M, N, m0 + wm * WM,
+                                      n0 + wn * WN, lane, smem + wave * STAGE_HALVES);
+  }
 }
 
 // ---------------------------------------------------------------------------
@@ -664,6 +691,38 @@ bt_status gemm_dispatch(const bt_half* A, const bt_half* W, int M, int N, int K,
     default: return BT_PIPE(64, 64, 2, 2, 4);
   }
 #undef BT_PIPE
+}
+
+// Split-K for token counts so small that the tile grid leaves most compute units idle and every tile
+// walks the whole K alone (Sec. IV-E, small batches): how many K slices to use for an M x N x K product
+// (1 = do not split).  Slices times tiles stays within one round of the chip; a slice keeps at least the
+// three slabs the pipeline needs; the slices divide K/64 evenly.  slices * M * N <= kSplitKFloats.
+int gemm_splitk_choice(int M, int N, int K) {
+  if ((K % 64) != 0 || M < 1) return 1;
+  const long long t64 = (long long)((M + 63) / 64) * ((N + 63) / 64);
+  if (t64 > 128) return 1;
+  const int nk = K / 64;
+  int best = 1;
+  for (int s = 2; s <= 8; ++s)
+    if (nk % s == 0 && nk / s >= 3 && t64 * s <= 256) best = s;
+  return best;
+}
+
+bt_status gemm_splitk_dispatch(const bt_half* A, const bt_half* W, int M, int N, int K, int ksplit, float* partial,
+                               hipStream_t st) {
+  constexpr int BM = 64, BN = 64, NS = 4;
+  if (ksplit < 2 || (K % (64 * ksplit)) != 0 || K / ksplit / 64 < NS - 1 || !partial) return BT_ERR_INVALID_ARG;
+  const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
+  const int n_tiles = tiles_m * tiles_n;
+  GemmEpi ep;
+  ep.partial = partial;
+  ep.ksplit = ksplit;
+  int group_m = (int)(sqrt((double)n_tiles / 8.0) + 0.5);
+  group_m = group_m < 1 ? 1 : (group_m > tiles_m ? tiles_m : group_m);
+  gemm_pipe_kernel<BM, BN, 2, 2, NS, BT_ACT_NONE, EPI_PARTIAL><<<dim3((unsigned)(n_tiles * ksplit)), dim3(256), 0, st>>>(
+      reinterpret_cast<const half_t*>(A), reinterpret_cast<const half_t*>(W), ep, nullptr, M, N, K, tiles_n, n_tiles,
+      group_m);
+  return launch_status();
 }
 
 }  // namespace bt

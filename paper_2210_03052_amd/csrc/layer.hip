@@ -17,8 +17,14 @@
 namespace bt {
 bt_status gemm_dispatch(const bt_half* A, const bt_half* W, int M, int N, int K, bt_act act, int epi,
                         const GemmEpi& ep, bt_half* C, hipStream_t st, int* np_out);
-bt_status layernorm_dispatch(const bt_half* x, const bt_half* bias, const bt_half* residual, const bt_half* gamma,
-                             const bt_half* beta, float eps, int T, int H, bt_half* y, hipStream_t st);
+bt_status layernorm_dispatch(const bt_half* x, const float* xpart, int nsplit, const bt_half* bias,
+                             const bt_half* residual, const bt_half* gamma, const bt_half* beta, float eps, int T,
+                             int H, bt_half* y, hipStream_t st);
+int gemm_splitk_choice(int M, int N, int K);
+bt_status gemm_splitk_dispatch(const bt_half* A, const bt_half* W, int M, int N, int K, int ksplit, float* partial,
+                               hipStream_t st);
+// slices * M * N of any split gemm_splitk_choice allows: at most 256 tiles of 64 x 64 outputs
+constexpr size_t kSplitKFloats = (size_t)256 * 64 * 64;
 bt_status ln_finalize_dispatch(const bt_half* u, const float2* part, int np, const bt_half* gamma,
                                const bt_half* beta, float eps, int T, int H, bt_half* y, hipStream_t st);
 bt_status fold_vectors_dispatch(const bt_half* W, const bt_half* gamma, const bt_half* beta, const bt_half* bias,
@@ -34,9 +40,11 @@ static inline const half_t* hp(const bt_half* p) { return reinterpret_cast<const
 //   qkv [T,3H] | attn [T,H] | proj [T,H] (GEMM1 and GEMM3 output) | y1 [T,H] | g [T,F] | ping [T,H] |
 //   pong [T,H] | part1 [T, H/64] float2 | part2 [T, H/64] float2   (partial row sums of the two LayerNorms;
 //   a column tile of the producing GEMM is at least 64 wide, so H/64 slots per row always suffice)
+//   | splitk fp32 [kSplitKFloats]   (K slices of GEMM1 / GEMM3 when the token count is small)
 struct Workspace {
   bt_half *qkv, *attn, *proj, *y1, *g, *ping, *pong;
   float2 *part1, *part2;
+  float* splitk;
   size_t bytes;
 };
 static inline size_t part_slots(int H) { return (size_t)(H + 63) / 64; }
@@ -60,6 +68,7 @@ static Workspace carve(void* ws, int T, int H, int F) {
   w.pong = static_cast<bt_half*>(take(t * H * 2));
   w.part1 = static_cast<float2*>(take(t * part_slots(H) * sizeof(float2)));
   w.part2 = static_cast<float2*>(take(t * part_slots(H) * sizeof(float2)));
+  w.splitk = static_cast<float*>(take(kSplitKFloats * sizeof(float)));
   w.bytes = off;
   return w;
 }
@@ -104,14 +113,29 @@ static bt_status layer_fwd(const bt_layer* l, const bt_half* x, const int32_t* c
                         max_len, l->heads, scale, w.attn, st)) != BT_OK)
     return s;
   ep.bias = nullptr;
-  if ((s = gemm_dispatch(w.attn, l->w_o, T, H, H, BT_ACT_NONE, EPI_PLAIN, ep, w.proj, st, nullptr)) != BT_OK) return s;
-  if ((s = layernorm_dispatch(w.proj, l->b_o, x, l->ln0_g, l->ln0_b, l->ln_eps, T, H, w.y1, st)) != BT_OK) return s;
+  // Output projection and FFN-down: with few tokens the K loop is split over otherwise idle compute
+  // units and the LayerNorm kernel adds the fp32 slices (no reduction kernel, no fp16 rounding in between).
+  const int split1 = gemm_splitk_choice(T, H, H), split3 = gemm_splitk_choice(T, H, F);
+  if (split1 > 1) {
+    if ((s = gemm_splitk_dispatch(w.attn, l->w_o, T, H, H, split1, w.splitk, st)) != BT_OK) return s;
+    if ((s = layernorm_dispatch(nullptr, w.splitk, split1, l->b_o, x, l->ln0_g, l->ln0_b, l->ln_eps, T, H, w.y1, st)) !=
+        BT_OK)
+      return s;
+  } else {
+    if ((s = gemm_dispatch(w.attn, l->w_o, T, H, H, BT_ACT_NONE, EPI_PLAIN, ep, w.proj, st, nullptr)) != BT_OK) return s;
+    if ((s = layernorm_dispatch(w.proj, nullptr, 0, l->b_o, x, l->ln0_g, l->ln0_b, l->ln_eps, T, H, w.y1, st)) != BT_OK)
+      return s;
+  }
   const bt_act act = l->gelu_kind == 0 ? BT_ACT_GELU_ERF : BT_ACT_GELU_TANH;
   ep.bias = hp(l->b_1);
   if ((s = gemm_dispatch(w.y1, l->w_1, T, F, H, act, EPI_PLAIN, ep, w.g, st, nullptr)) != BT_OK) return s;
   ep.bias = nullptr;
+  if (split3 > 1) {
+    if ((s = gemm_splitk_dispatch(w.g, l->w_2, T, H, F, split3, w.splitk, st)) != BT_OK) return s;
+    return layernorm_dispatch(nullptr, w.splitk, split3, l->b_2, w.y1, l->ln1_g, l->ln1_b, l->ln_eps, T, H, y, st);
+  }
   if ((s = gemm_dispatch(w.g, l->w_2, T, H, F, BT_ACT_NONE, EPI_PLAIN, ep, w.proj, st, nullptr)) != BT_OK) return s;
-  return layernorm_dispatch(w.proj, l->b_2, w.y1, l->ln1_g, l->ln1_b, l->ln_eps, T, H, y, st);
+  return layernorm_dispatch(w.proj, nullptr, 0, l->b_2, w.y1, l->ln1_g, l->ln1_b, l->ln_eps, T, H, y, st);
 }
 
 // Folded stack.  Between layers the activation lives as (u2 = gamma1 (.) z2, part2); inside a layer

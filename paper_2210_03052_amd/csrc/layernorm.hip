@@ -7,9 +7,11 @@
 namespace bt {
 
 // CPL = 16-byte chunks per lane; a row has H/8 chunks, chunk c = lane + 64*i.
-template <int CPL>
-__global__ __launch_bounds__(256) void bias_residual_ln_kernel(const half_t* x,
-                                                               const half_t* __restrict__ bias,
+// PART: the GEMM output arrives as nsplit fp32 slices xpart[s][T][H] of a split-K product, added here in
+// slice order (the reduction of the split costs no kernel of its own); otherwise x is fp16 [T,H].
+template <int CPL, bool PART>
+__global__ __launch_bounds__(256) void bias_residual_ln_kernel(const half_t* x, const float* __restrict__ xpart,
+                                                               int nsplit, const half_t* __restrict__ bias,
                                                                const half_t* residual,
                                                                const half_t* __restrict__ gamma,
                                                                const half_t* __restrict__ beta, float eps, int T,
@@ -26,10 +28,22 @@ __global__ __launch_bounds__(256) void bias_residual_ln_kernel(const half_t* x,
   for (int i = 0; i < CPL; ++i) {
     const int c = lane + i * kWave;
     if (c < chunks) {
-      const half8_t a = *reinterpret_cast<const half8_t*>(x + base + c * 8);
       const half8_t r = *reinterpret_cast<const half8_t*>(residual + base + c * 8);
+      if constexpr (PART) {
+        float acc8[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+        for (int sl = 0; sl < nsplit; ++sl) {
+          const float* src = xpart + (size_t)sl * T * H + base + c * 8;
+          const float4_t lo = *reinterpret_cast<const float4_t*>(src), hi = *reinterpret_cast<const float4_t*>(src + 4);
 #pragma unroll
-      for (int e = 0; e < 8; ++e) v[i][e] = (float)a[e] + (float)r[e];
+          for (int e = 0; e < 4; ++e) { acc8[e] += lo[e]; acc8[4 + e] += hi[e]; }
+        }
+#pragma unroll
+        for (int e = 0; e < 8; ++e) v[i][e] = acc8[e] + (float)r[e];
+      } else {
+        const half8_t a = *reinterpret_cast<const half8_t*>(x + base + c * 8);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) v[i][e] = (float)a[e] + (float)r[e];
+      }
       if (bias) {
         const half8_t b = *reinterpret_cast<const half8_t*>(bias + c * 8);
 #pragma unroll
@@ -154,8 +168,9 @@ bt_status fold_vectors_dispatch(const bt_half* W, const bt_half* gamma, const bt
   return launch_status();
 }
 
-bt_status layernorm_dispatch(const bt_half* x, const bt_half* bias, const bt_half* residual, const bt_half* gamma,
-                             const bt_half* beta, float eps, int T, int H, bt_half* y, hipStream_t st) {
+bt_status layernorm_dispatch(const bt_half* x, const float* xpart, int nsplit, const bt_half* bias,
+                             const bt_half* residual, const bt_half* gamma, const bt_half* beta, float eps, int T,
+                             int H, bt_half* y, hipStream_t st) {
   const half_t* px = reinterpret_cast<const half_t*>(x);
   const half_t* pb = reinterpret_cast<const half_t*>(bias);
   const half_t* pr = reinterpret_cast<const half_t*>(residual);
@@ -164,11 +179,17 @@ bt_status layernorm_dispatch(const bt_half* x, const bt_half* bias, const bt_hal
   half_t* py = reinterpret_cast<half_t*>(y);
   const int chunks = H / 8;
   dim3 grid((T + 3) / 4), block(256);
-  if (chunks <= 64) bias_residual_ln_kernel<1><<<grid, block, 0, st>>>(px, pb, pr, pg, pe, eps, T, H, py);
-  else if (chunks <= 128) bias_residual_ln_kernel<2><<<grid, block, 0, st>>>(px, pb, pr, pg, pe, eps, T, H, py);
-  else if (chunks <= 256) bias_residual_ln_kernel<4><<<grid, block, 0, st>>>(px, pb, pr, pg, pe, eps, T, H, py);
-  else if (chunks <= 512) bias_residual_ln_kernel<8><<<grid, block, 0, st>>>(px, pb, pr, pg, pe, eps, T, H, py);
-  else bias_residual_ln_kernel<16><<<grid, block, 0, st>>>(px, pb, pr, pg, pe, eps, T, H, py);
+#define BT_LN(CPL)                                                                                             \
+  do {                                                                                                         \
+    if (xpart) bias_residual_ln_kernel<CPL, true><<<grid, block, 0, st>>>(px, xpart, nsplit, pb, pr, pg, pe, eps, T, H, py); \
+    else bias_residual_ln_kernel<CPL, false><<<grid, block, 0, st>>>(px, xpart, nsplit, pb, pr, pg, pe, eps, T, H, py);     \
+  } while (0)
+  if (chunks <= 64) BT_LN(1);
+  else if (chunks <= 128) BT_LN(2);
+  else if (chunks <= 256) BT_LN(4);
+  else if (chunks <= 512) BT_LN(8);
+  else BT_LN(16);
+#undef BT_LN
   return launch_status();
 }
 
@@ -185,6 +206,6 @@ extern "C" bt_status bt_add_bias_residual_layernorm(const bt_half* d_x, const bt
   if (!bt::aligned16(d_x) || !bt::aligned16(d_residual) || !bt::aligned16(d_gamma) || !bt::aligned16(d_beta) ||
       !bt::aligned16(d_y) || (d_bias && !bt::aligned16(d_bias)))
     return BT_ERR_INVALID_ARG;
-  return bt::layernorm_dispatch(d_x, d_bias, d_residual, d_gamma, d_beta, eps, T, H, d_y,
+  return bt::layernorm_dispatch(d_x, nullptr, 0, d_bias, d_residual, d_gamma, d_beta, eps, T, H, d_y,
                                 static_cast<hipStream_t>(stream));
 }
