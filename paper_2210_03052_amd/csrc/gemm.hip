@@ -95,44 +95,51 @@ __device__ __forceinline__ void static_for(F&& f) {
 // The fp16 tile of this wave is then transposed through a private LDS region (rows padded to WN+8
 // halves) so that global memory is written with 16-byte-per-lane stores, 8 lanes covering 128
 // contiguous bytes of an output row.
+// Per-column epilogue operands of one lane (its 4*NI groups of 4 columns).  They do not depend on the
+// product, so the kernels request them before the K loop: the L2 is cold at kernel start and a fetch
+// issued in the epilogue would sit fully exposed at the end of every tile.  Unused members are dead code.
+template <int NI>
+struct EpiVecs {
+  half4_t bias[NI][4];             // PLAIN / RESID
+  float4_t fc[NI][4], fd[NI][4];   // FOLD: W gamma, W beta + bias
+  half4_t og[NI][4], rg[NI][4], rb[NI][4];  // RESID: output gamma; gamma / beta of a folded residual
+};
+
+template <int NI, int EPI>
+__device__ __forceinline__ void load_epi_vecs(const GemmEpi& ep, int N, int n_base, int hf, EpiVecs<NI>& v) {
+  const half4_t zero = {(half_t)0.f, (half_t)0.f, (half_t)0.f, (half_t)0.f};
+#pragma unroll
+  for (int j = 0; j < NI; ++j)
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+      const int nc = min(n_base + j * 32 + 8 * g + 4 * hf, N - 4);  // columns past N: clamped, never stored
+      if constexpr (EPI == EPI_FOLD) {
+        v.fc[j][g] = *reinterpret_cast<const float4_t*>(ep.fold_c + nc);
+        v.fd[j][g] = *reinterpret_cast<const float4_t*>(ep.fold_d + nc);
+      } else {
+        v.bias[j][g] = ep.bias ? *reinterpret_cast<const half4_t*>(ep.bias + nc) : zero;
+      }
+      if constexpr (EPI == EPI_RESID) {
+        v.og[j][g] = *reinterpret_cast<const half4_t*>(ep.out_gamma + nc);
+        if (ep.resid_part) {
+          v.rg[j][g] = *reinterpret_cast<const half4_t*>(ep.resid_gamma + nc);
+          v.rb[j][g] = *reinterpret_cast<const half4_t*>(ep.resid_beta + nc);
+        }
+      }
+    }
+}
+
 template <int MI, int NI, int WGN, int ACT, int EPI>
-__device__ __forceinline__ void store_tile(const float16_t (&acc)[MI][NI], const GemmEpi& ep, const float (&mu)[MI],
-                                           const float (&rstd)[MI], const half4_t (&rres)[MI][NI][4], int tile_n,
+__device__ __forceinline__ void store_tile(const float16_t (&acc)[MI][NI], const GemmEpi& ep, const EpiVecs<NI>& vec,
+                                           const float (&mu)[MI], const float (&rstd)[MI],
+                                           const half4_t (&rres)[MI][NI][4], int tile_n,
                                            int wn, int row_in_tile, float2* red /* LDS [WGN][rows of the tile] */,
                                            int tile_rows, half_t* __restrict__ C, int M, int N, int m_base,
                                            int n_base, int lane,
                                            half_t* stage /* this wave's LDS region: MI*32 x (NI*32+8) halves */) {
   constexpr int WN = NI * 32, LD = WN + 8;
   const int l32 = lane & 31, hf = lane >> 5;
-  // Per-column operands of this lane's 4*NI column groups, all requested at once (one memory latency
-  // instead of one per group); columns past N are clamped for the load and never stored.
-  float bv[NI][4][4], cv[EPI == EPI_FOLD ? NI : 1][4][4];
-  half4_t og[EPI == EPI_RESID ? NI : 1][4], rg[EPI == EPI_RESID ? NI : 1][4], rb[EPI == EPI_RESID ? NI : 1][4];
   const bool folded_resid = EPI == EPI_RESID && ep.resid_part != nullptr;
-#pragma unroll
-  for (int j = 0; j < NI; ++j)
-#pragma unroll
-    for (int g = 0; g < 4; ++g) {
-      const int nc = min(n_base + j * 32 + 8 * g + 4 * hf, N - 4);
-      if constexpr (EPI == EPI_FOLD) {
-        const float4_t c4 = *reinterpret_cast<const float4_t*>(ep.fold_c + nc);
-        const float4_t d4 = *reinterpret_cast<const float4_t*>(ep.fold_d + nc);
-#pragma unroll
-        for (int t = 0; t < 4; ++t) { cv[j][g][t] = c4[t]; bv[j][g][t] = d4[t]; }
-      } else {
-        half4_t b4 = {(half_t)0.f, (half_t)0.f, (half_t)0.f, (half_t)0.f};
-        if (ep.bias) b4 = *reinterpret_cast<const half4_t*>(ep.bias + nc);
-#pragma unroll
-        for (int t = 0; t < 4; ++t) bv[j][g][t] = (float)b4[t];
-      }
-      if constexpr (EPI == EPI_RESID) {
-        og[j][g] = *reinterpret_cast<const half4_t*>(ep.out_gamma + nc);
-        if (folded_resid) {
-          rg[j][g] = *reinterpret_cast<const half4_t*>(ep.resid_gamma + nc);
-          rb[j][g] = *reinterpret_cast<const half4_t*>(ep.resid_beta + nc);
-        }
-      }
-    }
   float s0[MI], s1[MI];
 #pragma unroll
   for (int i = 0; i < MI; ++i) s0[i] = s1[i] = 0.f;
@@ -150,10 +157,10 @@ __device__ __forceinline__ void store_tile(const float16_t (&acc)[MI][NI], const
         for (int t = 0; t < 4; ++t) v[t] = acc[i][j][4 * g + t];
         if constexpr (EPI == EPI_FOLD) {
 #pragma unroll
-          for (int t = 0; t < 4; ++t) v[t] = __builtin_fmaf(rstd[i], v[t] - mu[i] * cv[j][g][t], bv[j][g][t]);
+          for (int t = 0; t < 4; ++t) v[t] = __builtin_fmaf(rstd[i], v[t] - mu[i] * vec.fc[j][g][t], vec.fd[j][g][t]);
         } else {
 #pragma unroll
-          for (int t = 0; t < 4; ++t) v[t] += bv[j][g][t];
+          for (int t = 0; t < 4; ++t) v[t] += (float)vec.bias[j][g][t];
         }
         if constexpr (EPI == EPI_RESID) {
           const half4_t r4 = rres[i][j][g];
@@ -161,12 +168,12 @@ __device__ __forceinline__ void store_tile(const float16_t (&acc)[MI][NI], const
 #pragma unroll
           for (int t = 0; t < 4; ++t) {
             const float r = folded_resid
-                                ? __builtin_fmaf(rstd[i], (float)r4[t] - mu[i] * (float)rg[j][g][t], (float)rb[j][g][t])
+                                ? __builtin_fmaf(rstd[i], (float)r4[t] - mu[i] * (float)vec.rg[j][g][t], (float)vec.rb[j][g][t])
                                 : (float)r4[t];
             v[t] = ok ? v[t] + r : 0.f;
             s0[i] += v[t];
             s1[i] = __builtin_fmaf(v[t], v[t], s1[i]);
-            v[t] *= (float)og[j][g][t];
+            v[t] *= (float)vec.og[j][g][t];
           }
         } else {
 #pragma unroll
@@ -360,6 +367,8 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_pipe_kernel(const half_t* 
   // row sums behind mu / rstd (EPI_FOLD: rows of A; EPI_RESID: rows of a folded residual).
   half4_t rres[MI][NI][4];  // dead (and removed by the compiler) in the other epilogue forms
   if constexpr (EPI == EPI_RESID) load_resid<MI, NI>(ep.resid, M, N, m0 + wm * WM, n0 + wn * WN, l32, hf, rres);
+  EpiVecs<NI> vec;
+  if constexpr (EPI != EPI_PARTIAL) load_epi_vecs<NI, EPI>(ep, N, n0 + wn * WN, hf, vec);
   __shared__ float2 red[EPI == EPI_RESID ? WGN * BM : 1];
   float2 psum[MI][kMaxHalfParts];
   const float2* const stat_part = EPI == EPI_FOLD ? ep.ln_part : (EPI == EPI_RESID ? ep.resid_part : nullptr);
@@ -504,7 +513,7 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_pipe_kernel(const half_t* 
     store_partial<MI, NI>(acc, ep.partial + (size_t)split * M * N, M, N, m0 + wm * WM, n0 + wn * WN, l32, hf);
   } else {
     __builtin_amdgcn_s_barrier();  // every wave is done reading the last slab: LDS becomes staging space
-    store_tile<MI, NI, WGN, ACT, EPI>(acc, ep, mu, rstd, rres, tn, wn, wm * WM, red, BM, C, M, N, m0 + wm * WM,
+    store_tile<MI, NI, WGN, ACT, EPI>(acc, ep, vec, mu, rstd, rres, tn, wn, wm * WM, red, BM, C, M, N, m0 + wm * WM,
                                       n0 + wn * WN, lane, smem + wave * STAGE_HALVES);
   }
 }
@@ -566,7 +575,9 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_simple_kernel(const half_t*
     finish_row_sums<1>(stat_part, stat_np, M, m0 + wm * 32, l32, hf, ep.inv_h, ep.eps, psum, mu, rstd);
   }
   if constexpr (EPI == EPI_RESID) load_resid<1, 1>(ep.resid, M, N, m0 + wm * 32, n0 + wn * 32, l32, hf, rres);
-  store_tile<1, 1, 2, ACT, EPI>(acc, ep, mu, rstd, rres, tn, wn, wm * 32, red, BM, C, M, N, m0 + wm * 32, n0 + wn * 32,
+  EpiVecs<1> vec;
+  load_epi_vecs<1, EPI>(ep, N, n0 + wn * 32, hf, vec);
+  store_tile<1, 1, 2, ACT, EPI>(acc, ep, vec, mu, rstd, rres, tn, wn, wm * 32, red, BM, C, M, N, m0 + wm * 32, n0 + wn * 32,
                                 lane, (wave < 2 ? sA : sB) + (wave & 1) * 32 * 40);
 }
 
