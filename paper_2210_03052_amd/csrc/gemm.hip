@@ -659,19 +659,11 @@ bt_status gemm_dispatch(const bt_half* A, const bt_half* W, int M, int N, int K,
 #ifdef BT_TUNING
   switch (g_gemm_cfg) {  // tile shapes the sweeps compared
     case 0: return BT_PIPE(128, 128, 2, 2, 4);
-    case 1: return BT_PIPE(128, 128, 2, 2, 2);
-    case 2: return BT_PIPE(128, 128, 2, 2, 3);
     case 3: return BT_PIPE(128, 64, 2, 2, 4);
-    case 6: return BT_PIPE(256, 128, 2, 2, 3);
-    case 7: return BT_PIPE(192, 128, 2, 2, 3);
-    case 14: return BT_PIPE(128, 128, 4, 2, 4);
-    case 15: return BT_PIPE(256, 256, 4, 2, 2);
-    case 17: return BT_PIPE(256, 64, 4, 2, 4);
-    case 18: return BT_PIPE(256, 192, 4, 2, 2);
     case 5: return BT_PIPE(64, 64, 2, 2, 4);
+    case 6: return BT_PIPE(256, 128, 2, 2, 3);
     case 11: return BT_PIPE(256, 128, 4, 2, 3);
     case 16: return BT_PIPE(128, 64, 4, 2, 4);
-    case 20: return BT_PIPE(128, 64, 4, 2, 5);
     case 25: return BT_PIPE(192, 128, 2, 4, 3);
     case 26: return BT_PIPE(128, 256, 2, 4, 3);
     case 27: return BT_PIPE(128, 128, 2, 4, 4);
