@@ -110,6 +110,24 @@ def test_unpack_all_padding(bt):
 
 
 # ------------------------------------------------------------------ GEMM + epilogue
+@pytest.mark.parametrize("M,N", [(100, 768), (2308, 768), (2308, 2304), (2308, 3072)])
+def test_gemm_slab_schedule_all_residues(bt, M, N):
+    """The K loop splits its K/64 slabs into leading slabs, whole rounds of the pipeline depth and a tail;
+    every residue of K/64 modulo the depth (3 or 4 stages, one tile shape per (M,N) here) and the
+    K < depth fallback must give the same product.  Ragged M, and N not a multiple of the tile."""
+    rng = np.random.default_rng(M * 7 + N)
+    Kmax = 13 * 64
+    a = rng.normal(0, 1, (M, Kmax)).astype(np.float16)
+    w = rng.normal(0, 0.05, (N + 8, Kmax)).astype(np.float16)
+    for nk in range(1, 14):
+        K = nk * 64
+        ak, wk = np.ascontiguousarray(a[:, :K]), np.ascontiguousarray(w[:, :K])
+        got = host(bt.gemm_bias_act(dev(ak), dev(wk), None, 0)).astype(np.float64)
+        ref = ak.astype(np.float64) @ wk.astype(np.float64).T
+        err = np.abs(got - ref).max()
+        assert err <= 2e-3 * max(1.0, np.abs(ref).max()), (nk, err)
+
+
 def _gelu_tanh64(x):
     return 0.5 * x * (1 + np.tanh(np.sqrt(2 / np.pi) * (x + 0.044715 * x ** 3)))
 
@@ -117,7 +135,8 @@ def _gelu_tanh64(x):
 @pytest.mark.parametrize("M,N,K,act,bias", [
     (1, 8, 8, 0, False), (5, 16, 40, 0, True), (77, 72, 200, 1, True), (150, 2304, 768, 0, True),
     (129, 768, 3072, 0, False), (300, 3072, 768, 1, True), (2456, 768, 768, 0, True), (2456, 3072, 768, 2, True),
-    (1000, 1024, 4096, 0, True), (4710, 4096, 1024, 1, True)])
+    (1000, 1024, 4096, 0, True), (4710, 4096, 1024, 1, True), (2308, 2304, 768, 0, True), (4648, 1024, 4096, 0, False),
+    (2305, 2312, 832, 1, True)])
 def test_gemm_bias_act(bt, M, N, K, act, bias):
     rng = np.random.default_rng(M + N + K)
     a = rng.normal(0, 1, (M, K)).astype(np.float16)
