@@ -171,6 +171,25 @@ def test_bias_residual_layernorm(bt, T, H, bias):
     assert np.abs(got.astype(np.float64) - ref).max() <= 4e-3
 
 
+def test_layernorm_streaming_shape_sampled(bt):
+    """The launch configuration the bench times at 262 144 tokens (tensors larger than the memory-side
+    cache: the kernel switches to non-temporal loads and stores): sampled rows against the oracle."""
+    import torch
+    T, H = 262144, 768
+    g = torch.Generator(device="cuda:0").manual_seed(2210)
+    x = torch.randn((T, H), generator=g, device="cuda:0", dtype=torch.float16)
+    r = torch.randn((T, H), generator=g, device="cuda:0", dtype=torch.float16)
+    rng = np.random.default_rng(3052)
+    b, ga, be = (rng.normal(m, 0.3, H).astype(np.float16) for m in (0.0, 1.0, 0.0))
+    y = bt.add_bias_residual_layernorm(x, dev(b), r, dev(ga), dev(be), 1e-12)
+    rows = np.unique(np.concatenate([[0, 1, T - 1, T - 2], rng.integers(0, T, 60)]))
+    idx = torch.from_numpy(rows).to("cuda:0")
+    xs, rs, ys = (host(t[idx]).astype(np.float64) for t in (x, r, y))
+    ref = O.layer_norm(xs + rs + b.astype(np.float64), ga.astype(np.float64), be.astype(np.float64), 1e-12)
+    assert np.abs(ys - ref).max() <= 4e-3 + 2 ** -10 * np.abs(ref).max()
+
+
+
 # ------------------------------------------------------------------ variable-length MHA
 def _mha_case(bt, lengths, heads, seed, with_bias=False, max_len=None):
     lengths = np.asarray(lengths, np.int32)
