@@ -209,6 +209,26 @@ def main():
         "useful_tflops_per_s": round(flops_step / (ms_per_step * 1e-3) / 1e12, 2),
     }
 
+    # ---------------- the same step with pack / unpack fused into the first / last kernels (extra point)
+    if fold is None:
+        def step_fused():
+            cu, tok, t = bt.build_offsets(lengths=lengths_d, S=wl.S)
+            bt.encoder_fwd_padded(layers, x_padded, tok, cu, out=y_padded2, ws=ws)
+
+        y_padded2 = torch.empty_like(y_padded)
+        for _ in range(max(args.warmup // 2, 2)):
+            step_fused()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            step_fused()
+        torch.cuda.synchronize()
+        dtf = time.perf_counter() - t0
+        out["fused_pack_unpack"] = {"value": round(wl.B * args.steps / dtf, 1), "unit": "sequences/s",
+                                    "ms_per_step": round(dtf * 1e3 / args.steps, 4),
+                                    "step": "build_offsets+encoder_fwd_padded",
+                                    "outputs_equal": bool(torch.equal(y_padded2, y_padded))}
+
     # ---------------- throughput with two batches in flight (extra point, not `value`)
     # One batch at a time leaves the GPU idle at every kernel boundary (~2.5 us per dependent launch) and
     # while the host waits for the token count in build_offsets.  A server keeps a second batch in flight

@@ -200,6 +200,20 @@ bt_status bt_encoder_fwd(const bt_layer* layers, int n_layers, const float* d_fo
                          const int32_t* d_cu_seqlens, int B, int T, int max_len, bt_half* d_y,
                          void* d_ws, size_t ws_bytes, bt_stream stream);
 
+/*
+ * The same stack on PADDED tensors, with the zero-padding algorithm of Sec. III-D fused into the
+ * neighbouring kernels instead of running as kernels of its own: the first GEMM and the first
+ * residual read gather their rows of d_x_padded [B*S,H] through d_token_idx (pack), the last
+ * LayerNorm scatters its rows into d_y_padded [B*S,H] and zero-fills every padding row (unpack).
+ * d_token_idx / d_cu_seqlens / T come from bt_build_offsets for the same B and S.  Results are
+ * bit-identical to bt_pack + bt_encoder_fwd (without fold vectors) + bt_unpack; two launches fewer.
+ * d_x_padded is not modified and must not alias d_y_padded.  T == 0 zero-fills d_y_padded.
+ * Workspace as for bt_encoder_fwd (bt_layer_workspace_bytes with this T).
+ */
+bt_status bt_encoder_fwd_padded(const bt_layer* layers, int n_layers, const bt_half* d_x_padded,
+                                const int32_t* d_token_idx, const int32_t* d_cu_seqlens, int B, int T, int S,
+                                bt_half* d_y_padded, void* d_ws, size_t ws_bytes, bt_stream stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -58,6 +58,9 @@ _SIGNATURES = {
     "bt_encoder_prepare": (_c.c_int, [_c.POINTER(bt_layer), _c.c_int, _c.c_void_p, _c.c_size_t, _c.c_void_p]),
     "bt_encoder_fwd": (_c.c_int, [_c.POINTER(bt_layer), _c.c_int, _c.c_void_p, _c.c_void_p, _c.c_void_p, _c.c_int,
                                   _c.c_int, _c.c_int, _c.c_void_p, _c.c_void_p, _c.c_size_t, _c.c_void_p]),
+    "bt_encoder_fwd_padded": (_c.c_int, [_c.POINTER(bt_layer), _c.c_int, _c.c_void_p, _c.c_void_p, _c.c_void_p,
+                                         _c.c_int, _c.c_int, _c.c_int, _c.c_void_p, _c.c_void_p, _c.c_size_t,
+                                         _c.c_void_p]),
 }
 EXPORTED = tuple(_SIGNATURES)
 
@@ -318,4 +321,23 @@ def encoder_fwd(layers, x, cu_seqlens, max_len, out=None, ws=None, fold=None):
     arr = (bt_layer * len(layers))(*[l.desc for l in layers])
     _call("bt_encoder_fwd", arr, len(layers), _ptr(fold), _ptr(x), _ptr(cu_seqlens), B, T, int(max_len), _ptr(out),
           _ptr(ws), ws.numel(), _stream())
+    return out
+
+
+def encoder_fwd_padded(layers, x_padded, token_idx, cu_seqlens, out=None, ws=None):
+    """bt_encoder_fwd_padded: padded fp16 [B,S,H] in, padded fp16 [B,S,H] out (pads zero); pack and
+    unpack run inside the first and last kernels of the stack."""
+    torch = _torch()
+    _chk(x_padded, torch.float16, "x_padded", 3)
+    _chk(token_idx, torch.int32, "token_idx", 1)
+    _chk(cu_seqlens, torch.int32, "cu_seqlens", 1)
+    B, S, _ = x_padded.shape
+    T = token_idx.shape[0]
+    if out is None:
+        out = torch.empty_like(x_padded)
+    if ws is None:
+        ws, _ = _workspace(layers[0], max(T, 1), B, S, x_padded.device)
+    arr = (bt_layer * len(layers))(*[l.desc for l in layers])
+    _call("bt_encoder_fwd_padded", arr, len(layers), _ptr(x_padded), _ptr(token_idx), _ptr(cu_seqlens), B, T, S,
+          _ptr(out), _ptr(ws), ws.numel(), _stream())
     return out

@@ -40,7 +40,8 @@ __device__ __forceinline__ int xcd_remap(int id, int n) {
 // in a fixed order by whoever needs the mean and variance: no atomics, bit-reproducible.
 enum { EPI_PLAIN = 0, EPI_FOLD = 1, EPI_RESID = 2, EPI_PARTIAL = 3 };
 struct GemmEpi {
-  const half_t* bias = nullptr;  // PLAIN / RESID: [N] or null
+  const int32_t* a_rows = nullptr;  // any form: row m of the product reads row a_rows[m] of A (pack fused into the load)
+  const half_t* bias = nullptr;     // PLAIN / RESID: [N] or null
   // FOLD: the A operand is u = gamma (.) z of a LayerNorm whose row sums are ln_part
   const float2* ln_part = nullptr;  // [M][ln_np]
   int ln_np = 0;

@@ -384,7 +384,8 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_pipe_kernel(const half_t* 
   for (int q = 0; q < LA; ++q) {
     const int r = (wave * LA + q) * RPI + lane / CPR;
     const int c = (lane % CPR) ^ ((r >> 1) & (CPR - 1));
-    ga[q] = A + (size_t)min(m0 + r, M - 1) * K + k_off + c * 8;  // rows past M: clamped reads, never stored
+    const int ar = min(m0 + r, M - 1);  // rows past M: clamped reads, never stored
+    ga[q] = A + (size_t)(ep.a_rows ? ep.a_rows[ar] : ar) * K + k_off + c * 8;
   }
 #pragma unroll
   for (int q = 0; q < LB; ++q) {
@@ -544,7 +545,8 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_simple_kernel(const half_t*
 #pragma unroll
     for (int i = 0; i < CH; ++i) {
       const int row = (tid >> 3) + i * (kGemmThreads / 8);
-      ra[i] = in ? *reinterpret_cast<const uint4_t*>(A + (size_t)min(m0 + row, M - 1) * K + k0 + kc) : zero4;
+      const int ar = min(m0 + row, M - 1);
+      ra[i] = in ? *reinterpret_cast<const uint4_t*>(A + (size_t)(ep.a_rows ? ep.a_rows[ar] : ar) * K + k0 + kc) : zero4;
       rb[i] = in ? *reinterpret_cast<const uint4_t*>(W + (size_t)min(n0 + row, N - 1) * K + k0 + kc) : zero4;
     }
     __syncthreads();

@@ -19,7 +19,8 @@ bt_status gemm_dispatch(const bt_half* A, const bt_half* W, int M, int N, int K,
                         const GemmEpi& ep, bt_half* C, hipStream_t st, int* np_out);
 bt_status layernorm_dispatch(const bt_half* x, const float* xpart, int nsplit, const bt_half* bias,
                              const bt_half* residual, const bt_half* gamma, const bt_half* beta, float eps, int T,
-                             int H, bt_half* y, hipStream_t st);
+                             int H, bt_half* y, hipStream_t st, const int32_t* res_rows, const int32_t* out_idx,
+                             int out_rows);
 int gemm_splitk_choice(int M, int N, int K);
 bt_status gemm_splitk_dispatch(const bt_half* A, const bt_half* W, int M, int N, int K, int ksplit, float* partial,
                                hipStream_t st);
@@ -101,29 +102,39 @@ static bt_status check_stack(const bt_layer* layers, int n_layers) {
   return BT_OK;
 }
 
+// Where a layer's input rows come from and where its output rows go.  Defaults: packed in, packed out.
+struct LayerIo {
+  const int32_t* in_rows = nullptr;   // x is the PADDED tensor; packed row i is its row in_rows[i] (first layer)
+  const int32_t* out_idx = nullptr;   // y is the PADDED tensor [out_rows, H]; packed row i goes to row out_idx[i],
+  int out_rows = 0;                   // every other row is zero-filled (last layer)
+};
+
 static bt_status layer_fwd(const bt_layer* l, const bt_half* x, const int32_t* cu, int B, int T, int max_len,
-                           bt_half* y, const Workspace& w, hipStream_t st) {
+                           bt_half* y, const Workspace& w, hipStream_t st, const LayerIo& io = LayerIo()) {
   const int H = l->H, F = l->F;
   bt_status s;
   GemmEpi ep;
+  ep.a_rows = io.in_rows;
   ep.bias = hp(l->b_qkv);
   if ((s = gemm_dispatch(x, l->w_qkv, T, 3 * H, H, BT_ACT_NONE, EPI_PLAIN, ep, w.qkv, st, nullptr)) != BT_OK) return s;
   const float scale = 1.0f / sqrtf((float)l->head_dim);
   if ((s = mha_dispatch(w.qkv, w.qkv + H, w.qkv + 2 * H, 3 * (int64_t)H, nullptr, nullptr, nullptr, cu, B, T,
                         max_len, l->heads, scale, w.attn, st)) != BT_OK)
     return s;
+  ep.a_rows = nullptr;
   ep.bias = nullptr;
   // Output projection and FFN-down: with few tokens the K loop is split over otherwise idle compute
   // units and the LayerNorm kernel adds the fp32 slices (no reduction kernel, no fp16 rounding in between).
   const int split1 = gemm_splitk_choice(T, H, H), split3 = gemm_splitk_choice(T, H, F);
   if (split1 > 1) {
     if ((s = gemm_splitk_dispatch(w.attn, l->w_o, T, H, H, split1, w.splitk, st)) != BT_OK) return s;
-    if ((s = layernorm_dispatch(nullptr, w.splitk, split1, l->b_o, x, l->ln0_g, l->ln0_b, l->ln_eps, T, H, w.y1, st)) !=
-        BT_OK)
+    if ((s = layernorm_dispatch(nullptr, w.splitk, split1, l->b_o, x, l->ln0_g, l->ln0_b, l->ln_eps, T, H, w.y1, st,
+                                io.in_rows, nullptr, 0)) != BT_OK)
       return s;
   } else {
     if ((s = gemm_dispatch(w.attn, l->w_o, T, H, H, BT_ACT_NONE, EPI_PLAIN, ep, w.proj, st, nullptr)) != BT_OK) return s;
-    if ((s = layernorm_dispatch(w.proj, nullptr, 0, l->b_o, x, l->ln0_g, l->ln0_b, l->ln_eps, T, H, w.y1, st)) != BT_OK)
+    if ((s = layernorm_dispatch(w.proj, nullptr, 0, l->b_o, x, l->ln0_g, l->ln0_b, l->ln_eps, T, H, w.y1, st,
+                                io.in_rows, nullptr, 0)) != BT_OK)
       return s;
   }
   const bt_act act = l->gelu_kind == 0 ? BT_ACT_GELU_ERF : BT_ACT_GELU_TANH;
@@ -132,10 +143,12 @@ static bt_status layer_fwd(const bt_layer* l, const bt_half* x, const int32_t* c
   ep.bias = nullptr;
   if (split3 > 1) {
     if ((s = gemm_splitk_dispatch(w.g, l->w_2, T, H, F, split3, w.splitk, st)) != BT_OK) return s;
-    return layernorm_dispatch(nullptr, w.splitk, split3, l->b_2, w.y1, l->ln1_g, l->ln1_b, l->ln_eps, T, H, y, st);
+    return layernorm_dispatch(nullptr, w.splitk, split3, l->b_2, w.y1, l->ln1_g, l->ln1_b, l->ln_eps, T, H, y, st, nullptr,
+                              io.out_idx, io.out_rows);
   }
   if ((s = gemm_dispatch(w.g, l->w_2, T, H, F, BT_ACT_NONE, EPI_PLAIN, ep, w.proj, st, nullptr)) != BT_OK) return s;
-  return layernorm_dispatch(w.proj, nullptr, 0, l->b_2, w.y1, l->ln1_g, l->ln1_b, l->ln_eps, T, H, y, st);
+  return layernorm_dispatch(w.proj, nullptr, 0, l->b_2, w.y1, l->ln1_g, l->ln1_b, l->ln_eps, T, H, y, st, nullptr,
+                            io.out_idx, io.out_rows);
 }
 
 // Folded stack.  Between layers the activation lives as (u2 = gamma1 (.) z2, part2); inside a layer
@@ -288,6 +301,38 @@ extern "C" bt_status bt_encoder_fwd(const bt_layer* layers, int n_layers, const 
   for (int i = 0; i < n_layers; ++i) {
     bt_half* outp = (i == n_layers - 1) ? d_y : ((i & 1) ? w.pong : w.ping);
     if ((s = layer_fwd(&layers[i], in, d_cu_seqlens, B, T, max_len, outp, w, st)) != BT_OK) return s;
+    in = outp;
+  }
+  return BT_OK;
+}
+
+extern "C" bt_status bt_encoder_fwd_padded(const bt_layer* layers, int n_layers, const bt_half* d_x_padded,
+                                           const int32_t* d_token_idx, const int32_t* d_cu_seqlens, int B, int T,
+                                           int S, bt_half* d_y_padded, void* d_ws, size_t ws_bytes,
+                                           bt_stream stream) {
+  bt_status s = check_stack(layers, n_layers);
+  if (s != BT_OK) return s;
+  if (B < 0 || T < 0 || S < 0) return BT_ERR_INVALID_ARG;
+  if (B == 0 || S == 0) return BT_OK;
+  if ((int64_t)T > (int64_t)B * S || (int64_t)B * S >= (int64_t)INT32_MAX) return BT_ERR_INVALID_ARG;
+  if (!d_x_padded || !d_y_padded || d_x_padded == d_y_padded || !aligned16(d_x_padded) || !aligned16(d_y_padded))
+    return BT_ERR_INVALID_ARG;
+  if (T > 0 && (!d_token_idx || !d_cu_seqlens)) return BT_ERR_INVALID_ARG;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  const int H = layers[0].H;
+  if (T == 0)  // nothing valid: the output is all padding (the unpack kernel zero-fills; no memset node for graphs)
+    return bt_unpack(d_x_padded, d_token_idx, 0, B, S, H, d_y_padded, stream);
+  if (!d_ws || (reinterpret_cast<uintptr_t>(d_ws) & 255u)) return BT_ERR_WORKSPACE;
+  const Workspace w = carve(d_ws, T, H, layers[0].F);
+  if (ws_bytes < w.bytes) return BT_ERR_WORKSPACE;
+  const bt_half* in = d_x_padded;
+  for (int i = 0; i < n_layers; ++i) {
+    const bool last = i == n_layers - 1;
+    LayerIo io;
+    if (i == 0) io.in_rows = d_token_idx;
+    if (last) { io.out_idx = d_token_idx; io.out_rows = B * S; }
+    bt_half* outp = last ? d_y_padded : ((i & 1) ? w.pong : w.ping);
+    if ((s = layer_fwd(&layers[i], in, d_cu_seqlens, B, T, S, outp, w, st, io)) != BT_OK) return s;
     in = outp;
   }
   return BT_OK;

@@ -17,12 +17,37 @@ __global__ __launch_bounds__(256) void bias_residual_ln_kernel(const half_t* x, 
                                                                const half_t* residual,
                                                                const half_t* __restrict__ gamma,
                                                                const half_t* __restrict__ beta, float eps, int T,
-                                                               int H, half_t* y) {
+                                                               int H, half_t* y, const int32_t* __restrict__ res_rows,
+                                                               const int32_t* __restrict__ out_idx, int out_rows) {
+  // res_rows: the residual of packed row i is row res_rows[i] of `residual` (pack fused into the read).
+  // out_idx: y is the padded tensor [out_rows, H]; this wave owns padded row r, which is packed row
+  //   `lo` if out_idx[lo] == r (out_idx is increasing: uniform binary search) and a zero row otherwise
+  //   (unpack fused into the store, Sec. III-D).
   const int lane = threadIdx.x & 63;
-  const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
-  if (row >= T) return;
+  int row = blockIdx.x * 4 + (threadIdx.x >> 6);
   const int chunks = H >> 3;
+  size_t obase;
+  if (out_idx) {
+    const int r = row;
+    if (r >= out_rows) return;
+    int lo = 0, hi = T;
+    while (lo < hi) {
+      const int mid = (lo + hi) >> 1;
+      if (out_idx[mid] < r) lo = mid + 1; else hi = mid;
+    }
+    obase = (size_t)r * H;
+    if (!(lo < T && out_idx[lo] == r)) {
+      const half8_t z = {(half_t)0.f, (half_t)0.f, (half_t)0.f, (half_t)0.f, (half_t)0.f, (half_t)0.f, (half_t)0.f, (half_t)0.f};
+      for (int c = lane; c < chunks; c += kWave) *reinterpret_cast<half8_t*>(y + obase + c * 8) = z;
+      return;
+    }
+    row = lo;
+  } else {
+    if (row >= T) return;
+    obase = (size_t)row * H;
+  }
   const size_t base = (size_t)row * H;
+  const size_t rbase = res_rows ? (size_t)res_rows[row] * H : base;
 
   float v[CPL][8];
   float sum = 0.f;
@@ -30,8 +55,8 @@ __global__ __launch_bounds__(256) void bias_residual_ln_kernel(const half_t* x, 
   for (int i = 0; i < CPL; ++i) {
     const int c = lane + i * kWave;
     if (c < chunks) {
-      const half8_t r = STREAM ? __builtin_nontemporal_load(reinterpret_cast<const half8_t*>(residual + base + c * 8))
-                               : *reinterpret_cast<const half8_t*>(residual + base + c * 8);
+      const half8_t r = STREAM ? __builtin_nontemporal_load(reinterpret_cast<const half8_t*>(residual + rbase + c * 8))
+                               : *reinterpret_cast<const half8_t*>(residual + rbase + c * 8);
       if constexpr (PART) {
         float acc8[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
         for (int sl = 0; sl < nsplit; ++sl) {
@@ -83,8 +108,8 @@ __global__ __launch_bounds__(256) void bias_residual_ln_kernel(const half_t* x, 
       half8_t o;
 #pragma unroll
       for (int e = 0; e < 8; ++e) o[e] = (half_t)((v[i][e] - mean) * rstd * (float)g[e] + (float)b[e]);
-      if (STREAM) __builtin_nontemporal_store(o, reinterpret_cast<half8_t*>(y + base + c * 8));
-      else *reinterpret_cast<half8_t*>(y + base + c * 8) = o;
+      if (STREAM) __builtin_nontemporal_store(o, reinterpret_cast<half8_t*>(y + obase + c * 8));
+      else *reinterpret_cast<half8_t*>(y + obase + c * 8) = o;
     }
   }
 }
@@ -175,7 +200,8 @@ bt_status fold_vectors_dispatch(const bt_half* W, const bt_half* gamma, const bt
 
 bt_status layernorm_dispatch(const bt_half* x, const float* xpart, int nsplit, const bt_half* bias,
                              const bt_half* residual, const bt_half* gamma, const bt_half* beta, float eps, int T,
-                             int H, bt_half* y, hipStream_t st) {
+                             int H, bt_half* y, hipStream_t st, const int32_t* res_rows, const int32_t* out_idx,
+                             int out_rows) {
   const half_t* px = reinterpret_cast<const half_t*>(x);
   const half_t* pb = reinterpret_cast<const half_t*>(bias);
   const half_t* pr = reinterpret_cast<const half_t*>(residual);
@@ -183,13 +209,13 @@ bt_status layernorm_dispatch(const bt_half* x, const float* xpart, int nsplit, c
   const half_t* pe = reinterpret_cast<const half_t*>(beta);
   half_t* py = reinterpret_cast<half_t*>(y);
   const int chunks = H / 8;
-  dim3 grid((T + 3) / 4), block(256);
+  dim3 grid(((out_idx ? out_rows : T) + 3) / 4), block(256);
   const bool stream = (size_t)T * H * 6 > ((size_t)256 << 20);  // three tensors larger than the 256 MB Infinity Cache
 #define BT_LN(CPL)                                                                                             \
   do {                                                                                                         \
-    if (xpart) bias_residual_ln_kernel<CPL, true, false><<<grid, block, 0, st>>>(px, xpart, nsplit, pb, pr, pg, pe, eps, T, H, py); \
-    else if (stream) bias_residual_ln_kernel<CPL, false, true><<<grid, block, 0, st>>>(px, xpart, nsplit, pb, pr, pg, pe, eps, T, H, py); \
-    else bias_residual_ln_kernel<CPL, false, false><<<grid, block, 0, st>>>(px, xpart, nsplit, pb, pr, pg, pe, eps, T, H, py); \
+    if (xpart) bias_residual_ln_kernel<CPL, true, false><<<grid, block, 0, st>>>(px, xpart, nsplit, pb, pr, pg, pe, eps, T, H, py, res_rows, out_idx, out_rows); \
+    else if (stream) bias_residual_ln_kernel<CPL, false, true><<<grid, block, 0, st>>>(px, xpart, nsplit, pb, pr, pg, pe, eps, T, H, py, res_rows, out_idx, out_rows); \
+    else bias_residual_ln_kernel<CPL, false, false><<<grid, block, 0, st>>>(px, xpart, nsplit, pb, pr, pg, pe, eps, T, H, py, res_rows, out_idx, out_rows); \
   } while (0)
   if (chunks <= 64) BT_LN(1);
   else if (chunks <= 128) BT_LN(2);
@@ -214,5 +240,5 @@ extern "C" bt_status bt_add_bias_residual_layernorm(const bt_half* d_x, const bt
       !bt::aligned16(d_y) || (d_bias && !bt::aligned16(d_bias)))
     return BT_ERR_INVALID_ARG;
   return bt::layernorm_dispatch(d_x, nullptr, 0, d_bias, d_residual, d_gamma, d_beta, eps, T, H, d_y,
-                                static_cast<hipStream_t>(stream));
+                                static_cast<hipStream_t>(stream), nullptr, nullptr, 0);
 }

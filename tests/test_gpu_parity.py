@@ -381,6 +381,40 @@ def test_stack_bert_large_b32_s512_sampled(bt, folded):
     _sampled_stack(bt, "bert_large_b32_s512", TOL_12, TOL_24, folded)
 
 
+@pytest.mark.parametrize("name,n_layers,stress", [("layer_b4_s64", 1, True), ("layer_b4_s64", 2, True),
+                                                  ("bert_base_b16_s256", 3, False), ("bert_large_b32_s512", 2, True)])
+def test_encoder_fwd_padded_equals_pack_fwd_unpack(bt, name, n_layers, stress):
+    """Pack fused into the first GEMM / residual read and unpack fused into the last LayerNorm: the
+    result is the same bits as the three separate calls, pads are zero, the input is untouched."""
+    import torch
+    wl = I.WORKLOADS[name]
+    L = I.draw_lengths(wl)
+    L[0] = 0 if name == "layer_b4_s64" else L[0]             # an empty sequence in the small case
+    T = int(L.sum())
+    xpad = dev(I.pad_rows(I.make_hidden_packed(wl, T), L, wl.S, fill=7.0))   # junk in the pads must not matter
+    keep = xpad.clone()
+    layers = [bt.Layer(I.make_layer_params(wl, i, stress)) for i in range(n_layers)]
+    cu, tok, t = bt.build_offsets(lengths=dev(L), S=wl.S)
+    assert t == T
+    want = bt.unpack(bt.encoder_fwd(layers, bt.pack(xpad, tok), cu, wl.S), tok, wl.B, wl.S)
+    got = torch.full_like(xpad, 3.0)
+    bt.encoder_fwd_padded(layers, xpad, tok, cu, out=got)
+    assert torch.equal(got, want) and torch.equal(xpad, keep)
+    mask = O.lengths_to_mask(L, wl.S).astype(bool)
+    assert float(got[torch.from_numpy(~mask).to("cuda:0")].abs().sum()) == 0.0
+
+
+def test_encoder_fwd_padded_all_padding(bt):
+    import torch
+    wl = I.WORKLOADS["layer_b4_s64"]
+    layers = [bt.Layer(I.make_layer_params(wl, 0))]
+    L = np.zeros(wl.B, np.int32)
+    cu, tok, t = bt.build_offsets(lengths=dev(L), S=wl.S)
+    xpad = torch.ones((wl.B, wl.S, wl.H), dtype=torch.float16, device="cuda:0")
+    got = bt.encoder_fwd_padded(layers, xpad, tok, cu, out=torch.ones_like(xpad))
+    assert t == 0 and float(got.abs().sum()) == 0.0
+
+
 @pytest.mark.parametrize("name", ["albert_b16_s256", "distilbert_b16_s256"])
 def test_stack_table4_shape_variants_sampled(bt, name):
     """Stack variants of Table IV: 12 layers sharing one parameter set (16 heads, hidden 1024) and a
