@@ -679,11 +679,11 @@ bt_status gemm_dispatch(const bt_half* A, const bt_half* W, int M, int N, int K,
   // BM+BN, and the grid runs in ceil(tiles / 256) rounds of one tile per compute unit.  slab_us and
   // epi_us (epilogue + pipeline fill) were measured per shape on MI355X; GELU adds to the epilogue.
   struct Cand { int bm, bn; float slab_us, epi_us; };
-  static const Cand cands[4] = {{256, 128, 0.607f, 2.2f}, {192, 128, 0.482f, 1.5f}, {128, 64, 0.298f, 0.78f},
-                                {64, 64, 0.183f, 0.4f}};
+  static const Cand cands[5] = {{256, 128, 0.607f, 2.2f}, {192, 128, 0.482f, 1.5f}, {128, 64, 0.298f, 0.78f},
+                                {64, 128, 0.287f, 0.84f}, {64, 64, 0.183f, 0.4f}};
   int best = 0;
   float best_us = 0.f;
-  for (int c = 0; c < 4; ++c) {
+  for (int c = 0; c < 5; ++c) {
     const long long rounds = (tiles(cands[c].bm, cands[c].bn) + 255) / 256;
     const float act_us = act != BT_ACT_NONE ? 9e-5f * cands[c].bm * cands[c].bn : 0.f;
     const float us = (float)rounds * ((float)(K / 64) * cands[c].slab_us + cands[c].epi_us + act_us);
@@ -693,6 +693,7 @@ bt_status gemm_dispatch(const bt_half* A, const bt_half* W, int M, int N, int K,
     case 0: return BT_PIPE(256, 128, 4, 2, 3);
     case 1: return BT_PIPE(192, 128, 2, 4, 3);
     case 2: return BT_PIPE(128, 64, 4, 2, 4);
+    case 3: return BT_PIPE(64, 128, 2, 4, 4);
     default: return BT_PIPE(64, 64, 2, 2, 4);
   }
 #undef BT_PIPE
