@@ -670,6 +670,9 @@ bt_status gemm_dispatch(const bt_half* A, const bt_half* W, int M, int N, int K,
     case 26: return BT_PIPE(128, 256, 2, 4, 3);
     case 27: return BT_PIPE(128, 128, 2, 4, 4);
     case 28: return BT_PIPE(64, 128, 2, 4, 4);
+    case 29: return BT_PIPE(128, 128, 2, 4, 2);
+    case 30: return BT_PIPE(128, 128, 2, 2, 2);
+    case 31: return BT_PIPE(128, 64, 4, 2, 3);
     case 99: return launch_simple(a, w, c, M, N, K, act, epi, ep, st, np_out);
     default: break;
   }
