@@ -251,7 +251,7 @@ __device__ __forceinline__ void store_partial(const float16_t (&acc)[MI][NI], fl
 //     compiler does not put a wait for ALL outstanding memory operations in front of their first use;
 //   finish_row_sums: after the caller has waited (s_waitcnt vmcnt), add them in index order,
 //     exchange the halves, derive mu and rstd.
-constexpr int kMaxHalfParts = 8;  // np <= 16: H <= 1024 at 64-wide column tiles; more falls back to a loop
+constexpr int kMaxHalfParts = 4;  // np <= 8: H <= 1024 at 128-wide column tiles; more falls back to a loop
 
 template <int MI>
 __device__ __forceinline__ void request_row_sums(const float2* __restrict__ part, int np, int M, int m_base, int l32,
@@ -297,6 +297,26 @@ __device__ __forceinline__ void finish_row_sums(const float2* __restrict__ part,
     mu[i] = a * inv_h;
     rstd[i] = rsqrtf(fmaxf(b * inv_h - mu[i] * mu[i], 0.f) + eps);
   }
+}
+
+// The same tile requested through inline assembly, exactly MI*NI*4 load instructions whatever M and N
+// (addresses clamped into the matrix; positions outside it are ignored by the epilogue): the K loop counts
+// outstanding memory instructions by hand and must know this number.
+template <int MI, int NI>
+__device__ __forceinline__ void request_resid(const half_t* __restrict__ resid, int M, int N, int m_base, int n_base,
+                                              int l32, int hf, half4_t (&rres)[MI][NI][4]) {
+#pragma unroll
+  for (int i = 0; i < MI; ++i)
+#pragma unroll
+    for (int j = 0; j < NI; ++j)
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        const int m = min(m_base + i * 32 + l32, M - 1), n = min(n_base + j * 32 + 8 * g + 4 * hf, N - 4);
+        const half_t* src = resid + (size_t)m * N + n;
+        half4_t t;
+        asm volatile("global_load_dwordx2 %0, %1, off" : "=v"(t) : "v"(src) : "memory");
+        rres[i][j][g] = t;
+      }
 }
 
 // The residual tile of EPI_RESID in accumulator layout (zero outside the matrix).
@@ -362,18 +382,23 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_pipe_kernel(const half_t* 
   const int wm = wave / WGN, wn = wave % WGN;
   const int l32 = lane & 31, hf = lane >> 5;
 
-  // Epilogue operands that do not depend on the product are requested now, ahead of the operand
-  // slabs, so that their latency hides behind the K loop: the residual tile (EPI_RESID) and the partial
-  // row sums behind mu / rstd (EPI_FOLD: rows of A; EPI_RESID: rows of a folded residual).
+  // The bias of the plain epilogue is requested now (a cheap broadcast load whose latency then hides
+  // behind the K loop).  The folded forms hold more per-column operands than there are registers to park
+  // them across the K loop; they load them right before the epilogue.  Their residual tile and partial
+  // row sums are requested in the last steady round (see below).
   half4_t rres[MI][NI][4];  // dead (and removed by the compiler) in the other epilogue forms
-  if constexpr (EPI == EPI_RESID) load_resid<MI, NI>(ep.resid, M, N, m0 + wm * WM, n0 + wn * WN, l32, hf, rres);
   EpiVecs<NI> vec;
-  if constexpr (EPI != EPI_PARTIAL) load_epi_vecs<NI, EPI>(ep, N, n0 + wn * WN, hf, vec);
+  if constexpr (EPI == EPI_PLAIN) load_epi_vecs<NI, EPI>(ep, N, n0 + wn * WN, hf, vec);
   __shared__ float2 red[EPI == EPI_RESID ? WGN * BM : 1];
   float2 psum[MI][kMaxHalfParts];
-  const float2* const stat_part = EPI == EPI_FOLD ? ep.ln_part : (EPI == EPI_RESID ? ep.resid_part : nullptr);
-  const int stat_np = EPI == EPI_FOLD ? ep.ln_np : ep.resid_np;
-  if (EPI != EPI_PLAIN && stat_part) request_row_sums<MI>(stat_part, stat_np, M, m0 + wm * WM, l32, hf, psum);
+  constexpr bool kStats = EPI == EPI_FOLD || EPI == EPI_RESID;
+  // without statistics (a plain residual) the requests still issue, at a harmless valid address, so that
+  // the number of memory instructions in flight is a compile-time constant
+  const float2* const stat_src = EPI == EPI_FOLD ? ep.ln_part : (EPI == EPI_RESID ? ep.resid_part : nullptr);
+  const float2* const stat_part = stat_src ? stat_src : reinterpret_cast<const float2*>(W);
+  const int stat_np = stat_src ? (EPI == EPI_FOLD ? ep.ln_np : ep.resid_np) : 0;
+  constexpr int kLateLoads = (EPI == EPI_RESID ? MI * NI * 4 : 0) + (kStats ? MI * kMaxHalfParts : 0);
+  static_assert((NS - 2) * TOT + kLateLoads < 64, "vmcnt range");
 
   // DMA source pointers.  Instruction q of this wave fills LDS rows [r0, r0+8) of the slab; lane i
   // lands at row r0 + i/8, physical chunk i%8, and therefore fetches logical chunk
@@ -455,11 +480,11 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_pipe_kernel(const half_t* 
   // DMA instructions for slab kt+NS-1 (FETCH) are spread over the first KS-1 k-steps into the stage
   // that the previous hand-over freed.  The hand-over to the next slab sits in front of the last
   // k-step's MFMAs: every fragment of this slab is in registers (lgkmcnt 0), this wave's share of
-  // the next slab has landed (at most YOUNGER later slabs of TOT instructions stay in flight), and
+  // the next slab has landed (at most IN_FLIGHT younger memory instructions stay in flight), and
   // the barrier publishes both facts, so the next slab may be read and this stage refilled.
-  auto slab = [&](int kt, auto stage, auto fetch_c, auto last_c, auto younger_c) {
+  auto slab = [&](int kt, auto stage, auto fetch_c, auto last_c, auto in_flight_c) {
     constexpr bool FETCH = decltype(fetch_c)::value, LAST = decltype(last_c)::value;
-    constexpr int YOUNGER = decltype(younger_c)::value;
+    constexpr int IN_FLIGHT = decltype(in_flight_c)::value;  // memory instructions issued after slab kt+1
     const auto fstage = (stage + (NS - 1)) % NS, nstage = (stage + 1) % NS;
 #pragma unroll
     for (int ks = 0; ks < KS - 1; ++ks) {
@@ -473,7 +498,7 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_pipe_kernel(const half_t* 
     }
     if (!LAST) {
       __builtin_amdgcn_s_waitcnt(0xc07f);  // lgkmcnt(0), other counters untouched
-      wait_vmcnt<YOUNGER * TOT>();
+      wait_vmcnt<IN_FLIGHT>();
       __builtin_amdgcn_s_barrier();
       read_frags(nstage, 0, 0);
     }
@@ -484,13 +509,6 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_pipe_kernel(const half_t* 
   using yes = std::true_type;
   using no = std::false_type;
 
-  float mu[MI], rstd[MI];
-#pragma unroll
-  for (int i = 0; i < MI; ++i) { mu[i] = 0.f; rstd[i] = 1.f; }
-  if (EPI != EPI_PLAIN && stat_part) {
-    wait_vmcnt<(NS - 1) * TOT>();  // everything older than the NS-1 slabs just requested has arrived
-    finish_row_sums<MI>(stat_part, stat_np, M, m0 + wm * WM, l32, hf, ep.inv_h, ep.eps, psum, mu, rstd);
-  }
   wait_vmcnt<(NS - 2) * TOT>();  // slab 0 has landed
   __builtin_amdgcn_s_barrier();
   int kt = 0;
@@ -498,18 +516,70 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_pipe_kernel(const half_t* 
     int st = pre == 0 ? 0 : NS - pre;
     read_frags(st, 0, 0);
     for (; kt < pre; ++kt) {  // leading slabs: run-time stage
-      slab(kt, st, yes{}, no{}, integral_constant<int, NS - 2>{});
+      slab(kt, st, yes{}, no{}, integral_constant<int, (NS - 2) * TOT>{});
       st = st + 1 == NS ? 0 : st + 1;
     }
   }
-  for (int r = 0; r < rounds; ++r) {  // steady state: compile-time stages
-    static_for<NS>([&](auto s) { slab(kt + decltype(s)::value, s, yes{}, no{}, integral_constant<int, NS - 2>{}); });
+  // The epilogue operands that are expensive to fetch (residual tile: one cache line per lane; partial
+  // row sums; kLateLoads instructions in all) are requested at the start of the LAST steady round, about
+  // 2 NS slabs before they are needed: early enough to arrive in time, late enough not to sit in front of
+  // the first operand slabs in the in-order memory pipeline (issued at kernel start they delayed the whole
+  // K loop by more than a microsecond).  The waits that follow count them: they are younger than the
+  // NS-2 slabs in flight at that moment and older than every slab requested afterwards.
+  // They are requested through inline assembly and collected by hand, so from request to collection the
+  // code is straight-line (no loop, no join): the compiler must not get a chance to copy a destination
+  // register before its data has arrived.
+  float mu[MI], rstd[MI];
+#pragma unroll
+  for (int i = 0; i < MI; ++i) { mu[i] = 0.f; rstd[i] = 1.f; }
+  auto late_requests = [&]() {
+    if constexpr (EPI == EPI_RESID) request_resid<MI, NI>(ep.resid, M, N, m0 + wm * WM, n0 + wn * WN, l32, hf, rres);
+    if constexpr (kStats) request_row_sums<MI>(stat_part, stat_np, M, m0 + wm * WM, l32, hf, psum);
+  };
+  auto late_collect = [&]() {
+    if constexpr (kLateLoads > 0) {
+      wait_vmcnt<0>();
+      if constexpr (EPI == EPI_RESID) {
+#pragma unroll
+        for (int i = 0; i < MI; ++i)
+#pragma unroll
+          for (int j = 0; j < NI; ++j)
+#pragma unroll
+            for (int g = 0; g < 4; ++g) asm volatile("" : "+v"(rres[i][j][g]));  // ordered after the wait
+      }
+      finish_row_sums<MI>(stat_part, stat_np, M, m0 + wm * WM, l32, hf, ep.inv_h, ep.eps, psum, mu, rstd);
+    }
+  };
+  for (int r = 0; r + 1 < rounds; ++r) {  // steady state: compile-time stages
+    static_for<NS>([&](auto s) { slab(kt + decltype(s)::value, s, yes{}, no{}, integral_constant<int, (NS - 2) * TOT>{}); });
     kt += NS;
   }
-  static_for<NS - 1>([&](auto j) {  // last NS-1 slabs: everything is already in flight
-    constexpr int J = decltype(j)::value;
-    slab(kt + J, j, no{}, integral_constant<bool, J == NS - 2>{}, integral_constant<int, (NS - 3 - J > 0 ? NS - 3 - J : 0)>{});
-  });
+  if (rounds > 0) {  // last steady round + the last NS-1 slabs (which fetch nothing)
+    late_requests();
+    static_for<NS>([&](auto s) {
+      constexpr int S = decltype(s)::value;
+      slab(kt + S, s, yes{}, no{}, integral_constant<int, (NS - 2) * TOT + (S <= NS - 3 ? kLateLoads : 0)>{});
+    });
+    static_for<NS - 1>([&](auto j) {
+      constexpr int J = decltype(j)::value;
+      slab(kt + NS + J, j, no{}, integral_constant<bool, J == NS - 2>{},
+           integral_constant<int, (NS - 3 - J > 0 ? NS - 3 - J : 0) * TOT>{});
+    });
+    late_collect();
+  } else {  // short K: the late requests go behind all operand slabs and the remaining waits allow for them
+    late_requests();
+    static_for<NS - 1>([&](auto j) {
+      constexpr int J = decltype(j)::value;
+      slab(kt + J, j, no{}, integral_constant<bool, J == NS - 2>{},
+           integral_constant<int, (NS - 3 - J > 0 ? NS - 3 - J : 0) * TOT + kLateLoads>{});
+    });
+    late_collect();
+  }
+  if (!stat_src) {  // a plain residual: no LayerNorm to rebuild
+#pragma unroll
+    for (int i = 0; i < MI; ++i) { mu[i] = 0.f; rstd[i] = 1.f; }
+  }
+  if constexpr (EPI == EPI_FOLD || EPI == EPI_RESID) load_epi_vecs<NI, EPI>(ep, N, n0 + wn * WN, hf, vec);
   if constexpr (EPI == EPI_PARTIAL) {
     store_partial<MI, NI>(acc, ep.partial + (size_t)split * M * N, M, N, m0 + wm * WM, n0 + wn * WN, l32, hf);
   } else {
@@ -611,7 +681,9 @@ static bt_status launch_pipe(const half_t* A, const half_t* W, half_t* C, int M,
 #define BT_LAUNCH(ACT, EPI) \
   gemm_pipe_kernel<BM, BN, WGM, WGN, NS, ACT, EPI><<<grid, block, 0, st>>>(A, W, ep, C, M, N, K, tiles_n, (int)n_tiles, group_m)
   if (epi == EPI_RESID) {
-    BT_LAUNCH(BT_ACT_NONE, EPI_RESID);
+    // only for shapes with one 32x32 block per wavefront (the residual tile lives in registers)
+    if constexpr ((BM / WGM) * (BN / WGN) == 32 * 32) BT_LAUNCH(BT_ACT_NONE, EPI_RESID);
+    else return BT_ERR_UNSUPPORTED;
   } else if (epi == EPI_FOLD) {
     if (act == BT_ACT_NONE) BT_LAUNCH(BT_ACT_NONE, EPI_FOLD);
     else if (act == BT_ACT_GELU_ERF) BT_LAUNCH(BT_ACT_GELU_ERF, EPI_FOLD);
@@ -687,10 +759,13 @@ bt_status gemm_dispatch(const bt_half* A, const bt_half* W, int M, int N, int K,
   int best = 0;
   float best_us = 0.f;
   for (int c = 0; c < 5; ++c) {
+    // EPI_RESID keeps a residual tile per lane across the last slabs: only the shapes with one 32x32
+    // block per wavefront have the registers for it
+    if (epi == EPI_RESID && c < 2) continue;
     const long long rounds = (tiles(cands[c].bm, cands[c].bn) + 255) / 256;
     const float act_us = act != BT_ACT_NONE ? 9e-5f * cands[c].bm * cands[c].bn : 0.f;
     const float us = (float)rounds * ((float)(K / 64) * cands[c].slab_us + cands[c].epi_us + act_us);
-    if (c == 0 || us < best_us) { best = c; best_us = us; }
+    if (best_us == 0.f || us < best_us) { best = c; best_us = us; }
   }
   switch (best) {
     case 0: return BT_PIPE(256, 128, 4, 2, 3);

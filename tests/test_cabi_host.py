@@ -118,3 +118,24 @@ def test_no_fallback_when_library_missing(tmp_path):
             mod.load_library(str(tmp_path / "missing.so"))
     finally:
         importlib.reload(bt)
+
+
+def test_gemm_kernels_use_no_scratch():
+    """The GEMM kernels request some operands through inline assembly and collect them by hand; a register
+    spill of such a destination before its data has arrived would store garbage.  Every GEMM kernel must
+    therefore compile without scratch memory (checked in the compiler's own metadata)."""
+    import shutil
+    import subprocess
+    hipcc = shutil.which("hipcc") or "/opt/rocm/bin/hipcc"
+    if not os.path.exists(hipcc):
+        pytest.skip("hipcc not available")
+    src = os.path.join(ROOT, "paper_2210_03052_amd", "csrc", "gemm.hip")
+    out = subprocess.run([hipcc, "--offload-arch=gfx950", "-O3", "-std=c++17", "-w", "-I" + os.path.join(ROOT, "include"),
+                          "-I" + os.path.dirname(src), "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+                          "-S", "--cuda-device-only", "-o", "-", src], capture_output=True, text=True, timeout=600)
+    assert out.returncode == 0, out.stderr[-2000:]
+    sizes = re.findall(r"\.name:\s+(\S+)\n(?:.*\n)*?\s+\.private_segment_fixed_size:\s+(\d+)", out.stdout)
+    assert len(sizes) >= 20
+    spilled = [n for n, b in sizes if int(b) != 0]
+    assert not spilled, spilled
+
