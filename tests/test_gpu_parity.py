@@ -222,6 +222,12 @@ def test_varlen_mha_long_ragged_tall_tiles(bt):
     assert _mha_case(bt, lengths, 12, seed=77) <= 4e-3
 
 
+def test_varlen_mha_maximum_length(bt):
+    """The longest sequence the offsets accept (4096), one token short of it, and a short neighbour; two
+    heads (the oracle builds a 4096 x 4096 score matrix per head)."""
+    assert _mha_case(bt, [4096, 3, 4095], 2, seed=4096) <= 4e-3
+
+
 def test_varlen_mha_many_sequences(bt):
     """More than 64 sequences (plain sequence order path), two-wave kernel."""
     rng = np.random.default_rng(5)
