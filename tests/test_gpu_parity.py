@@ -155,6 +155,30 @@ def test_gemm_bias_act(bt, M, N, K, act, bias):
     assert (err <= 1e-3 + 2 ** -10 * np.abs(ref)).mean() > 0.999
 
 
+@pytest.mark.parametrize("act", [1, 2])
+def test_gelu_epilogue_over_every_fp16_input(bt, act):
+    """The activation alone: with A = identity the product hands each weight through unchanged
+    (C[m][n] = W[n][m], exact in fp16), so the epilogue sees chosen inputs -- here every finite fp16 value
+    in [-16, 16] (beyond: GELU(x) = x or 0 to fp16 precision, a few samples).  Against the fp64 definition the
+    fp16 result may differ by rounding only: at most 1 ulp, and for at least 99 % of inputs not at all."""
+    K = 64
+    bits = np.arange(0, 0x4C01, dtype=np.uint16)                      # +0 ... 16.0, subnormals included
+    vals = np.concatenate([bits, bits | 0x8000, np.array([0x7BFF, 0xFBFF, 0x7000, 0xF000], np.uint16)])
+    n = -(-vals.size // (8 * K)) * 8 * K                               # N = n / K a multiple of 8
+    vals = np.concatenate([vals, np.zeros(n - vals.size, np.uint16)]).view(np.float16)
+    w = np.ascontiguousarray(vals.reshape(-1, K))                      # [N, K]; C[m][n] = w[n][m]
+    a = np.eye(K, dtype=np.float16)
+    got = host(bt.gemm_bias_act(dev(a), dev(w), None, act))            # [K, N]
+    x = w.T.astype(np.float64)
+    ref = (O.gelu(x) if act == 1 else _gelu_tanh64(x)).astype(np.float16)
+    def line(h):                                                       # fp16 bits -> position on the number line
+        b = h.view(np.uint16).astype(np.int32)
+        return np.where(b & 0x8000, -(b & 0x7FFF), b)                  # +0 and -0 coincide
+    ulp = np.abs(line(got) - line(ref))
+    assert ulp.max() <= 1, (ulp.max(), x.flat[ulp.argmax()])
+    assert (ulp == 0).mean() >= 0.99, (ulp == 0).mean()
+
+
 # ------------------------------------------------------------------ bias + residual + LayerNorm
 @pytest.mark.parametrize("T,H,bias", [(1, 8, True), (5, 64, True), (150, 768, True), (2456, 768, False),
                                       (333, 1024, True), (9, 4096, True), (3, 8192, True), (7, 520, True)])
