@@ -64,15 +64,11 @@ __device__ __forceinline__ FragAddr make_frag_addr(int lane) {
   return f;
 }
 
-// One 64-key tile for the 32 query rows of a wavefront: S^T = K Q^T, online softmax, O^T += V^T P^T.
-// m_run is kept in the scaled log2 domain and is only raised when the tile maximum exceeds it by
-// more than 8 (a factor 256: probabilities stay <= 256, exact in fp16/fp32 terms), so the rescale
-// of the accumulators is skipped for most tiles; any reference maximum gives the same softmax.
-__device__ __forceinline__ void process_tile(const half_t* sk, const half_t* sv, const half8_t (&qf)[4], int k0, int L,
-                                             float scale_log2e, const FragAddr& fa, float& m_run, float& l_run,
-                                             float16_t (&o_acc)[2]) {
-  const int hf = fa.hf;
-  float16_t s[2];
+// One 64-key tile for the 32 query rows of a wavefront, step by step:  S^T = K Q^T (qk_tile);  mask of a
+// ragged last tile;  running maximum and rescale (softmax_max);  P = exp2(S - m), row sums, fp16 P
+// (softmax_exp);  O^T += V^T P^T (pv_tile).
+__device__ __forceinline__ void qk_tile(const half_t* sk, const half8_t (&qf)[4], const FragAddr& fa,
+                                        float16_t (&s)[2]) {
 #pragma unroll
   for (int kb = 0; kb < 2; ++kb) {
 #pragma unroll
@@ -80,25 +76,47 @@ __device__ __forceinline__ void process_tile(const half_t* sk, const half_t* sv,
 #pragma unroll
     for (int ks = 0; ks < 4; ++ks) {
       const half8_t a =
-          *reinterpret_cast<const half8_t*>(sk + fa.k_rd + kb * 32 * kD + (((2 * ks + hf) ^ fa.swz_k) * 8));
+          *reinterpret_cast<const half8_t*>(sk + fa.k_rd + kb * 32 * kD + (((2 * ks + fa.hf) ^ fa.swz_k) * 8));
       s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, qf[ks], s[kb], 0, 0, 0);
     }
   }
-  if (k0 + kKT > L) {  // ragged last tile (wave-uniform): keys past the end of the sequence drop out
-#pragma unroll
-    for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int key = k0 + kb * 32 + 8 * (r >> 2) + 4 * hf + (r & 3);
-        if (key >= L) s[kb][r] = -INFINITY;
-      }
-  }
-  float mx = s[0][0];
+}
+
+// Keys past the end of the sequence drop out (only the last tile of a sequence can hold any).
+__device__ __forceinline__ void mask_ragged(float16_t (&s)[2], int k0, int L, int hf) {
 #pragma unroll
   for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-    for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[kb][r]);
-  mx = fmaxf(mx, __shfl_xor(mx, 32, kWave));
+    for (int r = 0; r < 16; ++r) {
+      const int key = k0 + kb * 32 + 8 * (r >> 2) + 4 * hf + (r & 3);
+      if (key >= L) s[kb][r] = -INFINITY;
+    }
+}
+
+// m_run is kept in the scaled log2 domain and is only raised when the tile maximum exceeds it by
+// more than 8 (a factor 256: probabilities stay <= 256, exact in fp16/fp32 terms), so the rescale
+// of the accumulators is skipped for most tiles; any reference maximum gives the same softmax.
+__device__ __forceinline__ void softmax_max(const float16_t (&s)[2], float scale_log2e, float& m_run, float& l_run,
+                                            float16_t (&o_acc)[2]) {
+  // four independent chains, then the exchange between the two 32-lane halves by the lane-swap
+  // instruction of gfx950 (a VALU operation: no trip through the LDS queue behind the fragment reads)
+  float c[4];
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    const float16_t& t = s[j >> 1];
+    const int o = 8 * (j & 1);
+    float m = fmaxf(fmaxf(t[o], t[o + 1]), t[o + 2]);  // three-operand maxima
+    m = fmaxf(fmaxf(m, t[o + 3]), t[o + 4]);
+    m = fmaxf(fmaxf(m, t[o + 5]), t[o + 6]);
+    c[j] = fmaxf(m, t[o + 7]);
+  }
+  float mx = fmaxf(fmaxf(fmaxf(c[0], c[1]), c[2]), c[3]);
+  {
+    const unsigned u = __builtin_bit_cast(unsigned, mx);
+    const auto sw = __builtin_amdgcn_permlane32_swap(u, u, false, false);  // {lo,lo} and {hi,hi} of the halves
+    const unsigned lo = sw[0], hi = sw[1];
+    mx = fmaxf(__builtin_bit_cast(float, lo), __builtin_bit_cast(float, hi));
+  }
   const float mx_s = mx * scale_log2e;            // finite: every tile holds at least one valid key
   const bool raise = mx_s > m_run + 8.0f;         // same in both halves of a query column
   if (__builtin_amdgcn_ballot_w64(raise)) {
@@ -111,8 +129,11 @@ __device__ __forceinline__ void process_tile(const half_t* sk, const half_t* sv,
 #pragma unroll
       for (int r = 0; r < 16; ++r) o_acc[db][r] *= alpha;
   }
+}
+
+__device__ __forceinline__ void softmax_exp(const float16_t (&s)[2], float scale_log2e, float m_run, float& l_run,
+                                            half8_t (&pf)[2][2]) {
   float psum = 0.f;
-  half8_t pf[2][2];
 #pragma unroll
   for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
@@ -122,8 +143,12 @@ __device__ __forceinline__ void process_tile(const half_t* sk, const half_t* sv,
       pf[kb][r >> 3][r & 7] = (half_t)p;
     }
   l_run += psum;
-  // O^T += V^T P^T ; 16-key step ks covers S^T registers 8*(ks%2)..+7 of block ks/2, i.e. keys
-  // 16ks + {0..3, 8..11} + 4hf, the order the two transposing reads deliver.
+}
+
+// O^T += V^T P^T ; 16-key step ks covers S^T registers 8*(ks%2)..+7 of block ks/2, i.e. keys
+// 16ks + {0..3, 8..11} + 4hf, the order the two transposing reads deliver.
+__device__ __forceinline__ void pv_tile(const half_t* sv, const FragAddr& fa, const half8_t (&pf)[2][2],
+                                        float16_t (&o_acc)[2]) {
 #pragma unroll
   for (int db = 0; db < 2; ++db) {
 #pragma unroll
@@ -141,6 +166,18 @@ __device__ __forceinline__ void process_tile(const half_t* sk, const half_t* sv,
       o_acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, pf[ks >> 1][ks & 1], o_acc[db], 0, 0, 0);
     }
   }
+}
+
+__device__ __forceinline__ void process_tile(const half_t* sk, const half_t* sv, const half8_t (&qf)[4], int k0, int L,
+                                             float scale_log2e, const FragAddr& fa, float& m_run, float& l_run,
+                                             float16_t (&o_acc)[2]) {
+  float16_t s[2];
+  qk_tile(sk, qf, fa, s);
+  if (k0 + kKT > L) mask_ragged(s, k0, L, fa.hf);  // wave-uniform
+  softmax_max(s, scale_log2e, m_run, l_run, o_acc);
+  half8_t pf[2][2];
+  softmax_exp(s, scale_log2e, m_run, l_run, pf);
+  pv_tile(sv, fa, pf, o_acc);
 }
 
 // Locate the (sequence, q-tile) a workgroup owns.  Results are wave-uniform (readfirstlane).
@@ -270,6 +307,12 @@ __global__ __launch_bounds__(NW * 64) void varlen_mha_kernel(
 #pragma unroll
       for (int e = 0; e < 8; ++e) qf[ks][e] = (half_t)((float)qf[ks][e] + (float)bq[hofs + ks * 16 + hf * 8 + e]);
   }
+  // The Q loads must be complete BEFORE the tile loop.  Left to the compiler, their s_waitcnt vmcnt(3..0)
+  // land at the first use inside the loop body and are executed by every iteration, where the only
+  // loads in flight are the K/V DMA of the next tile just issued: each iteration would wait for its own
+  // prefetch.  A use of the registers here moves the wait out of the loop.
+#pragma unroll
+  for (int ks = 0; ks < 4; ++ks) asm volatile("" : "+v"(qf[ks]));
 
   float16_t o_acc[2];
 #pragma unroll
@@ -388,6 +431,12 @@ __global__ __launch_bounds__(NK * 64) void varlen_mha_splitkey_kernel(
 #pragma unroll
       for (int e = 0; e < 8; ++e) qf[ks][e] = (half_t)((float)qf[ks][e] + (float)bq[hofs + ks * 16 + hf * 8 + e]);
   }
+  // The Q loads must be complete BEFORE the tile loop.  Left to the compiler, their s_waitcnt vmcnt(3..0)
+  // land at the first use inside the loop body and are executed by every iteration, where the only
+  // loads in flight are the K/V DMA of the next tile just issued: each iteration would wait for its own
+  // prefetch.  A use of the registers here moves the wait out of the loop.
+#pragma unroll
+  for (int ks = 0; ks < 4; ++ks) asm volatile("" : "+v"(qf[ks]));
 
   float16_t o_acc[2];
 #pragma unroll
