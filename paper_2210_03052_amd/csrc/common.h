@@ -61,6 +61,8 @@ struct GemmEpi {
   // fp32 accumulators to partial[s][M][N]; whoever consumes the product adds the ksplit slices in order.
   float* partial = nullptr;
   int ksplit = 1;
+  // set by the launcher: the fp16 product is larger than the L2s together hold, store it non-temporally
+  bool stream_out = false;
 };
 
 // Butterfly reductions over the 64 lanes of a wavefront.
