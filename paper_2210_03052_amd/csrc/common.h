@@ -61,9 +61,20 @@ struct GemmEpi {
   // fp32 accumulators to partial[s][M][N]; whoever consumes the product adds the ksplit slices in order.
   float* partial = nullptr;
   int ksplit = 1;
-  // set by the launcher: the fp16 product is larger than the L2s together hold, store it non-temporally
-  bool stream_out = false;
 };
+
+// Stores with device scope: written through the XCD's L2 instead of staying dirty in it until the
+// write-back that ends every kernel (during which no CU computes).  As assembly because the scope is
+// not expressible on a plain store; the s_nop covers the hazard of a wide store whose data registers are
+// overwritten by the next instruction.  16 and 8 bytes per lane.
+__device__ __forceinline__ void store_through(half_t* gptr, const uint4_t& v) {
+  asm volatile("global_store_dwordx4 %0, %1, off sc1\n\ts_nop 1"
+               ::"v"((half_t __attribute__((address_space(1)))*)gptr), "v"(v) : "memory");
+}
+__device__ __forceinline__ void store_through(half_t* gptr, const uint2_t& v) {
+  asm volatile("global_store_dwordx2 %0, %1, off sc1\n\ts_nop 0"
+               ::"v"((half_t __attribute__((address_space(1)))*)gptr), "v"(v) : "memory");
+}
 
 // Butterfly reductions over the 64 lanes of a wavefront.
 __device__ __forceinline__ float wave_sum(float v) {

@@ -23,12 +23,6 @@ namespace bt {
 
 constexpr int kGemmThreads = 256;  // fallback kernel
 
-// A product larger than the eight 4 MB L2s together is stored non-temporally: its dirty lines would be
-// evicted before the kernel ends anyway, and on the way they push the operand panels out of the L2
-// they share (the 60 MB FFN intermediate at 9.9 k tokens: 10 % off that product).  Smaller products
-// stay cached: streamed out, the kernels that read them next were slower by more than the store saved.
-constexpr size_t kL2BytesTotal = 32u << 20;
-
 #define BT_AS1 __attribute__((address_space(1)))
 #define BT_AS3 __attribute__((address_space(3)))
 
@@ -230,13 +224,11 @@ __device__ __forceinline__ void store_tile(const float16_t (&acc)[MI][NI], const
   for (int r0 = 0; r0 < MI * 32; r0 += RPP) {
     const int m = m_base + r0 + rr, n = n_base + cc;
     const uint4_t v = *reinterpret_cast<const uint4_t*>(stage + (r0 + rr) * LD + cc);
-    if (m < M && n < N) {
-      half_t BT_AS1* dst = (half_t BT_AS1*)C + ((size_t)m * N + n);
-      if (ep.stream_out)  // as assembly: the compiler merges the two branches and drops the hint otherwise
-        asm volatile("global_store_dwordx4 %0, %1, off nt\n\ts_nop 1" ::"v"(dst), "v"(v) : "memory");
-      else
-        *reinterpret_cast<uint4_t BT_AS1*>(dst) = v;
-    }
+    // Device-scope (write-through) store: the tile leaves the L2 as it is produced.  Plain stores leave
+    // 1-2 MB of dirty lines in every XCD's L2 and the kernel then ends with their write-back, ~3 us for
+    // a 14 MB product with every CU idle; written through, that overlaps the tail of the computation
+    // (3 % off a 12-layer forward).  Non-temporal stores save the same but the next kernel reads slower.
+    if (m < M && n < N) store_through(C + ((size_t)m * N + n), v);
   }
 }
 
@@ -684,7 +676,6 @@ static bt_status launch_pipe(const half_t* A, const half_t* W, half_t* C, int M,
   if (K / 64 < NS - 1) return launch_simple(A, W, C, M, N, K, act, epi, ep, st, np_out);  // pipeline deeper than K
   const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
   ep.part_np = tiles_n;
-  ep.stream_out = (size_t)M * N * sizeof(half_t) > kL2BytesTotal;
   if (np_out) *np_out = ep.part_np;
   const long long n_tiles = (long long)tiles_m * tiles_n;
   if (n_tiles > 0x7fffffffLL) return BT_ERR_UNSUPPORTED;
