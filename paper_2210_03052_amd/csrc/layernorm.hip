@@ -109,7 +109,7 @@ __global__ __launch_bounds__(256) void bias_residual_ln_kernel(const half_t* x, 
 #pragma unroll
       for (int e = 0; e < 8; ++e) o[e] = (half_t)((v[i][e] - mean) * rstd * (float)g[e] + (float)b[e]);
       if (STREAM) __builtin_nontemporal_store(o, reinterpret_cast<half8_t*>(y + obase + c * 8));
-      else *reinterpret_cast<half8_t*>(y + obase + c * 8) = o;
+      else store_through(y + obase + c * 8, __builtin_bit_cast(uint4_t, o));  // see store_through
     }
   }
 }
