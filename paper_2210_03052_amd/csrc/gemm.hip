@@ -761,25 +761,27 @@ bt_status gemm_dispatch(const bt_half* A, const bt_half* W, int M, int N, int K,
   // operand slabs (~85 GB/s here whatever the shape), so one 64-deep slab costs a time proportional to
   // BM+BN, and the grid runs in ceil(tiles / 256) rounds of one tile per compute unit.  slab_us and
   // epi_us (epilogue + pipeline fill) were measured per shape on MI355X; GELU adds to the epilogue.
-  struct Cand { int bm, bn; float slab_us, epi_us; };
-  static const Cand cands[5] = {{256, 128, 0.607f, 2.2f}, {192, 128, 0.482f, 1.5f}, {128, 64, 0.298f, 0.78f},
-                                {64, 128, 0.287f, 0.84f}, {64, 64, 0.183f, 0.4f}};
-  int best = 0;
+  struct Cand { int bm, bn; float slab_us, epi_us; bool one_block_per_wave; };
+  static const Cand cands[6] = {{256, 128, 0.607f, 2.2f, false}, {192, 128, 0.482f, 1.5f, false},
+                                {128, 128, 0.384f, 1.5f, false}, {128, 64, 0.298f, 0.78f, true},
+                                {64, 128, 0.287f, 0.84f, true},  {64, 64, 0.183f, 0.4f, true}};
+  int best = -1;
   float best_us = 0.f;
-  for (int c = 0; c < 5; ++c) {
+  for (int c = 0; c < 6; ++c) {
     // EPI_RESID keeps a residual tile per lane across the last slabs: only the shapes with one 32x32
     // block per wavefront have the registers for it
-    if (epi == EPI_RESID && c < 2) continue;
+    if (epi == EPI_RESID && !cands[c].one_block_per_wave) continue;
     const long long rounds = (tiles(cands[c].bm, cands[c].bn) + 255) / 256;
     const float act_us = act != BT_ACT_NONE ? 9e-5f * cands[c].bm * cands[c].bn : 0.f;
     const float us = (float)rounds * ((float)(K / 64) * cands[c].slab_us + cands[c].epi_us + act_us);
-    if (best_us == 0.f || us < best_us) { best = c; best_us = us; }
+    if (best < 0 || us < best_us) { best = c; best_us = us; }
   }
   switch (best) {
     case 0: return BT_PIPE(256, 128, 4, 2, 3);
     case 1: return BT_PIPE(192, 128, 2, 4, 3);
-    case 2: return BT_PIPE(128, 64, 4, 2, 4);
-    case 3: return BT_PIPE(64, 128, 2, 4, 4);
+    case 2: return BT_PIPE(128, 128, 2, 4, 4);
+    case 3: return BT_PIPE(128, 64, 4, 2, 4);
+    case 4: return BT_PIPE(64, 128, 2, 4, 4);
     default: return BT_PIPE(64, 64, 2, 2, 4);
   }
 #undef BT_PIPE

@@ -110,10 +110,11 @@ def test_unpack_all_padding(bt):
 
 
 # ------------------------------------------------------------------ GEMM + epilogue
-@pytest.mark.parametrize("M,N", [(100, 768), (2308, 768), (2308, 2304), (2308, 3072)])
+@pytest.mark.parametrize("M,N", [(100, 768), (2308, 768), (2308, 2304), (2308, 3072), (2699, 768)])
 def test_gemm_slab_schedule_all_residues(bt, M, N):
     """The K loop splits its K/64 slabs into leading slabs, whole rounds of the pipeline depth and a tail;
-    every residue of K/64 modulo the depth (3 or 4 stages, one tile shape per (M,N) here) and the
+    every residue of K/64 modulo the depth (3 or 4 stages, one tile shape per (M,N) here: 64x64, 64x128,
+    192x128, 256x128, 128x128) and the
     K < depth fallback must give the same product.  Ragged M, and N not a multiple of the tile."""
     rng = np.random.default_rng(M * 7 + N)
     Kmax = 13 * 64
@@ -136,7 +137,7 @@ def _gelu_tanh64(x):
     (1, 8, 8, 0, False), (5, 16, 40, 0, True), (77, 72, 200, 1, True), (150, 2304, 768, 0, True),
     (129, 768, 3072, 0, False), (300, 3072, 768, 1, True), (2456, 768, 768, 0, True), (2456, 3072, 768, 2, True),
     (1000, 1024, 4096, 0, True), (4710, 4096, 1024, 1, True), (2308, 2304, 768, 0, True), (4648, 1024, 4096, 0, False),
-    (2305, 2312, 832, 1, True)])
+    (2305, 2312, 832, 1, True), (2699, 768, 3072, 0, True), (2764, 1024, 1024, 1, True)])
 def test_gemm_bias_act(bt, M, N, K, act, bias):
     rng = np.random.default_rng(M + N + K)
     a = rng.normal(0, 1, (M, K)).astype(np.float16)
