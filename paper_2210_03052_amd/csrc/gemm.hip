@@ -147,15 +147,21 @@ __device__ __forceinline__ void store_tile(const float16_t (&acc)[MI][NI], const
   float s0[MI], s1[MI];
 #pragma unroll
   for (int i = 0; i < MI; ++i) s0[i] = s1[i] = 0.f;
+  // rows of this wave's tile in the store pass: WN/8 lanes per row
+  constexpr int LPR = WN / 8, RPP = 64 / LPR;  // lanes per row, rows per pass
+  const int rr = lane / LPR, cc = (lane % LPR) * 8;
+  // One 32-row block at a time: arithmetic on the accumulators, fp16 block to LDS, then (except with
+  // EPI_RESID, whose partial sums go out first) straight to memory -- the stores of block i drain while
+  // the arithmetic of block i+1 runs.
 #pragma unroll
-  for (int j = 0; j < NI; ++j) {
+  for (int i = 0; i < MI; ++i) {
+    const int m = m_base + i * 32 + l32;
 #pragma unroll
-    for (int g = 0; g < 4; ++g) {
-      const int nl = j * 32 + 8 * g + 4 * hf;
-      const bool n_ok = n_base + nl < N;  // N % 8 == 0: the 4 columns are all in or all out
+    for (int j = 0; j < NI; ++j) {
 #pragma unroll
-      for (int i = 0; i < MI; ++i) {
-        const int m = m_base + i * 32 + l32;
+      for (int g = 0; g < 4; ++g) {
+        const int nl = j * 32 + 8 * g + 4 * hf;
+        const bool n_ok = n_base + nl < N;  // N % 8 == 0: the 4 columns are all in or all out
         float v[4];
 #pragma unroll
         for (int t = 0; t < 4; ++t) v[t] = acc[i][j][4 * g + t];
@@ -192,6 +198,14 @@ __device__ __forceinline__ void store_tile(const float16_t (&acc)[MI][NI], const
         *reinterpret_cast<half4_t*>(stage + (i * 32 + l32) * LD + nl) = o;
       }
     }
+    if constexpr (EPI != EPI_RESID) {
+#pragma unroll
+      for (int r0 = i * 32; r0 < (i + 1) * 32; r0 += RPP) {
+        const int mr = m_base + r0 + rr, n = n_base + cc;
+        const uint4_t v = *reinterpret_cast<const uint4_t*>(stage + (r0 + rr) * LD + cc);
+        if (mr < M && n < N) store_through(C + ((size_t)mr * N + n), v);
+      }
+    }
   }
   if constexpr (EPI == EPI_RESID) {
     // Row sums of this wave's columns -> LDS; after the barrier the wavefronts of tile column 0 add the
@@ -217,18 +231,17 @@ __device__ __forceinline__ void store_tile(const float16_t (&acc)[MI][NI], const
       }
     }
   }
-  // rows of this wave's tile: WN/8 lanes per row
-  constexpr int LPR = WN / 8, RPP = 64 / LPR;  // lanes per row, rows per pass
-  const int rr = lane / LPR, cc = (lane % LPR) * 8;
+  // Device-scope (write-through) stores: the tile leaves the L2 as it is produced.  Plain stores leave
+  // 1-2 MB of dirty lines in every XCD's L2 and the kernel then ends with their write-back, ~3 us for
+  // a 14 MB product with every CU idle; written through, that overlaps the tail of the computation
+  // (3 % off a 12-layer forward).  Non-temporal stores save the same but the next kernel reads slower.
+  if constexpr (EPI == EPI_RESID) {
 #pragma unroll
-  for (int r0 = 0; r0 < MI * 32; r0 += RPP) {
-    const int m = m_base + r0 + rr, n = n_base + cc;
-    const uint4_t v = *reinterpret_cast<const uint4_t*>(stage + (r0 + rr) * LD + cc);
-    // Device-scope (write-through) store: the tile leaves the L2 as it is produced.  Plain stores leave
-    // 1-2 MB of dirty lines in every XCD's L2 and the kernel then ends with their write-back, ~3 us for
-    // a 14 MB product with every CU idle; written through, that overlaps the tail of the computation
-    // (3 % off a 12-layer forward).  Non-temporal stores save the same but the next kernel reads slower.
-    if (m < M && n < N) store_through(C + ((size_t)m * N + n), v);
+    for (int r0 = 0; r0 < MI * 32; r0 += RPP) {
+      const int mr = m_base + r0 + rr, n = n_base + cc;
+      const uint4_t v = *reinterpret_cast<const uint4_t*>(stage + (r0 + rr) * LD + cc);
+      if (mr < M && n < N) store_through(C + ((size_t)mr * N + n), v);
+    }
   }
 }
 
