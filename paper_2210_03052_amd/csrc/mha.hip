@@ -340,10 +340,17 @@ __global__ __launch_bounds__(NW * 64) void varlen_mha_kernel(
     stage = stage + 1 == NS ? 0 : stage + 1;
   }
 
-  if (wave_active && q_row < L) {
+  // Output.  A lane holds 4 consecutive values of one row per register group, so stored directly a
+  // row leaves in 8-byte pieces (16 per 128-byte head slice); instead the 32 x 64 block of a wavefront
+  // is transposed through LDS (the K/V stages are free once every wave has left the loop) and leaves
+  // as whole 128-byte rows, 16 bytes per lane, written through the L2 like the GEMM tiles.
+  constexpr int OLD = kD + 8;  // row pitch of the staged block, halves
+  __builtin_amdgcn_s_barrier();
+  half_t* ostage = ((wave & 2) ? sV : sK) + (wave & 1) * (32 * OLD);
+  static_assert(2 * 32 * OLD <= NS * TILE, "two staged blocks fit one operand ring");
+  if (wave_active) {
     const float l_tot = l_run + __shfl_xor(l_run, 32, kWave);
     const float inv = 1.0f / l_tot;
-    half_t* op = out + (size_t)(tok0 + q_row) * (heads * kD) + hofs + 4 * hf;
 #pragma unroll
     for (int db = 0; db < 2; ++db)
 #pragma unroll
@@ -356,8 +363,16 @@ __global__ __launch_bounds__(NW * 64) void varlen_mha_kernel(
         half4_t o;
 #pragma unroll
         for (int t = 0; t < 4; ++t) o[t] = (half_t)(o_acc[db][4 * g + t] * inv + bias4[t]);
-        *reinterpret_cast<half4_t*>(op + db * 32 + 8 * g) = o;
+        *reinterpret_cast<half4_t*>(ostage + l32 * OLD + db * 32 + 8 * g + 4 * hf) = o;
       }
+    // same wavefront reads what it wrote: LDS operations of a wave complete in order
+    const int rr = lane >> 3, cc = (lane & 7) * 8;
+#pragma unroll
+    for (int r0 = 0; r0 < 32; r0 += 8) {
+      const int q = q0 + wave * 32 + r0 + rr;
+      const uint4_t v = *reinterpret_cast<const uint4_t*>(ostage + (r0 + rr) * OLD + cc);
+      if (q < L) store_through(out + (size_t)(tok0 + q) * (heads * kD) + hofs + cc, v);
+    }
   }
 }
 
