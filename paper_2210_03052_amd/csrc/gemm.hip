@@ -360,10 +360,13 @@ __device__ __forceinline__ void load_resid(const half_t* __restrict__ resid, int
 // Pipelined kernel: direct-to-LDS slabs, NS stages, WGM x WGN wavefronts.
 // ---------------------------------------------------------------------------
 template <int BM, int BN, int WGM, int WGN, int NS, int ACT, int EPI>
-__global__ __launch_bounds__(WGM* WGN * 64) void gemm_pipe_kernel(const half_t* __restrict__ A,
-                                                                  const half_t* __restrict__ W, const GemmEpi ep,
-                                                                  half_t* __restrict__ C, int M, int N, int K,
-                                                                  int tiles_n, int n_tiles, int group_m) {
+__global__ __launch_bounds__(WGM* WGN * 64) void gemm_pipe_kernel(
+    // Argument order: what the prologue and the K loop need comes first and fits the 14 dwords that are
+    // preloaded into SGPRs at wave launch (-amdgpu-kernarg-preload-count), so the first DMA does not
+    // wait for a scalar load of the kernel arguments; the epilogue descriptor is fetched behind it.
+    const half_t* __restrict__ A, const half_t* __restrict__ W, half_t* __restrict__ C,
+    const int32_t* __restrict__ a_rows /* = ep.a_rows */, int M, int N, int K, int tiles_n, int n_tiles, int group_m,
+    const GemmEpi ep) {
   constexpr int BK = 64, KS = BK / 16;
   constexpr int NWAVES = WGM * WGN;
   constexpr int WM = BM / WGM, WN = BN / WGN;   // wave tile
@@ -431,7 +434,7 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_pipe_kernel(const half_t* 
     const int r = (wave * LA + q) * RPI + lane / CPR;
     const int c = (lane % CPR) ^ ((r >> 1) & (CPR - 1));
     const int ar = min(m0 + r, M - 1);  // rows past M: clamped reads, never stored
-    ga[q] = A + (size_t)(ep.a_rows ? ep.a_rows[ar] : ar) * K + k_off + c * 8;
+    ga[q] = A + (size_t)(a_rows ? a_rows[ar] : ar) * K + k_off + c * 8;
   }
 #pragma unroll
   for (int q = 0; q < LB; ++q) {
@@ -700,7 +703,7 @@ static bt_status launch_pipe(const half_t* A, const half_t* W, half_t* C, int M,
 #endif
   group_m = group_m < 1 ? 1 : (group_m > tiles_m ? tiles_m : group_m);
 #define BT_LAUNCH(ACT, EPI) \
-  gemm_pipe_kernel<BM, BN, WGM, WGN, NS, ACT, EPI><<<grid, block, 0, st>>>(A, W, ep, C, M, N, K, tiles_n, (int)n_tiles, group_m)
+  gemm_pipe_kernel<BM, BN, WGM, WGN, NS, ACT, EPI><<<grid, block, 0, st>>>(A, W, C, ep.a_rows, M, N, K, tiles_n, (int)n_tiles, group_m, ep)
   if (epi == EPI_RESID) {
     // only for shapes with one 32x32 block per wavefront (the residual tile lives in registers)
     if constexpr ((BM / WGM) * (BN / WGN) == 32 * 32) BT_LAUNCH(BT_ACT_NONE, EPI_RESID);
@@ -827,8 +830,8 @@ bt_status gemm_splitk_dispatch(const bt_half* A, const bt_half* W, int M, int N,
   int group_m = (int)(sqrt((double)n_tiles / 8.0) + 0.5);
   group_m = group_m < 1 ? 1 : (group_m > tiles_m ? tiles_m : group_m);
   gemm_pipe_kernel<BM, BN, 2, 2, NS, BT_ACT_NONE, EPI_PARTIAL><<<dim3((unsigned)(n_tiles * ksplit)), dim3(256), 0, st>>>(
-      reinterpret_cast<const half_t*>(A), reinterpret_cast<const half_t*>(W), ep, nullptr, M, N, K, tiles_n, n_tiles,
-      group_m);
+      reinterpret_cast<const half_t*>(A), reinterpret_cast<const half_t*>(W), nullptr, nullptr, M, N, K, tiles_n, n_tiles,
+      group_m, ep);
   return launch_status();
 }
 

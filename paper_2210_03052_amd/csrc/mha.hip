@@ -238,9 +238,10 @@ __device__ __forceinline__ bool locate_tile(const int32_t* __restrict__ cu, int 
 
 template <int NW, int NS>
 __global__ __launch_bounds__(NW * 64) void varlen_mha_kernel(
-    const half_t* __restrict__ Q, const half_t* __restrict__ K, const half_t* __restrict__ V, int64_t row_stride,
-    const half_t* __restrict__ bq, const half_t* __restrict__ bv, const int32_t* __restrict__ cu, int B, int heads,
-    int max_tiles, float scale_log2e, half_t* __restrict__ out) {
+    // in the order of first use: the first 14 dwords are preloaded into SGPRs at wave launch
+    const int32_t* __restrict__ cu, int B, int heads, int max_tiles, float scale_log2e, const half_t* __restrict__ Q,
+    const half_t* __restrict__ K, const half_t* __restrict__ V, int64_t row_stride, half_t* __restrict__ out,
+    const half_t* __restrict__ bq, const half_t* __restrict__ bv) {
   constexpr int BQ = NW * 32;
   constexpr int TILE = kKT * kD;            // halves per K (or V) tile
   constexpr int PER = 8 / NW;               // DMA instructions per wave per operand tile (8 rows each)
@@ -388,9 +389,10 @@ __global__ __launch_bounds__(NW * 64) void varlen_mha_kernel(
 // ---------------------------------------------------------------------------
 template <int NK, int NS>
 __global__ __launch_bounds__(NK * 64) void varlen_mha_splitkey_kernel(
-    const half_t* __restrict__ Q, const half_t* __restrict__ K, const half_t* __restrict__ V, int64_t row_stride,
-    const half_t* __restrict__ bq, const half_t* __restrict__ bv, const int32_t* __restrict__ cu, int B, int heads,
-    int max_tiles, float scale_log2e, half_t* __restrict__ out) {
+    // in the order of first use: the first 14 dwords are preloaded into SGPRs at wave launch
+    const int32_t* __restrict__ cu, int B, int heads, int max_tiles, float scale_log2e, const half_t* __restrict__ Q,
+    const half_t* __restrict__ K, const half_t* __restrict__ V, int64_t row_stride, half_t* __restrict__ out,
+    const half_t* __restrict__ bq, const half_t* __restrict__ bv) {
   constexpr int BQ = 32;
   constexpr int TILE = kKT * kD;       // halves per K (or V) tile
   constexpr int WAVE_LDS = NS * 2 * TILE;  // halves per wave: NS x (K tile + V tile), >= 8 KB + 256 B for the merge
@@ -551,8 +553,8 @@ static bt_status launch_mha_splitkey(const half_t* q, const half_t* k, const hal
   const long long tiles = by_len < by_tok ? by_len : by_tok;
   const long long blocks = tiles * heads;
   if (blocks > 0x7fffffffLL) return BT_ERR_UNSUPPORTED;
-  varlen_mha_splitkey_kernel<NK, NS><<<(unsigned)blocks, NK * 64, 0, st>>>(q, k, v, row_stride, bq, bv, cu, B, heads,
-                                                                         (max_len + BQ - 1) / BQ, scale * 1.4426950408889634f, out);
+  varlen_mha_splitkey_kernel<NK, NS><<<(unsigned)blocks, NK * 64, 0, st>>>(
+      cu, B, heads, (max_len + BQ - 1) / BQ, scale * 1.4426950408889634f, q, k, v, row_stride, out, bq, bv);
   return launch_status();
 }
 
@@ -567,8 +569,8 @@ static bt_status launch_mha(const half_t* q, const half_t* k, const half_t* v, i
   const long long tiles = by_len < by_tok ? by_len : by_tok;
   const long long blocks = tiles * heads;
   if (blocks > 0x7fffffffLL) return BT_ERR_UNSUPPORTED;
-  varlen_mha_kernel<NW, NS><<<(unsigned)blocks, NW * 64, 0, st>>>(q, k, v, row_stride, bq, bv, cu, B, heads,
-                                                                (max_len + BQ - 1) / BQ, scale * 1.4426950408889634f, out);
+  varlen_mha_kernel<NW, NS><<<(unsigned)blocks, NW * 64, 0, st>>>(
+      cu, B, heads, (max_len + BQ - 1) / BQ, scale * 1.4426950408889634f, q, k, v, row_stride, out, bq, bv);
   return launch_status();
 }
 

@@ -130,9 +130,10 @@ def test_gemm_kernels_use_no_scratch():
     if not os.path.exists(hipcc):
         pytest.skip("hipcc not available")
     src = os.path.join(ROOT, "paper_2210_03052_amd", "csrc", "gemm.hip")
-    out = subprocess.run([hipcc, "--offload-arch=gfx950", "-O3", "-std=c++17", "-w", "-I" + os.path.join(ROOT, "include"),
-                          "-I" + os.path.dirname(src), "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-                          "-S", "--cuda-device-only", "-o", "-", src], capture_output=True, text=True, timeout=600)
+    from paper_2210_03052_amd.build import EXTRA_FLAGS, FLAGS            # the flags libbt.so is built with
+    flags = [f for f in FLAGS if f != "-fPIC"] + EXTRA_FLAGS.get("gemm.hip", [])
+    out = subprocess.run([hipcc, *flags, "-w", "-S", "--cuda-device-only", "-o", "-", src],
+                         capture_output=True, text=True, timeout=600)
     assert out.returncode == 0, out.stderr[-2000:]
     sizes = re.findall(r"\.name:\s+(\S+)\n(?:.*\n)*?\s+\.private_segment_fixed_size:\s+(\d+)", out.stdout)
     assert len(sizes) >= 20
