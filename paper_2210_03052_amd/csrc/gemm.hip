@@ -110,7 +110,8 @@ struct EpiVecs {
 };
 
 template <int NI, int EPI>
-__device__ __forceinline__ void load_epi_vecs(const GemmEpi& ep, int N, int n_base, int hf, EpiVecs<NI>& v) {
+__device__ __forceinline__ void load_epi_vecs(const GemmEpi& ep, const half_t* bias /* = ep.bias */, int N,
+                                              int n_base, int hf, EpiVecs<NI>& v) {
   const half4_t zero = {(half_t)0.f, (half_t)0.f, (half_t)0.f, (half_t)0.f};
 #pragma unroll
   for (int j = 0; j < NI; ++j)
@@ -121,7 +122,7 @@ __device__ __forceinline__ void load_epi_vecs(const GemmEpi& ep, int N, int n_ba
         v.fc[j][g] = *reinterpret_cast<const float4_t*>(ep.fold_c + nc);
         v.fd[j][g] = *reinterpret_cast<const float4_t*>(ep.fold_d + nc);
       } else {
-        v.bias[j][g] = ep.bias ? *reinterpret_cast<const half4_t*>(ep.bias + nc) : zero;
+        v.bias[j][g] = bias ? *reinterpret_cast<const half4_t*>(bias + nc) : zero;
       }
       if constexpr (EPI == EPI_RESID) {
         v.og[j][g] = *reinterpret_cast<const half4_t*>(ep.out_gamma + nc);
@@ -364,9 +365,9 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_pipe_kernel(
     // Argument order: what the prologue and the K loop need comes first and fits the 14 dwords that are
     // preloaded into SGPRs at wave launch (-amdgpu-kernarg-preload-count), so the first DMA does not
     // wait for a scalar load of the kernel arguments; the epilogue descriptor is fetched behind it.
-    const half_t* __restrict__ A, const half_t* __restrict__ W, half_t* __restrict__ C,
-    const int32_t* __restrict__ a_rows /* = ep.a_rows */, int M, int N, int K, int tiles_n, int n_tiles, int group_m,
-    const GemmEpi ep) {
+    const half_t* __restrict__ A, const half_t* __restrict__ W, const int32_t* __restrict__ a_rows /* = ep.a_rows */,
+    const half_t* __restrict__ bias /* = ep.bias */, int M, int N, int K, int tiles_n, int n_tiles, int group_m,
+    half_t* __restrict__ C, const GemmEpi ep) {
   constexpr int BK = 64, KS = BK / 16;
   constexpr int NWAVES = WGM * WGN;
   constexpr int WM = BM / WGM, WN = BN / WGN;   // wave tile
@@ -412,7 +413,7 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_pipe_kernel(
   // row sums are requested in the last steady round (see below).
   half4_t rres[MI][NI][4];  // dead (and removed by the compiler) in the other epilogue forms
   EpiVecs<NI> vec;
-  if constexpr (EPI == EPI_PLAIN) load_epi_vecs<NI, EPI>(ep, N, n0 + wn * WN, hf, vec);
+  if constexpr (EPI == EPI_PLAIN) load_epi_vecs<NI, EPI>(ep, bias, N, n0 + wn * WN, hf, vec);
   __shared__ float2 red[EPI == EPI_RESID ? WGN * BM : 1];
   float2 psum[MI][kMaxHalfParts];
   constexpr bool kStats = EPI == EPI_FOLD || EPI == EPI_RESID;
@@ -603,7 +604,7 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_pipe_kernel(
 #pragma unroll
     for (int i = 0; i < MI; ++i) { mu[i] = 0.f; rstd[i] = 1.f; }
   }
-  if constexpr (EPI == EPI_FOLD || EPI == EPI_RESID) load_epi_vecs<NI, EPI>(ep, N, n0 + wn * WN, hf, vec);
+  if constexpr (EPI == EPI_FOLD || EPI == EPI_RESID) load_epi_vecs<NI, EPI>(ep, bias, N, n0 + wn * WN, hf, vec);
   if constexpr (EPI == EPI_PARTIAL) {
     store_partial<MI, NI>(acc, ep.partial + (size_t)split * M * N, M, N, m0 + wm * WM, n0 + wn * WN, l32, hf);
   } else {
@@ -672,7 +673,7 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_simple_kernel(const half_t*
   }
   if constexpr (EPI == EPI_RESID) load_resid<1, 1>(ep.resid, M, N, m0 + wm * 32, n0 + wn * 32, l32, hf, rres);
   EpiVecs<1> vec;
-  load_epi_vecs<1, EPI>(ep, N, n0 + wn * 32, hf, vec);
+  load_epi_vecs<1, EPI>(ep, ep.bias, N, n0 + wn * 32, hf, vec);
   store_tile<1, 1, 2, ACT, EPI>(acc, ep, vec, mu, rstd, rres, tn, wn, wm * 32, red, BM, C, M, N, m0 + wm * 32, n0 + wn * 32,
                                 lane, (wave < 2 ? sA : sB) + (wave & 1) * 32 * 40);
 }
@@ -703,7 +704,7 @@ static bt_status launch_pipe(const half_t* A, const half_t* W, half_t* C, int M,
 #endif
   group_m = group_m < 1 ? 1 : (group_m > tiles_m ? tiles_m : group_m);
 #define BT_LAUNCH(ACT, EPI) \
-  gemm_pipe_kernel<BM, BN, WGM, WGN, NS, ACT, EPI><<<grid, block, 0, st>>>(A, W, C, ep.a_rows, M, N, K, tiles_n, (int)n_tiles, group_m, ep)
+  gemm_pipe_kernel<BM, BN, WGM, WGN, NS, ACT, EPI><<<grid, block, 0, st>>>(A, W, ep.a_rows, ep.bias, M, N, K, tiles_n, (int)n_tiles, group_m, C, ep)
   if (epi == EPI_RESID) {
     // only for shapes with one 32x32 block per wavefront (the residual tile lives in registers)
     if constexpr ((BM / WGM) * (BN / WGN) == 32 * 32) BT_LAUNCH(BT_ACT_NONE, EPI_RESID);
@@ -831,7 +832,7 @@ bt_status gemm_splitk_dispatch(const bt_half* A, const bt_half* W, int M, int N,
   group_m = group_m < 1 ? 1 : (group_m > tiles_m ? tiles_m : group_m);
   gemm_pipe_kernel<BM, BN, 2, 2, NS, BT_ACT_NONE, EPI_PARTIAL><<<dim3((unsigned)(n_tiles * ksplit)), dim3(256), 0, st>>>(
       reinterpret_cast<const half_t*>(A), reinterpret_cast<const half_t*>(W), nullptr, nullptr, M, N, K, tiles_n, n_tiles,
-      group_m, ep);
+      group_m, nullptr, ep);
   return launch_status();
 }
 
