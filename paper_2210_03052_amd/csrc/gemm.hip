@@ -366,7 +366,7 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_pipe_kernel(
     // preloaded into SGPRs at wave launch (-amdgpu-kernarg-preload-count), so the first DMA does not
     // wait for a scalar load of the kernel arguments; the epilogue descriptor is fetched behind it.
     const half_t* __restrict__ A, const half_t* __restrict__ W, const int32_t* __restrict__ a_rows /* = ep.a_rows */,
-    const half_t* __restrict__ bias /* = ep.bias */, int M, int N, int K, int tiles_n, int n_tiles, int group_m,
+    const half_t* __restrict__ bias /* = ep.bias */, int M, int N, int K, int tiles_n, int tiles_m, int group_m,
     half_t* __restrict__ C, const GemmEpi ep) {
   constexpr int BK = 64, KS = BK / 16;
   constexpr int NWAVES = WGM * WGN;
@@ -392,10 +392,10 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_pipe_kernel(
   // column by column, so the tiles an XCD works on together form a near-square patch of C whose A
   // and W panels fit its private L2 instead of streaming all of W through every L2.
   // split-K (EPI_PARTIAL): the grid holds ksplit copies of the tile grid, copy s works on K slice s
+  const int n_tiles = tiles_m * tiles_n;
   const int split = EPI == EPI_PARTIAL ? (int)blockIdx.x / n_tiles : 0;
   const int k_len = EPI == EPI_PARTIAL ? K / ep.ksplit : K, k_off = split * k_len;
   const int lin = xcd_remap((int)blockIdx.x - split * n_tiles, n_tiles);
-  const int tiles_m = n_tiles / tiles_n;
   const int per_group = group_m * tiles_n;
   const int first_m = (lin / per_group) * group_m;
   const int rows_here = min(tiles_m - first_m, group_m);
@@ -407,13 +407,12 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_pipe_kernel(
   const int wm = wave / WGN, wn = wave % WGN;
   const int l32 = lane & 31, hf = lane >> 5;
 
-  // The bias of the plain epilogue is requested now (a cheap broadcast load whose latency then hides
-  // behind the K loop).  The folded forms hold more per-column operands than there are registers to park
-  // them across the K loop; they load them right before the epilogue.  Their residual tile and partial
-  // row sums are requested in the last steady round (see below).
+  // The bias of the plain epilogue is requested right behind the first operand slabs (a cheap broadcast
+  // load whose latency then hides behind the K loop).  The folded forms hold more per-column operands than
+  // there are registers to park them across the K loop; they load them right before the epilogue.  Their
+  // residual tile and partial row sums are requested in the last steady round (see below).
   half4_t rres[MI][NI][4];  // dead (and removed by the compiler) in the other epilogue forms
   EpiVecs<NI> vec;
-  if constexpr (EPI == EPI_PLAIN) load_epi_vecs<NI, EPI>(ep, bias, N, n0 + wn * WN, hf, vec);
   __shared__ float2 red[EPI == EPI_RESID ? WGN * BM : 1];
   float2 psum[MI][kMaxHalfParts];
   constexpr bool kStats = EPI == EPI_FOLD || EPI == EPI_RESID;
@@ -476,6 +475,10 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_pipe_kernel(
       st = st + 1 == NS ? 0 : st + 1;
     }
   }
+  // These loads sit between the DMA of the first NS-1 slabs and of the later ones in the in-order queue the
+  // hand-written waits count: a wait for slab k then also waits for as many of the younger entries as there
+  // are loads here -- more than needed, never less, and only for the first slabs.
+  if constexpr (EPI == EPI_PLAIN) load_epi_vecs<NI, EPI>(ep, bias, N, n0 + wn * WN, hf, vec);
 
   // operand read offsets (halves): row*BK + ((2ks+hf) ^ swz(row))*8 ; swz depends on l32 only
   const int swz = (l32 >> 1) & (CPR - 1);
@@ -704,7 +707,7 @@ static bt_status launch_pipe(const half_t* A, const half_t* W, half_t* C, int M,
 #endif
   group_m = group_m < 1 ? 1 : (group_m > tiles_m ? tiles_m : group_m);
 #define BT_LAUNCH(ACT, EPI) \
-  gemm_pipe_kernel<BM, BN, WGM, WGN, NS, ACT, EPI><<<grid, block, 0, st>>>(A, W, ep.a_rows, ep.bias, M, N, K, tiles_n, (int)n_tiles, group_m, C, ep)
+  gemm_pipe_kernel<BM, BN, WGM, WGN, NS, ACT, EPI><<<grid, block, 0, st>>>(A, W, ep.a_rows, ep.bias, M, N, K, tiles_n, tiles_m, group_m, C, ep)
   if (epi == EPI_RESID) {
     // only for shapes with one 32x32 block per wavefront (the residual tile lives in registers)
     if constexpr ((BM / WGM) * (BN / WGN) == 32 * 32) BT_LAUNCH(BT_ACT_NONE, EPI_RESID);
@@ -831,7 +834,7 @@ bt_status gemm_splitk_dispatch(const bt_half* A, const bt_half* W, int M, int N,
   int group_m = (int)(sqrt((double)n_tiles / 8.0) + 0.5);
   group_m = group_m < 1 ? 1 : (group_m > tiles_m ? tiles_m : group_m);
   gemm_pipe_kernel<BM, BN, 2, 2, NS, BT_ACT_NONE, EPI_PARTIAL><<<dim3((unsigned)(n_tiles * ksplit)), dim3(256), 0, st>>>(
-      reinterpret_cast<const half_t*>(A), reinterpret_cast<const half_t*>(W), nullptr, nullptr, M, N, K, tiles_n, n_tiles,
+      reinterpret_cast<const half_t*>(A), reinterpret_cast<const half_t*>(W), nullptr, nullptr, M, N, K, tiles_n, tiles_m,
       group_m, nullptr, ep);
   return launch_status();
 }
