@@ -435,6 +435,49 @@ def test_encoder_fwd_padded_equals_pack_fwd_unpack(bt, name, n_layers, stress):
     assert float(got[torch.from_numpy(~mask).to("cuda:0")].abs().sum()) == 0.0
 
 
+def test_encoder_fwd_graph_replay_equals_eager(bt):
+    """pack + encoder + unpack enqueue kernels only (no allocation, no synchronisation, no memset), so a caller
+    may capture them in a HIP graph: every replay -- with eager work and synchronisation in between, and after
+    the input changed -- gives the bits of the eager calls."""
+    import torch
+    wl = I.WORKLOADS["bert_base_b16_s256"]
+    L = I.draw_lengths(wl)
+    T = int(L.sum())
+    layers = [bt.Layer(I.make_layer_params(wl, i)) for i in range(2)]
+    cu, tok, t = bt.build_offsets(lengths=dev(L), S=wl.S)                      # host sync: stays outside the graph
+    xpad = dev(I.pad_rows(I.make_hidden_packed(wl, T), L, wl.S))
+    ws = torch.empty(bt.layer_workspace_bytes(layers[0], T, wl.B, wl.S), dtype=torch.uint8, device="cuda:0")
+    xp, yp = (torch.empty((T, wl.H), dtype=torch.float16, device="cuda:0") for _ in range(2))
+    out = torch.empty_like(xpad)
+
+    def run():
+        bt.pack(xpad, tok, out=xp)
+        bt.encoder_fwd(layers, xp, cu, wl.S, out=yp, ws=ws)
+        bt.unpack(yp, tok, wl.B, wl.S, out=out)
+
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        run()
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        run()
+    for k in range(3):
+        if k == 2:
+            xpad.mul_(0.5)                                                     # new input, same addresses
+        run()
+        torch.cuda.synchronize()
+        want = out.clone()
+        out.fill_(9.0)
+        ws.fill_(0xFF)                                                         # stale workspace must not matter
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out, want), k
+
+
 def test_encoder_fwd_padded_all_padding(bt):
     import torch
     wl = I.WORKLOADS["layer_b4_s64"]
