@@ -279,6 +279,45 @@ def main():
                                     "step": "build_offsets+encoder_fwd_padded",
                                     "outputs_equal": bool(torch.equal(y_padded2, y_padded))}
 
+    # ---------------- the same step with pack + encoder + unpack replayed from a HIP graph (extra point)
+    # One graph launch instead of ~90 kernel launches per step: if this is faster than `value`, the host of
+    # this box did not keep ahead of the GPU in the eager loop; on a quiet host the two agree.
+    if fold is None:
+        y_padded3 = torch.empty_like(y_padded)
+        cu_g, tok_g, t_g = bt.build_offsets(lengths=lengths_d, S=wl.S)
+
+        def body():
+            xp = bt.pack(x_padded, tok_g, out=x_packed[:t_g])
+            yp = bt.encoder_fwd(layers, xp, cu_g, wl.S, out=y_packed[:t_g], ws=ws)
+            bt.unpack(yp, tok_g, wl.B, wl.S, out=y_padded3)
+
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            body()
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            body()
+
+        def step_graph():
+            bt.build_offsets(lengths=lengths_d, S=wl.S)      # same offsets every step here; still computed and waited for
+            graph.replay()
+
+        for _ in range(max(args.warmup // 2, 2)):
+            step_graph()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            step_graph()
+        torch.cuda.synchronize()
+        dtg = time.perf_counter() - t0
+        out["graph_replay"] = {"value": round(wl.B * args.steps / dtg, 1), "unit": "sequences/s",
+                               "ms_per_step": round(dtg * 1e3 / args.steps, 4),
+                               "step": "build_offsets + one HIP graph of pack+encoder_fwd+unpack",
+                               "outputs_equal": bool(torch.equal(y_padded3, y_padded))}
+
     # ---------------- throughput with two batches in flight (extra point, not `value`)
     # One batch at a time leaves the GPU idle at every kernel boundary (~2.5 us per dependent launch) and
     # while the host waits for the token count in build_offsets.  A server keeps a second batch in flight
