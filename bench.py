@@ -176,7 +176,33 @@ def sweep(args):
     ln_separate = graph_us(lambda: nn.layer_norm((x + b_h) + r, (H,), g_h, be_h, 1e-12))
     gelu_fused = graph_us(lambda: bt.gemm_bias_act(a, w1, b_f, 1, out=y_f))
     gelu_separate = graph_us(lambda: nn.gelu(bt.gemm_bias_act(a, w1, None, 0, out=y_f) + b_f))
-    fusion = {"tokens": T, "hidden": H, "ffn": F,
+    # Attention (the shape of the fused-MHA figures, Sec. IV-C): the variable-length fused kernel on the packed
+    # batch against padded attention through torch -- three launches with the S x S logits in memory
+    # (batched product, masked softmax, batched product), and torch's own fused padded kernel where this
+    # torch build has one.  Stand-ins again; same lengths, heads and head size.
+    attention = []
+    for wname in ("bert_base_b16_s256", "bert_base_b16_s1024"):
+        w = I.WORKLOADS[wname]
+        Lw = I.draw_lengths(w)
+        Tw, S, B, nh = int(Lw.sum()), w.S, w.B, w.heads
+        qkv = h16(Tw, 3 * nh * 64)
+        cu = dev(np.concatenate([[0], np.cumsum(Lw)]).astype(np.int32))
+        o = torch.empty((Tw, nh * 64), dtype=torch.float16, device="cuda:0")
+        fused = graph_us(lambda: bt.varlen_mha(qkv, cu, S, nh, out=o), per_graph=10, replays=10)
+        q, k, v = (torch.randn((B, nh, S, 64), dtype=torch.float16, device="cuda:0") for _ in range(3))
+        keep = dev(np.arange(S)[None, :] < Lw[:, None])[:, None, None, :]          # [B,1,1,S] valid keys
+        neg = torch.zeros((B, 1, 1, S), dtype=torch.float16, device="cuda:0").masked_fill(~keep, float("-inf"))
+        three = graph_us(lambda: torch.matmul(torch.softmax(torch.matmul(q, k.transpose(-1, -2)) * 0.125 + neg, -1), v),
+                         per_graph=10, replays=10)
+        row = {"workload": wname, "valid_tokens": Tw, "fused_varlen_us": round(fused, 2),
+               "padded_three_launches_us": round(three, 2)}
+        try:
+            sdpa = graph_us(lambda: nn.scaled_dot_product_attention(q, k, v, attn_mask=neg), per_graph=10, replays=10)
+            row["padded_torch_fused_us"] = round(sdpa, 2)
+        except Exception as e:                                                     # no such kernel in this build
+            row["padded_torch_fused_us"] = None
+        attention.append(row)
+    fusion = {"tokens": T, "hidden": H, "ffn": F, "attention": attention,
               "add_bias_residual_layernorm_us": {"fused": round(ln_fused, 2), "separate_3_launches": round(ln_separate, 2),
                                                  "saved": round(1 - ln_fused / ln_separate, 3)},
               "gemm_add_bias_gelu_us": {"fused": round(gelu_fused, 2), "separate_3_launches": round(gelu_separate, 2),
