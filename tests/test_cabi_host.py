@@ -140,3 +140,27 @@ def test_gemm_kernels_use_no_scratch():
     spilled = [n for n, b in sizes if int(b) != 0]
     assert not spilled, spilled
 
+
+def test_gelu_polynomial_in_the_kernel_source():
+    """The GELU epilogue approximates Phi(-a) by exp2 of a polynomial whose coefficients are literals in
+    gemm.hip.  Read them from the source and evaluate the same float32 Horner scheme here: within 1e-6 of
+    x Phi(x) (erf from scipy) on a dense grid, and so negative beyond the fitted range that exp2 underflows
+    -- so a mistyped coefficient fails without a GPU."""
+    import numpy as np
+    from scipy.special import erf
+    src = open(os.path.join(ROOT, "paper_2210_03052_amd", "csrc", "gemm.hip")).read()
+    body = src[src.index("float gelu_erf(float x)"):src.index("float gelu_tanh(float x)")]
+    first = re.search(r"fmaf\(a, (-?[0-9.e+-]+)f, (-?[0-9.e+-]+)f\)", body)
+    rest = re.findall(r"fmaf\(a, p, (-?[0-9.e+-]+)f\)", body)
+    coef = [np.float32(first.group(1)), np.float32(first.group(2))] + [np.float32(c) for c in rest]
+    assert len(coef) == 8
+    x = np.concatenate([np.linspace(-12, 12, 400001), [-1e4, 1e4, -65504.0, 65504.0]]).astype(np.float32)
+    a = np.abs(x)
+    p = np.zeros_like(a)
+    with np.errstate(over="ignore"):
+        for c in coef:
+            p = (p * a + c).astype(np.float32)
+    got = np.maximum(x, 0) - a * np.exp2(p).astype(np.float32)
+    ref = x.astype(np.float64) * 0.5 * (1.0 + erf(x.astype(np.float64) / np.sqrt(2.0)))
+    assert np.abs(got - ref).max() <= 1e-6
+    assert p[a >= 9].max() < -60 and (np.diff(p[:400001][x[:400001] >= 0]) <= 0).all()
