@@ -429,6 +429,8 @@ def main():
             ("unpack", "hbm", 2.0 * T * H + 2.0 * wl.B * wl.S * H,
              bind(lib.bt_unpack, ptr(y2), ptr(tok), T, wl.B, wl.S, H, ptr(y_padded), st)),
         ]
+        gemm_shapes = {"gemm0_qkv_bias": (T, 3 * H, H, 0), "gemm1_proj": (T, H, H, 0),
+                       "gemm2_bias_gelu": (T, F, H, 1), "gemm3_ffn_down": (T, H, F, 0)}
         kernels = []
         for name, bound, work, fn in steps:
             if fn() != 0:
@@ -442,6 +444,15 @@ def main():
             kernels.append({"kernel": name, "bound": bound, "us": round(us, 2), "launches_per_step": per_step,
                             "achieved": round(ach, 2), "peak": peak, "unit": unit, "frac": round(ach / peak, 4),
                             "work_per_launch": work})
+            if name in gemm_shapes:
+                # tile-quantisation ceiling of this product: useful share of the tiles' area times the share of
+                # the 256 compute units that the last round of tiles occupies
+                M_, N_, K_, act_ = gemm_shapes[name]
+                bm, bn = bt.gemm_tile_shape(M_, N_, K_, act_)
+                tiles = -(-M_ // bm) * -(-N_ // bn)
+                rounds = -(-tiles // 256)
+                kernels[-1].update({"tile": f"{bm}x{bn}", "tiles": tiles, "rounds_of_256_cus": rounds,
+                                    "tile_quantisation_ceiling": round(M_ * N_ / (tiles * bm * bn) * tiles / (rounds * 256), 4)})
         dom = max(kernels, key=lambda k: k["us"] * k["launches_per_step"])
         out["roofline"] = {"kernel": dom["kernel"], "bound": dom["bound"], "achieved": dom["achieved"],
                            "peak": dom["peak"], "unit": dom["unit"], "frac": dom["frac"],

@@ -129,6 +129,14 @@ bt_status bt_gemm_bias_act(const bt_half* d_A, const bt_half* d_W, const bt_half
                            bt_act act, bt_half* d_C, bt_stream stream);
 
 /*
+ * Which block tile bt_gemm_bias_act uses for an M x N x K product (host only, nothing is launched): the
+ * library picks among 256x128 ... 64x64 by a cost model of rounds of tiles over the 256 compute units.
+ * For reports: with it a caller can state the tile-quantisation ceiling of a measured product,
+ * M*N / (tiles * bm * bn) * tiles / (ceil(tiles/256) * 256).  Same argument checks as bt_gemm_bias_act.
+ */
+bt_status bt_gemm_tile_shape(int M, int N, int K, bt_act act, int* bm, int* bn);
+
+/*
  * Fused add-bias + residual + LayerNorm, Sec. III-C1:
  *   y[i,:] = LN(x[i,:] + bias + residual[i,:]) * gamma + beta,   one pass over memory.
  * x, residual, y fp16 [T,H]; bias, gamma, beta fp16 [H]; bias may be NULL.

@@ -58,6 +58,7 @@ _SIGNATURES = {
     "bt_encoder_prepare": (_c.c_int, [_c.POINTER(bt_layer), _c.c_int, _c.c_void_p, _c.c_size_t, _c.c_void_p]),
     "bt_encoder_fwd": (_c.c_int, [_c.POINTER(bt_layer), _c.c_int, _c.c_void_p, _c.c_void_p, _c.c_void_p, _c.c_int,
                                   _c.c_int, _c.c_int, _c.c_void_p, _c.c_void_p, _c.c_size_t, _c.c_void_p]),
+    "bt_gemm_tile_shape": (_c.c_int, [_c.c_int, _c.c_int, _c.c_int, _c.c_int, _c.POINTER(_c.c_int), _c.POINTER(_c.c_int)]),
     "bt_encoder_fwd_padded": (_c.c_int, [_c.POINTER(bt_layer), _c.c_int, _c.c_void_p, _c.c_void_p, _c.c_void_p,
                                          _c.c_int, _c.c_int, _c.c_int, _c.c_void_p, _c.c_void_p, _c.c_size_t,
                                          _c.c_void_p]),
@@ -233,6 +234,13 @@ def gemm_bias_act(a, w, bias=None, act=ACT_NONE, out=None):
         out = torch.empty((M, N), dtype=torch.float16, device=a.device)
     _call("bt_gemm_bias_act", _ptr(a), _ptr(w), _ptr(bias), M, N, K, int(act), _ptr(out), _stream())
     return out
+
+
+def gemm_tile_shape(M, N, K, act=ACT_NONE):
+    """bt_gemm_tile_shape: the (BM, BN) block tile bt_gemm_bias_act uses for this product."""
+    bm, bn = _c.c_int(0), _c.c_int(0)
+    _call("bt_gemm_tile_shape", int(M), int(N), int(K), int(act), _c.byref(bm), _c.byref(bn))
+    return bm.value, bn.value
 
 
 def add_bias_residual_layernorm(x, bias, residual, gamma, beta, eps, out=None):

@@ -749,6 +749,32 @@ static bt_status launch_simple(const half_t* A, const half_t* W, half_t* C, int 
   return launch_status();
 }
 
+// Tile choice by a small cost model.  Every tile shape is bound by how fast a compute unit ingests
+// operand slabs (~85 GB/s here whatever the shape), so one 64-deep slab costs a time proportional to
+// BM+BN, and the grid runs in ceil(tiles / 256) rounds of one tile per compute unit.  slab_us and
+// epi_us (epilogue + pipeline fill) were measured per shape on MI355X; GELU adds to the epilogue.
+// Returns the index into kGemmTiles.  K % 64 == 0.
+struct GemmTile { int bm, bn; float slab_us, epi_us; bool one_block_per_wave; };
+static const GemmTile kGemmTiles[6] = {{256, 128, 0.607f, 2.2f, false}, {192, 128, 0.482f, 1.5f, false},
+                                       {128, 128, 0.384f, 1.5f, false}, {128, 64, 0.298f, 0.78f, true},
+                                       {64, 128, 0.287f, 0.84f, true},  {64, 64, 0.183f, 0.4f, true}};
+static int gemm_tile_choice(int M, int N, int K, bt_act act, int epi) {
+  int best = -1;
+  float best_us = 0.f;
+  for (int c = 0; c < 6; ++c) {
+    const GemmTile& t = kGemmTiles[c];
+    // EPI_RESID keeps a residual tile per lane across the last slabs: only the shapes with one 32x32
+    // block per wavefront have the registers for it
+    if (epi == EPI_RESID && !t.one_block_per_wave) continue;
+    const long long tiles = (long long)((M + t.bm - 1) / t.bm) * ((N + t.bn - 1) / t.bn);
+    const long long rounds = (tiles + 255) / 256;
+    const float act_us = act != BT_ACT_NONE ? 9e-5f * t.bm * t.bn : 0.f;
+    const float us = (float)rounds * ((float)(K / 64) * t.slab_us + t.epi_us + act_us);
+    if (best < 0 || us < best_us) { best = c; best_us = us; }
+  }
+  return best;
+}
+
 bt_status gemm_dispatch(const bt_half* A, const bt_half* W, int M, int N, int K, bt_act act, int epi,
                         const GemmEpi& ep, bt_half* C, hipStream_t st, int* np_out) {
   const half_t* a = reinterpret_cast<const half_t*>(A);
@@ -756,7 +782,6 @@ bt_status gemm_dispatch(const bt_half* A, const bt_half* W, int M, int N, int K,
   half_t* c = reinterpret_cast<half_t*>(C);
   if (epi == EPI_RESID && act != BT_ACT_NONE) return BT_ERR_INVALID_ARG;
   if ((K % 64) != 0) return launch_simple(a, w, c, M, N, K, act, epi, ep, st, np_out);
-  auto tiles = [&](int bm, int bn) { return (long long)((M + bm - 1) / bm) * ((N + bn - 1) / bn); };
 #define BT_PIPE(BM, BN, WGM, WGN, NS) launch_pipe<BM, BN, WGM, WGN, NS>(a, w, c, M, N, K, act, epi, ep, st, np_out)
 #ifdef BT_TUNING
   switch (g_gemm_cfg) {  // tile shapes the sweeps compared
@@ -777,25 +802,7 @@ bt_status gemm_dispatch(const bt_half* A, const bt_half* W, int M, int N, int K,
     default: break;
   }
 #endif
-  // Tile choice by a small cost model.  Every tile shape is bound by how fast a compute unit ingests
-  // operand slabs (~85 GB/s here whatever the shape), so one 64-deep slab costs a time proportional to
-  // BM+BN, and the grid runs in ceil(tiles / 256) rounds of one tile per compute unit.  slab_us and
-  // epi_us (epilogue + pipeline fill) were measured per shape on MI355X; GELU adds to the epilogue.
-  struct Cand { int bm, bn; float slab_us, epi_us; bool one_block_per_wave; };
-  static const Cand cands[6] = {{256, 128, 0.607f, 2.2f, false}, {192, 128, 0.482f, 1.5f, false},
-                                {128, 128, 0.384f, 1.5f, false}, {128, 64, 0.298f, 0.78f, true},
-                                {64, 128, 0.287f, 0.84f, true},  {64, 64, 0.183f, 0.4f, true}};
-  int best = -1;
-  float best_us = 0.f;
-  for (int c = 0; c < 6; ++c) {
-    // EPI_RESID keeps a residual tile per lane across the last slabs: only the shapes with one 32x32
-    // block per wavefront have the registers for it
-    if (epi == EPI_RESID && !cands[c].one_block_per_wave) continue;
-    const long long rounds = (tiles(cands[c].bm, cands[c].bn) + 255) / 256;
-    const float act_us = act != BT_ACT_NONE ? 9e-5f * cands[c].bm * cands[c].bn : 0.f;
-    const float us = (float)rounds * ((float)(K / 64) * cands[c].slab_us + cands[c].epi_us + act_us);
-    if (best < 0 || us < best_us) { best = c; best_us = us; }
-  }
+  const int best = gemm_tile_choice(M, N, K, act, epi);
   switch (best) {
     case 0: return BT_PIPE(256, 128, 4, 2, 3);
     case 1: return BT_PIPE(192, 128, 2, 4, 3);
@@ -857,4 +864,17 @@ extern "C" bt_status bt_gemm_bias_act(const bt_half* d_A, const bt_half* d_W, co
   bt::GemmEpi ep;
   ep.bias = reinterpret_cast<const bt::half_t*>(d_bias);
   return bt::gemm_dispatch(d_A, d_W, M, N, K, act, bt::EPI_PLAIN, ep, d_C, static_cast<hipStream_t>(stream), nullptr);
+}
+
+extern "C" bt_status bt_gemm_tile_shape(int M, int N, int K, bt_act act, int* bm, int* bn) {
+  if (M < 0 || N < 1 || K < 1 || (N % 8) != 0 || (K % 8) != 0 || !bm || !bn) return BT_ERR_INVALID_ARG;
+  if (act != BT_ACT_NONE && act != BT_ACT_GELU_ERF && act != BT_ACT_GELU_TANH) return BT_ERR_INVALID_ARG;
+  *bm = *bn = 64;  // the register-staged fallback kernel: K not a multiple of 64, or shorter than the pipeline
+  if ((K % 64) != 0) return BT_OK;
+  const int c = bt::gemm_tile_choice(M, N, K, act, bt::EPI_PLAIN);
+  const bt::GemmTile& t = bt::kGemmTiles[c];
+  if (K / 64 < (c < 2 ? 3 : 4) - 1) return BT_OK;  // stages of that shape: 3 for the two widest, else 4
+  *bm = t.bm;
+  *bn = t.bn;
+  return BT_OK;
 }

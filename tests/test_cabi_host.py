@@ -164,3 +164,18 @@ def test_gelu_polynomial_in_the_kernel_source():
     ref = x.astype(np.float64) * 0.5 * (1.0 + erf(x.astype(np.float64) / np.sqrt(2.0)))
     assert np.abs(got - ref).max() <= 1e-6
     assert p[a >= 9].max() < -60 and (np.diff(p[:400001][x[:400001] >= 0]) <= 0).all()
+
+
+def test_gemm_tile_shape_query_is_host_only():
+    """bt_gemm_tile_shape answers on the host (no GPU needed): the shapes the cost model picks for the four
+    products of the headline layer, the 128x128 tile just past one round of the 64x128 tiles, the fallback
+    for a K that is not a multiple of 64, and the argument checks."""
+    assert bt.gemm_tile_shape(2308, 2304, 768) == (192, 128)
+    assert bt.gemm_tile_shape(2308, 768, 768) == (64, 128)
+    assert bt.gemm_tile_shape(2308, 3072, 768, bt.ACT_GELU_ERF) == (256, 128)
+    assert bt.gemm_tile_shape(2308, 768, 3072) == (64, 128)
+    assert bt.gemm_tile_shape(2699, 768, 3072) == (128, 128)
+    assert bt.gemm_tile_shape(100, 768, 72) == (64, 64)
+    for bad in ((10, 7, 64), (10, 8, 60), (-1, 8, 64)):
+        with pytest.raises(bt.BtError):
+            bt.gemm_tile_shape(*bad)
