@@ -48,11 +48,14 @@ __global__ __launch_bounds__(256) void bias_residual_ln_kernel(
   const size_t rbase = res_rows ? (size_t)res_rows[row] * H : base;
 
   float v[CPL][8];
+  half8_t gm[CPL], bt[CPL];  // gamma and beta are requested with the row, not after the two reductions
   float sum = 0.f;
 #pragma unroll
   for (int i = 0; i < CPL; ++i) {
     const int c = lane + i * kWave;
     if (c < chunks) {
+      gm[i] = *reinterpret_cast<const half8_t*>(gamma + c * 8);
+      bt[i] = *reinterpret_cast<const half8_t*>(beta + c * 8);
       const half8_t r = STREAM ? __builtin_nontemporal_load(reinterpret_cast<const half8_t*>(residual + rbase + c * 8))
                                : *reinterpret_cast<const half8_t*>(residual + rbase + c * 8);
       if constexpr (PART) {
@@ -101,11 +104,9 @@ __global__ __launch_bounds__(256) void bias_residual_ln_kernel(
   for (int i = 0; i < CPL; ++i) {
     const int c = lane + i * kWave;
     if (c < chunks) {
-      const half8_t g = *reinterpret_cast<const half8_t*>(gamma + c * 8);
-      const half8_t b = *reinterpret_cast<const half8_t*>(beta + c * 8);
       half8_t o;
 #pragma unroll
-      for (int e = 0; e < 8; ++e) o[e] = (half_t)((v[i][e] - mean) * rstd * (float)g[e] + (float)b[e]);
+      for (int e = 0; e < 8; ++e) o[e] = (half_t)((v[i][e] - mean) * rstd * (float)gm[i][e] + (float)bt[i][e]);
       if (STREAM) __builtin_nontemporal_store(o, reinterpret_cast<half8_t*>(y + obase + c * 8));
       else store_through(y + obase + c * 8, __builtin_bit_cast(uint4_t, o));  // see store_through
     }
