@@ -15,7 +15,8 @@ design notes of the repository):
   * softmax scale is 1/sqrt(d_k) as in eq. (1), d_k = head size;
   * masked keys are excluded from the softmax (logit = -inf);
   * post-LayerNorm: LN(x + sublayer(x)), biased variance, eps a parameter;
-  * GELU is the exact erf form  x/2 (1 + erf(x/sqrt 2));
+  * GELU is the exact erf form  x/2 (1 + erf(x/sqrt 2)); the tanh form of the same
+    citation is available as ``gelu_tanh`` / ``gelu_kind="tanh"`` (never the default);
   * outputs at padded positions are zero;
   * a stack of layers feeds the unrounded fp64 output to the next layer.
 
@@ -93,6 +94,13 @@ def gelu(x):
     """Exact GELU, x * Phi(x) (activation of Sec. III-C2)."""
     x = np.asarray(x, dtype=F64)
     return 0.5 * x * (1.0 + _erf(x / np.sqrt(2.0)))
+
+
+def gelu_tanh(x):
+    """The tanh form of GELU given beside the exact one in the work Sec. III-C2 cites for the
+    activation:  x/2 (1 + tanh(sqrt(2/pi) (x + 0.044715 x^3))).  Selected by ``gelu_kind = "tanh"``."""
+    x = np.asarray(x, dtype=F64)
+    return 0.5 * x * (1.0 + np.tanh(np.sqrt(2.0 / np.pi) * (x + 0.044715 * x ** 3)))
 
 
 def layer_norm(x, gamma, beta, eps):
@@ -180,6 +188,9 @@ class LayerWeights:
             setattr(self, f, np.asarray(kw[f], dtype=F64))
         self.heads = int(kw["heads"])
         self.eps = float(kw.get("eps", 1e-12))
+        self.gelu_kind = str(kw.get("gelu_kind", "erf"))           # "erf" (exact, default) | "tanh"
+        if self.gelu_kind not in ("erf", "tanh"):
+            raise ValueError("gelu_kind must be 'erf' or 'tanh'")
 
 
 def encoder_layer(x_padded, mask, w: LayerWeights):
@@ -197,7 +208,8 @@ def encoder_layer(x_padded, mask, w: LayerWeights):
     attn = attention_padded(q, k, v, mask, w.heads)
     proj = attn @ w.w_o.T + w.b_o
     y1 = layer_norm(x + proj, w.ln0_g, w.ln0_b, w.eps)
-    g = gelu(y1 @ w.w_1.T + w.b_1)
+    act = gelu if w.gelu_kind == "erf" else gelu_tanh
+    g = act(y1 @ w.w_1.T + w.b_1)
     ffn = g @ w.w_2.T + w.b_2
     y2 = layer_norm(y1 + ffn, w.ln1_g, w.ln1_b, w.eps)
     y2 = y2 * (np.asarray(mask) != 0)[..., None]

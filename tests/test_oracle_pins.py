@@ -209,6 +209,47 @@ def test_gelu_closed_forms():
     assert abs(O.gelu(1.0) - 0.8413447460685429) < 1e-12      # Phi(1)
 
 
+def test_gelu_tanh_form_pins():
+    """The tanh form: closed forms, the odd-part identity (tanh is odd), torch's float64 CPU routine as an
+    independent library implementation, and the known distance to the exact form (largest near |x| = 2.7,
+    4.7e-4; identical at 0 and in both tails)."""
+    import torch
+    assert O.gelu_tanh(0.0) == 0.0
+    assert abs(O.gelu_tanh(10.0) - 10.0) < 1e-12 and abs(O.gelu_tanh(-10.0)) < 1e-12
+    x = np.linspace(-6, 6, 2401)
+    assert np.abs(O.gelu_tanh(x) - O.gelu_tanh(-x) - x).max() < 1e-14
+    ref = torch.nn.functional.gelu(torch.tensor(x, dtype=torch.float64), approximate="tanh").numpy()
+    assert np.abs(O.gelu_tanh(x) - ref).max() < 1e-14
+    # scalar re-computation at one point
+    u = math.sqrt(2 / math.pi) * (1.5 + 0.044715 * 1.5 ** 3)
+    assert abs(O.gelu_tanh(1.5) - 0.75 * (1 + math.tanh(u))) < 1e-15
+    gap = np.abs(O.gelu_tanh(x) - O.gelu(x))
+    assert 4.5e-4 < gap.max() < 5e-4 and 2.5 < abs(x[gap.argmax()]) < 2.9
+    assert gap[np.abs(x) > 5.5].max() < 1e-7
+
+
+def test_layer_gelu_kind_selects_the_activation():
+    """gelu_kind reaches the FFN and nothing else: the two layers differ by exactly the FFN-down image of the
+    activation difference, pushed through the last LayerNorm (checked by recomputing that path by hand)."""
+    rng = np.random.default_rng(21)
+    H, heads, F, S = 8, 2, 16, 4
+    p = _tiny_layer(rng, H, heads, F)
+    x = rng.normal(size=(1, S, H)) * 2
+    mask = np.ones((1, S), np.int32)
+    a = O.encoder_layer(x, mask, O.LayerWeights(**p))
+    b = O.encoder_layer(x, mask, O.LayerWeights(**p, gelu_kind="tanh"))
+    assert 0 < np.abs(a - b).max() < 5e-2
+    w = O.LayerWeights(**p)
+    qkv = x @ w.w_qkv.T + w.b_qkv
+    attn = O.attention_padded(qkv[..., :H], qkv[..., H:2 * H], qkv[..., 2 * H:], mask, heads)
+    y1 = O.layer_norm(x + attn @ w.w_o.T + w.b_o, w.ln0_g, w.ln0_b, w.eps)
+    h = y1 @ w.w_1.T + w.b_1
+    want = O.layer_norm(y1 + O.gelu_tanh(h) @ w.w_2.T + w.b_2, w.ln1_g, w.ln1_b, w.eps)
+    assert np.abs(b - want).max() < 1e-13
+    with pytest.raises(ValueError):
+        O.LayerWeights(**p, gelu_kind="relu")
+
+
 # ---------------------------------------------------------------- whole layer
 def _tiny_layer(rng, H, heads, F, stress=True):
     p = dict(
