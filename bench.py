@@ -4,13 +4,18 @@
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME]
 
 A step is one pass of the whole hot path over one synthetic batch that is
-already resident in HBM: bt_build_offsets (with its one host sync) -> bt_pack ->
-bt_encoder_fwd (all layers) -> bt_unpack.  Prints ONE JSON line:
-sequences/s (whole job), plus
+already resident in HBM: bt_build_offsets (prefix sum; its token count is waited
+for on the host) -> bt_encoder_fwd_padded (all layers; the pack is fused into
+the first GEMM's operand load and the first residual read, the unpack into the
+last LayerNorm's store).  Prints ONE JSON line: sequences/s (whole job; mean over
+the timed steps, with the median and the minimum step beside it), plus
   "roofline"     the dominant kernel's achieved rate against MI355X's published
-                 peak, from HIP-event timing of that kernel in this process,
+                 peak, from HIP-event timing of that kernel in this process
+                 (--peaks adds the rates this GPU sustains in an MFMA-only loop
+                 and a read-only stream as measured denominators),
   "kernels"      the same figures for every kernel of the layer,
   "cpu_baseline" the fp64 numpy oracle timed on this machine's host cores.
+The attention-alone workload (mha_b16_s256) times bt_varlen_mha as the step.
 """
 from __future__ import annotations
 
@@ -28,17 +33,21 @@ sys.path.insert(0, ROOT)
 PEAK_MFMA_F16 = 2500.0   # TFLOP/s, dense fp16 MFMA, published
 PEAK_HBM = 8000.0        # GB/s, published
 
-# HBM bytes per launch (fetched + written) from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this
-# script, scaled by the same counters' reading of a 1 GiB copy; see profiles/ for the runs.
-MEASURED_TRAFFIC = {
-    ("bert_base_b16_s256", "gemm0_qkv_bias"): 35989 * 1024,
-    ("bert_base_b16_s256", "varlen_mha"): 20582 * 1024,
-    ("bert_base_b16_s256", "gemm1_proj"): 16892 * 1024,
-    ("bert_base_b16_s256", "bias_residual_ln0"): 10455 * 1024,
-    ("bert_base_b16_s256", "gemm2_bias_gelu"): 41553 * 1024,
-    ("bert_base_b16_s256", "gemm3_ffn_down"): 56984 * 1024,
-    ("bert_base_b16_s256", "bias_residual_ln1"): 10455 * 1024,
-}
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "hbm_traffic.txt")
+
+
+def measured_traffic(workload, kernel):
+    """HBM-side bytes per launch of `kernel` in `workload` from the rocprofv3 FETCH_SIZE / WRITE_SIZE summary
+    under profiles/ (written by paper_2210_03052_amd.profile_summary), or None when that pair was not profiled."""
+    kernel = {"bias_residual_ln0": "bias_residual_ln", "bias_residual_ln1": "bias_residual_ln"}.get(kernel, kernel)
+    try:
+        for line in open(TRAFFIC_FILE):
+            f = line.split()
+            if len(f) == 5 and f[0] == workload and f[1] == kernel:
+                return int(f[4])
+    except OSError:
+        pass
+    return None
 
 
 def parse():
@@ -59,6 +68,11 @@ def parse():
                          "single-layer batch-1 points of Table III, plus fused against separate element-wise launches "
                          "(LayerNorm, GELU) at the headline shape; prints one JSON line")
     ap.add_argument("--calibrate-copy", action="store_true", help="also run one 1 GiB device copy (counter scaling)")
+    ap.add_argument("--peaks", action="store_true",
+                    help="also measure what this GPU sustains in an MFMA-only fp16 loop and in a read-only stream, and "
+                         "report the roofline against those measured rates as well as the published ones")
+    ap.add_argument("--separate-pack-unpack", action="store_true",
+                    help="time bt_pack + bt_encoder_fwd + bt_unpack as the step instead of bt_encoder_fwd_padded")
     return ap.parse_args()
 
 
@@ -97,14 +111,11 @@ def sweep(args):
         x_padded = dev(I.pad_rows(I.make_hidden_packed(base, T), lengths, S))
         ld = dev(lengths.astype(np.int32))
         ws = torch.empty(bt.layer_workspace_bytes(layers[0], B * S, B, S), dtype=torch.uint8, device="cuda:0")
-        xp, yp = (torch.empty((B * S, H), dtype=torch.float16, device="cuda:0") for _ in range(2))
         ypad = torch.empty((B, S, H), dtype=torch.float16, device="cuda:0")
 
         def step():
             cu, tok, t = bt.build_offsets(lengths=ld, S=S)
-            x = bt.pack(x_padded, tok, out=xp[:t])
-            y = bt.encoder_fwd(layers[:n_layers], x, cu, S, out=yp[:t], ws=ws)
-            bt.unpack(y, tok, B, S, out=ypad)
+            bt.encoder_fwd_padded(layers[:n_layers], x_padded, tok, cu, out=ypad, ws=ws)
 
         for _ in range(5):
             step()
@@ -134,8 +145,8 @@ def sweep(args):
         us = time_launches(torch, lambda: bt.encoder_layer_fwd(layers[0], x, cu, S, out=y, ws=ws), 200)
         table3.append({"batch": 1, "seq": S, "layers": 1, "ms_layer_only": round(us / 1e3, 4),
                        "ms_whole_step": round(ms, 4), "paper_a100_ms": paper_ms,
-                       "note": "layer only = bt_encoder_layer_fwd (7 launches, HIP events); whole step adds "
-                               "build_offsets + pack + unpack"})
+                       "note": "layer only = bt_encoder_layer_fwd (HIP events); whole step = build_offsets + "
+                               "encoder_fwd_padded (pack / unpack fused into the first / last kernels)"})
     # Kernel fusion at the headline shape -- the shape of the add-bias + LayerNorm and add-bias + GELU figures
     # (Sec. IV-A, IV-B).  "Separate" runs the same arithmetic as one launch per element-wise operation, with
     # torch's element-wise kernels standing in for the unfused ones (they are not part of the library).
@@ -215,6 +226,162 @@ def sweep(args):
                       "length_law": "U[ceil(0.2 S), S] (mean 0.6 S)", "sweep": rows, "table3_single_layer": table3}))
 
 
+def timed_steps(torch, step, steps, warmup):
+    """Runs `warmup` untimed and `steps` timed steps.  Returns (seconds for all timed steps, per-step seconds).
+    The total is the wall clock between two device synchronisations around exactly `steps` steps.  A step begins
+    with a call that waits on the host for a device result that is ordered behind the previous step's kernels
+    (the token count of bt_build_offsets), so the host timestamps taken at the top of each step are paced by the
+    GPU and their differences are per-step durations without any extra synchronisation."""
+    for _ in range(warmup):
+        step()
+    torch.cuda.synchronize()
+    stamps = []
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        stamps.append(time.perf_counter())
+        step()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    stamps.append(t1)
+    per = [b - a for a, b in zip(stamps[:-1], stamps[1:])]
+    return t1 - t0, per
+
+
+def step_stats(B, total_s, per_step_s):
+    n = len(per_step_s)
+    srt = sorted(per_step_s)
+    med = srt[n // 2] if n % 2 else 0.5 * (srt[n // 2 - 1] + srt[n // 2])
+    return {"value": round(B * n / total_s, 1), "ms_per_step": round(total_s * 1e3 / n, 4),
+            "ms_per_step_median": round(med * 1e3, 4), "ms_per_step_min": round(srt[0] * 1e3, 4)}
+
+
+def measure_peaks(torch):
+    """What this GPU sustains: an MFMA-only fp16 loop (constant operands; random operands, under which the clock
+    settles lower) and a read-only stream over 2 GiB."""
+    import ctypes as C
+    path = os.path.join(ROOT, "paper_2210_03052_amd", "libbt_peaks.so")
+    if not os.path.exists(path):
+        raise RuntimeError(f"{path} is not built: run `python -m paper_2210_03052_amd.build`")
+    lib = C.CDLL(path)
+    lib.bt_peak_mfma_f16.argtypes = [C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_void_p]
+    lib.bt_peak_stream_read.argtypes = [C.c_void_p, C.c_size_t, C.c_int, C.c_void_p, C.c_void_p]
+    st = C.c_void_p(torch.cuda.current_stream().cuda_stream)
+    blocks, iters = 256 * 8, 4096
+    sink = torch.empty(blocks * 256, dtype=torch.float32, device="cuda:0")
+    flop = blocks * 4 * iters * 4 * 2.0 * 32 * 32 * 16
+    out = {}
+    for pattern, key in ((0, "mfma_f16_constant_operands_tflops"), (1, "mfma_f16_random_operands_tflops")):
+        fn = lambda: lib.bt_peak_mfma_f16(iters, blocks, pattern, C.c_void_p(sink.data_ptr()), st)
+        if fn() != 0:
+            raise RuntimeError("bt_peak_mfma_f16 failed")
+        us = time_launches(torch, fn, 10, warm=3)
+        out[key] = round(flop / us / 1e6, 1)
+    nbytes = 2 << 30
+    src = torch.empty(nbytes, dtype=torch.uint8, device="cuda:0")
+    src.random_(0, 255)
+    rb = 256 * 16
+    rsink = torch.empty(rb * 256, dtype=torch.int32, device="cuda:0")
+    fn = lambda: lib.bt_peak_stream_read(C.c_void_p(src.data_ptr()), C.c_size_t(nbytes), rb, C.c_void_p(rsink.data_ptr()), st)
+    if fn() != 0:
+        raise RuntimeError("bt_peak_stream_read failed")
+    us = time_launches(torch, fn, 10, warm=3)
+    out["hbm_read_stream_GBps"] = round(nbytes / us / 1e3, 1)
+    out["note"] = ("MFMA: 2048 workgroups x 4 wavefronts x 4096 x 4 independent 32x32x16 fp16 MFMAs on register "
+                   "operands; read: 2 GiB, 16 bytes per lane, non-temporal")
+    del src
+    return out
+
+
+def cpu_baseline_encoder(wl, L, x_packed_h, params, nl):
+    """The oracle as it stands on this machine's cores: whole batch, up to 12 layers timed once, scaled to nl."""
+    from oracle import bt_oracle as O
+    from paper_2210_03052_amd import inputs as I
+    cores = len(os.sched_getaffinity(0))
+    try:                                                   # threads the BLAS behind numpy really uses
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [cores])
+    except Exception:
+        pass
+    mask = O.lengths_to_mask(L, wl.S)
+    xh = I.pad_rows(x_packed_h, L, wl.S).astype(np.float64)
+    ow = [O.LayerWeights(**p) for p in params]
+    # a bounded sample: as many layers as fit ~20 s of CPU work, estimated from one warm layer on two sequences
+    O.encoder_layer(xh[:2], mask[:2], ow[0])            # warm the BLAS threads
+    t0 = time.perf_counter()
+    O.encoder_layer(xh, mask, ow[0])
+    one = time.perf_counter() - t0
+    n_base = int(max(1, min(nl, 12, 20.0 // max(one, 1e-3))))
+    t0 = time.perf_counter()
+    O.encoder_stack(xh, mask, ow[:n_base])
+    cpu_s = (time.perf_counter() - t0) * nl / n_base
+    return {"value": round(wl.B / cpu_s, 3), "unit": "sequences/s", "cores": cores, "kind": "oracle",
+            "sample": f"whole batch, {n_base} of {nl} layers timed once (scaled to {nl}), numpy fp64 padded semantics",
+            "seconds": round(cpu_s, 2)}
+
+
+def bench_mha_alone(args, torch, bt, I, wl):
+    """The attention-alone workload: a step is one bt_varlen_mha over the packed fused QKV buffer."""
+    import ctypes as C
+    lib = bt.load_library()
+    L = I.draw_lengths(wl)
+    T, s2 = int(L.sum()), int((L.astype(np.int64) ** 2).sum())
+    qkv_h = I.make_qkv_packed(wl, T)
+    cu_h = np.concatenate([[0], np.cumsum(L)]).astype(np.int32)
+    qkv = torch.from_numpy(qkv_h).to("cuda:0")
+    cu = torch.from_numpy(cu_h).to("cuda:0")
+    o = torch.empty((T, wl.H), dtype=torch.float16, device="cuda:0")
+    st = C.c_void_p(torch.cuda.current_stream().cuda_stream)
+    qb = qkv.data_ptr()
+    fn = lambda: lib.bt_varlen_mha(C.c_void_p(qb), C.c_void_p(qb + 2 * wl.H), C.c_void_p(qb + 4 * wl.H), 3 * wl.H, None,
+                                   None, None, C.c_void_p(cu.data_ptr()), wl.B, T, wl.S, wl.heads, wl.head_dim,
+                                   C.c_float(wl.head_dim ** -0.5), C.c_void_p(o.data_ptr()), None, 0, st)
+    if fn() != 0:
+        raise RuntimeError("bt_varlen_mha failed")
+    for _ in range(args.warmup):
+        fn()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        fn()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    us = time_launches(torch, fn, args.kernel_iters)
+    flop = 4.0 * s2 * wl.H
+    ach = flop / us / 1e6
+    out = {"metric": "sequences/s variable-length fused MHA alone (b16, max256, 12 heads x 64)",
+           "value": round(wl.B * args.steps / dt, 1), "unit": "sequences/s", "n_gpus": 1, "steps": args.steps,
+           "warmup": args.warmup, "ms_per_step": round(dt * 1e3 / args.steps, 5), "higher_is_better": True,
+           "scaling": "weak", "vs_baseline": None, "dtype": "f16", "data": "synthetic",
+           "config": {"workload": args.workload, "batch": wl.B, "max_seq": wl.S, "heads": wl.heads,
+                      "head_dim": wl.head_dim, "length_law": wl.length_law, "valid_tokens": T, "sum_len_sq": s2,
+                      "step": "bt_varlen_mha"},
+           "roofline": {"kernel": "varlen_mha", "bound": "mfma", "achieved": round(ach, 2), "peak": PEAK_MFMA_F16,
+                        "unit": "TFLOP/s", "frac": round(ach / PEAK_MFMA_F16, 4),
+                        "traffic": measured_traffic(args.workload, "varlen_mha"), "us_per_launch": round(us, 2),
+                        "work_per_launch": flop},
+           "kernels": [{"kernel": "varlen_mha", "bound": "mfma", "us": round(us, 2), "launches_per_step": 1,
+                        "achieved": round(ach, 2), "peak": PEAK_MFMA_F16, "unit": "TFLOP/s",
+                        "frac": round(ach / PEAK_MFMA_F16, 4), "work_per_launch": flop}],
+           "algorithmic_bytes": {"varlen_mha": 8 * T * wl.H},
+           "hbm_fraction_of_the_same_launch": round(8.0 * T * wl.H / us / 1e3 / PEAK_HBM, 4)}
+    if args.peaks:
+        out["measured_peaks"] = measure_peaks(torch)
+    if not args.no_cpu_baseline:
+        from oracle import bt_oracle as O
+        cores = len(os.sched_getaffinity(0))
+        try:
+            from threadpoolctl import threadpool_info
+            cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [cores])
+        except Exception:
+            pass
+        t0 = time.perf_counter()
+        O.varlen_mha_packed(qkv_h, cu_h, wl.heads, wl.head_dim)
+        cpu_s = time.perf_counter() - t0
+        out["cpu_baseline"] = {"value": round(wl.B / cpu_s, 3), "unit": "sequences/s", "cores": cores, "kind": "oracle",
+                               "sample": "whole batch, once, numpy fp64 padded attention", "seconds": round(cpu_s, 3)}
+    print(json.dumps(out))
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -235,8 +402,7 @@ def main():
     torch.cuda.set_device(0)
     wl = I.WORKLOADS[args.workload]
     if wl.layers < 1:
-        print("bench.py: pick an encoder workload", file=sys.stderr)
-        sys.exit(2)
+        return bench_mha_alone(args, torch, bt, I, wl)
 
     # ---------------- synthetic batch, resident in HBM before timing starts
     L = I.draw_lengths(wl)
@@ -254,68 +420,54 @@ def main():
     x_packed = torch.empty((wl.B * wl.S, H), dtype=torch.float16, device="cuda:0")
     y_packed = torch.empty((wl.B * wl.S, H), dtype=torch.float16, device="cuda:0")
     y_padded = torch.empty((wl.B, wl.S, H), dtype=torch.float16, device="cuda:0")
+    y_padded_sep = torch.empty_like(y_padded)
 
-    def step():
+    def step_separate(out_=y_padded_sep):
         cu, tok, t = bt.build_offsets(lengths=lengths_d, S=wl.S)
         xp = bt.pack(x_padded, tok, out=x_packed[:t])
         yp = bt.encoder_fwd(layers, xp, cu, wl.S, out=y_packed[:t], ws=ws, fold=fold)
-        bt.unpack(yp, tok, wl.B, wl.S, out=y_padded)
+        bt.unpack(yp, tok, wl.B, wl.S, out=out_)
 
-    for _ in range(args.warmup):
-        step()
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        step()
-    torch.cuda.synchronize()
-    dt = time.perf_counter() - t0
-    ms_per_step = dt * 1e3 / args.steps
-    seq_per_s = wl.B * args.steps / dt
+    def step_fused():
+        cu, tok, t = bt.build_offsets(lengths=lengths_d, S=wl.S)
+        bt.encoder_fwd_padded(layers, x_padded, tok, cu, out=y_padded, ws=ws)
+
+    separate = args.separate_pack_unpack or fold is not None     # the padded entry point takes no fold vectors
+    step = (lambda: step_separate(y_padded)) if separate else step_fused
+    step_name = "build_offsets+pack+encoder_fwd+unpack" if separate else "build_offsets+encoder_fwd_padded"
+    dt, per = timed_steps(torch, step, args.steps, args.warmup)
+    stats = step_stats(wl.B, dt, per)
     flops_step = nl * (24.0 * T * H * H + 4.0 * sum_l2 * H)
 
     out = {
         "metric": "sequences/s BERT-base fp16 varlen (b16, max256)" if args.workload == "bert_base_b16_s256"
                   else f"sequences/s {args.workload} fp16 varlen",
-        "value": round(seq_per_s, 1), "unit": "sequences/s", "n_gpus": 1, "steps": args.steps,
-        "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak",
+        "value": stats["value"], "unit": "sequences/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": stats["ms_per_step"], "ms_per_step_median": stats["ms_per_step_median"],
+        "ms_per_step_min": stats["ms_per_step_min"], "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "f16", "data": "synthetic",
         "config": {"workload": args.workload, "batch": wl.B, "max_seq": wl.S, "hidden": H, "heads": wl.heads,
                    "ffn": F, "layers": nl, "length_law": wl.length_law, "valid_tokens": T, "sum_len_sq": sum_l2,
-                   "step": "build_offsets+pack+encoder_fwd+unpack", "layernorm_folded": fold is not None},
-        "useful_tflops_per_s": round(flops_step / (ms_per_step * 1e-3) / 1e12, 2),
+                   "step": step_name, "layernorm_fold_vectors_given": fold is not None},
+        "useful_tflops_per_s": round(flops_step / (stats["ms_per_step"] * 1e-3) / 1e12, 2),
     }
 
-    # ---------------- the same step with pack / unpack fused into the first / last kernels (extra point)
-    if fold is None:
-        def step_fused():
-            cu, tok, t = bt.build_offsets(lengths=lengths_d, S=wl.S)
-            bt.encoder_fwd_padded(layers, x_padded, tok, cu, out=y_padded2, ws=ws)
+    # ---------------- the same work with pack / unpack as kernels of their own (extra point; same bits)
+    if not separate:
+        dts, pers = timed_steps(torch, step_separate, args.steps, max(args.warmup // 2, 2))
+        out["separate_pack_unpack"] = dict(step_stats(wl.B, dts, pers), unit="sequences/s",
+                                           step="build_offsets+pack+encoder_fwd+unpack",
+                                           outputs_equal=bool(torch.equal(y_padded_sep, y_padded)))
 
-        y_padded2 = torch.empty_like(y_padded)
-        for _ in range(max(args.warmup // 2, 2)):
-            step_fused()
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for _ in range(args.steps):
-            step_fused()
-        torch.cuda.synchronize()
-        dtf = time.perf_counter() - t0
-        out["fused_pack_unpack"] = {"value": round(wl.B * args.steps / dtf, 1), "unit": "sequences/s",
-                                    "ms_per_step": round(dtf * 1e3 / args.steps, 4),
-                                    "step": "build_offsets+encoder_fwd_padded",
-                                    "outputs_equal": bool(torch.equal(y_padded2, y_padded))}
-
-    # ---------------- the same step with pack + encoder + unpack replayed from a HIP graph (extra point)
-    # One graph launch instead of ~90 kernel launches per step: if this is faster than `value`, the host of
+    # ---------------- the same step with the forward replayed from a HIP graph (extra point)
+    # One graph launch instead of ~85 kernel launches per step: if this is faster than `value`, the host of
     # this box did not keep ahead of the GPU in the eager loop; on a quiet host the two agree.
-    if fold is None:
+    if not separate:
         y_padded3 = torch.empty_like(y_padded)
         cu_g, tok_g, t_g = bt.build_offsets(lengths=lengths_d, S=wl.S)
 
         def body():
-            xp = bt.pack(x_padded, tok_g, out=x_packed[:t_g])
-            yp = bt.encoder_fwd(layers, xp, cu_g, wl.S, out=y_packed[:t_g], ws=ws)
-            bt.unpack(yp, tok_g, wl.B, wl.S, out=y_padded3)
+            bt.encoder_fwd_padded(layers, x_padded, tok_g, cu_g, out=y_padded3, ws=ws)
 
         side = torch.cuda.Stream()
         side.wait_stream(torch.cuda.current_stream())
@@ -331,25 +483,17 @@ def main():
             bt.build_offsets(lengths=lengths_d, S=wl.S)      # same offsets every step here; still computed and waited for
             graph.replay()
 
-        for _ in range(max(args.warmup // 2, 2)):
-            step_graph()
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for _ in range(args.steps):
-            step_graph()
-        torch.cuda.synchronize()
-        dtg = time.perf_counter() - t0
-        out["graph_replay"] = {"value": round(wl.B * args.steps / dtg, 1), "unit": "sequences/s",
-                               "ms_per_step": round(dtg * 1e3 / args.steps, 4),
-                               "step": "build_offsets + one HIP graph of pack+encoder_fwd+unpack",
-                               "outputs_equal": bool(torch.equal(y_padded3, y_padded))}
+        dtg, perg = timed_steps(torch, step_graph, args.steps, max(args.warmup // 2, 2))
+        out["graph_replay"] = dict(step_stats(wl.B, dtg, perg), unit="sequences/s",
+                                   step="build_offsets + one HIP graph of encoder_fwd_padded",
+                                   outputs_equal=bool(torch.equal(y_padded3, y_padded)))
 
     # ---------------- throughput with two batches in flight (extra point, not `value`)
     # One batch at a time leaves the GPU idle at every kernel boundary (~2.5 us per dependent launch) and
     # while the host waits for the token count in build_offsets.  A server keeps a second batch in flight
     # on another stream, which fills those holes; each batch has its own buffers and its own host thread,
     # the library keeps no state between calls.  Same steps, same kernels, same results.
-    if not args.no_pipelined:
+    if not args.no_pipelined and not separate:
         import threading
 
         class Batch:
@@ -358,20 +502,17 @@ def main():
                 self.x_padded = x_padded.clone()
                 self.lengths_d = lengths_d.clone()
                 self.ws = torch.empty_like(ws)
-                self.x_packed, self.y_packed, self.y_padded = (torch.empty_like(x_packed), torch.empty_like(y_packed),
-                                                               torch.empty_like(y_padded))
+                self.y_padded = torch.empty_like(y_padded)
 
             def run(self, n):
                 torch.cuda.set_device(0)
                 with torch.cuda.stream(self.stream):
                     for _ in range(n):
                         cu, tok, t = bt.build_offsets(lengths=self.lengths_d, S=wl.S)
-                        xp = bt.pack(self.x_padded, tok, out=self.x_packed[:t])
-                        yp = bt.encoder_fwd(layers, xp, cu, wl.S, out=self.y_packed[:t], ws=self.ws, fold=fold)
-                        bt.unpack(yp, tok, wl.B, wl.S, out=self.y_padded)
+                        bt.encoder_fwd_padded(layers, self.x_padded, tok, cu, out=self.y_padded, ws=self.ws)
 
         batches = [Batch(), Batch()]
-        per = max(args.steps // 2, 1)
+        per_b = max(args.steps // 2, 1)
 
         def both(n):
             th = [threading.Thread(target=b.run, args=(n,)) for b in batches]
@@ -383,11 +524,11 @@ def main():
 
         both(max(args.warmup // 2, 2))
         t0 = time.perf_counter()
-        both(per)
+        both(per_b)
         dt2 = time.perf_counter() - t0
         same = bool(torch.equal(batches[0].y_padded, y_padded) and torch.equal(batches[1].y_padded, y_padded))
-        out["two_batches_in_flight"] = {"value": round(wl.B * 2 * per / dt2, 1), "unit": "sequences/s",
-                                        "steps": 2 * per, "ms_per_step": round(dt2 * 1e3 / (2 * per), 4),
+        out["two_batches_in_flight"] = {"value": round(wl.B * 2 * per_b / dt2, 1), "unit": "sequences/s",
+                                        "steps": 2 * per_b, "ms_per_step": round(dt2 * 1e3 / (2 * per_b), 4),
                                         "streams": 2, "outputs_equal_single_stream": same}
         del batches
 
@@ -427,16 +568,22 @@ def main():
             ("bias_residual_ln1", "hbm", 6.0 * T * H, lnk(proj, P["b_2"], y1, P["ln1_g"], P["ln1_b"], y2)),
             ("pack", "hbm", 4.0 * T * H, bind(lib.bt_pack, ptr(x_padded), ptr(tok), T, H, ptr(x_packed), st)),
             ("unpack", "hbm", 2.0 * T * H + 2.0 * wl.B * wl.S * H,
-             bind(lib.bt_unpack, ptr(y2), ptr(tok), T, wl.B, wl.S, H, ptr(y_padded), st)),
+             bind(lib.bt_unpack, ptr(y2), ptr(tok), T, wl.B, wl.S, H, ptr(y_padded_sep), st)),
         ]
         gemm_shapes = {"gemm0_qkv_bias": (T, 3 * H, H, 0), "gemm1_proj": (T, H, H, 0),
                        "gemm2_bias_gelu": (T, F, H, 1), "gemm3_ffn_down": (T, H, F, 0)}
+        # operands read once + result written once, fp16 (what a launch must move at the least)
+        out["algorithmic_bytes"] = {
+            "gemm0_qkv_bias": 2 * (T * H + 3 * H * H + 3 * T * H + 3 * H), "varlen_mha": 8 * T * H,
+            "gemm1_proj": 2 * (T * H + H * H + T * H), "bias_residual_ln": 6 * T * H + 6 * H,
+            "gemm2_bias_gelu": 2 * (T * H + F * H + T * F + F), "gemm3_ffn_down": 2 * (T * F + H * F + T * H),
+            "pack": 4 * T * H, "unpack": 2 * T * H + 2 * wl.B * wl.S * H}
         kernels = []
         for name, bound, work, fn in steps:
             if fn() != 0:
                 raise RuntimeError(f"{name} failed")
             us = time_launches(torch, fn, args.kernel_iters)
-            per_step = nl if name not in ("pack", "unpack") else 1
+            per_step = nl if name not in ("pack", "unpack") else (1 if separate else 0)
             if bound == "mfma":
                 ach, peak, unit = work / us / 1e6, PEAK_MFMA_F16, "TFLOP/s"
             else:
@@ -456,44 +603,54 @@ def main():
         dom = max(kernels, key=lambda k: k["us"] * k["launches_per_step"])
         out["roofline"] = {"kernel": dom["kernel"], "bound": dom["bound"], "achieved": dom["achieved"],
                            "peak": dom["peak"], "unit": dom["unit"], "frac": dom["frac"],
-                           "traffic": MEASURED_TRAFFIC.get((args.workload, dom["kernel"])),
+                           "traffic": measured_traffic(args.workload, dom["kernel"]),
                            "us_per_launch": dom["us"], "work_per_launch": dom["work_per_launch"]}
         out["kernels"] = kernels
         out["kernel_time_sum_ms_per_step"] = round(sum(k["us"] * k["launches_per_step"] for k in kernels) / 1e3, 4)
 
         # ---- two more measured points named by the metric ----------------------------------------
-        # (a) variable-length MHA alone on the "attention alone" workload (b16, max 256, U[1,256])
-        wm = I.WORKLOADS["mha_b16_s256"]
-        Lm = I.draw_lengths(wm)
-        Tm, s2m = int(Lm.sum()), int((Lm.astype(np.int64) ** 2).sum())
-        qkv_m = dev(I.make_qkv_packed(wm, Tm))
-        cu_m = dev(np.concatenate([[0], np.cumsum(Lm)]).astype(np.int32))
-        out_m = f16(Tm, wm.H)
-        qm = qkv_m.data_ptr()
-        mha_m = bind(lib.bt_varlen_mha, C.c_void_p(qm), C.c_void_p(qm + 2 * wm.H), C.c_void_p(qm + 4 * wm.H), 3 * wm.H,
-                     None, None, None, ptr(cu_m), wm.B, Tm, wm.S, wm.heads, wm.head_dim,
-                     C.c_float(wm.head_dim ** -0.5), ptr(out_m), None, 0, st)
-        us_m = time_launches(torch, mha_m, args.kernel_iters)
-        out["varlen_mha_b16_s256"] = {"us": round(us_m, 2), "valid_tokens": Tm, "sum_len_sq": s2m,
-                                      "tflops": round(4.0 * s2m * wm.H / us_m / 1e6, 2),
-                                      "frac_mfma_peak": round(4.0 * s2m * wm.H / us_m / 1e6 / PEAK_MFMA_F16, 4)}
-        # (b) the HBM-bound kernels at a streaming shape (tensors >> the 256 MB Infinity Cache), same code path
-        Ts = 262144
-        xs, rs, ys = f16(Ts, H), f16(Ts, H), f16(Ts, H)
-        xs.normal_(); rs.normal_()
-        ln_s = bind(lib.bt_add_bias_residual_layernorm, ptr(xs), ptr(P["b_o"]), ptr(rs), ptr(P["ln0_g"]), ptr(P["ln0_b"]),
-                    eps, Ts, H, ptr(ys), st)
-        us_ln = time_launches(torch, ln_s, 20, warm=3)
-        tok_s = torch.arange(Ts, dtype=torch.int32, device="cuda:0")
-        pk_s = bind(lib.bt_pack, ptr(xs), ptr(tok_s), Ts, H, ptr(ys), st)
-        us_pk = time_launches(torch, pk_s, 20, warm=3)
-        out["hbm_streaming"] = {
-            "tokens": Ts, "hidden": H,
-            "bias_residual_ln": {"us": round(us_ln, 1), "GBps": round(6.0 * Ts * H / us_ln / 1e3, 1),
-                                 "frac_hbm_peak": round(6.0 * Ts * H / us_ln / 1e3 / PEAK_HBM, 4)},
-            "pack": {"us": round(us_pk, 1), "GBps": round(4.0 * Ts * H / us_pk / 1e3, 1),
-                     "frac_hbm_peak": round(4.0 * Ts * H / us_pk / 1e3 / PEAK_HBM, 4)}}
-        del xs, rs, ys
+        if args.workload == "bert_base_b16_s256":
+            # (a) variable-length MHA alone on the "attention alone" workload (b16, max 256, U[1,256])
+            wm = I.WORKLOADS["mha_b16_s256"]
+            Lm = I.draw_lengths(wm)
+            Tm, s2m = int(Lm.sum()), int((Lm.astype(np.int64) ** 2).sum())
+            qkv_m = dev(I.make_qkv_packed(wm, Tm))
+            cu_m = dev(np.concatenate([[0], np.cumsum(Lm)]).astype(np.int32))
+            out_m = f16(Tm, wm.H)
+            qm = qkv_m.data_ptr()
+            mha_m = bind(lib.bt_varlen_mha, C.c_void_p(qm), C.c_void_p(qm + 2 * wm.H), C.c_void_p(qm + 4 * wm.H), 3 * wm.H,
+                         None, None, None, ptr(cu_m), wm.B, Tm, wm.S, wm.heads, wm.head_dim,
+                         C.c_float(wm.head_dim ** -0.5), ptr(out_m), None, 0, st)
+            us_m = time_launches(torch, mha_m, args.kernel_iters)
+            out["varlen_mha_b16_s256"] = {"us": round(us_m, 2), "valid_tokens": Tm, "sum_len_sq": s2m,
+                                          "tflops": round(4.0 * s2m * wm.H / us_m / 1e6, 2),
+                                          "frac_mfma_peak": round(4.0 * s2m * wm.H / us_m / 1e6 / PEAK_MFMA_F16, 4)}
+            # (b) the HBM-bound kernels at a streaming shape (tensors >> the 256 MB Infinity Cache), same code path
+            Ts = 262144
+            xs, rs, ys = f16(Ts, H), f16(Ts, H), f16(Ts, H)
+            xs.normal_(); rs.normal_()
+            ln_s = bind(lib.bt_add_bias_residual_layernorm, ptr(xs), ptr(P["b_o"]), ptr(rs), ptr(P["ln0_g"]), ptr(P["ln0_b"]),
+                        eps, Ts, H, ptr(ys), st)
+            us_ln = time_launches(torch, ln_s, 20, warm=3)
+            tok_s = torch.arange(Ts, dtype=torch.int32, device="cuda:0")
+            pk_s = bind(lib.bt_pack, ptr(xs), ptr(tok_s), Ts, H, ptr(ys), st)
+            us_pk = time_launches(torch, pk_s, 20, warm=3)
+            out["hbm_streaming"] = {
+                "tokens": Ts, "hidden": H,
+                "bias_residual_ln": {"us": round(us_ln, 1), "GBps": round(6.0 * Ts * H / us_ln / 1e3, 1),
+                                     "frac_hbm_peak": round(6.0 * Ts * H / us_ln / 1e3 / PEAK_HBM, 4)},
+                "pack": {"us": round(us_pk, 1), "GBps": round(4.0 * Ts * H / us_pk / 1e3, 1),
+                         "frac_hbm_peak": round(4.0 * Ts * H / us_pk / 1e3 / PEAK_HBM, 4)}}
+            del xs, rs, ys
+
+    if args.peaks:
+        mp = measure_peaks(torch)
+        out["measured_peaks"] = mp
+        if "roofline" in out:
+            r = out["roofline"]
+            den = mp["mfma_f16_random_operands_tflops"] if r["bound"] == "mfma" else mp["hbm_read_stream_GBps"]
+            r["frac_of_measured_peak"] = round(r["achieved"] / den, 4)
+            r["measured_peak"] = den
 
     if args.calibrate_copy:
         # a plain device copy of known size (1 GiB read + 1 GiB written) for scaling rocprofv3's
@@ -505,25 +662,7 @@ def main():
 
     # ---------------- CPU baseline: the oracle as it stands, on this machine's cores
     if not args.no_cpu_baseline:
-        from oracle import bt_oracle as O
-        cores = len(os.sched_getaffinity(0))
-        try:                                                   # threads the BLAS behind numpy really uses
-            from threadpoolctl import threadpool_info
-            cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [cores])
-        except Exception:
-            pass
-        mask = O.lengths_to_mask(L, wl.S)
-        xh = I.pad_rows(x_packed_h, L, wl.S).astype(np.float64)
-        ow = [O.LayerWeights(**p) for p in params]
-        n_base = min(nl, 12)
-        O.encoder_layer(xh[:2], mask[:2], ow[0])            # warm the BLAS threads
-        t0 = time.perf_counter()
-        O.encoder_stack(xh, mask, ow[:n_base])
-        cpu_s = (time.perf_counter() - t0) * nl / n_base
-        out["cpu_baseline"] = {"value": round(wl.B / cpu_s, 3), "unit": "sequences/s", "cores": cores,
-                               "kind": "oracle",
-                               "sample": f"whole batch, {n_base} of {nl} layers timed once (scaled to {nl}), "
-                                         f"numpy fp64 padded semantics", "seconds": round(cpu_s, 2)}
+        out["cpu_baseline"] = cpu_baseline_encoder(wl, L, x_packed_h, params, nl)
     print(json.dumps(out))
 
 

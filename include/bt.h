@@ -12,7 +12,9 @@
  *     stated at bt_build_offsets.
  *   - Errors are return codes only.  Argument checks happen on the host before
  *     any launch: a call that returns BT_ERR_INVALID_ARG / BT_ERR_UNSUPPORTED /
- *     BT_ERR_WORKSPACE has enqueued nothing.  A failed launch gives BT_ERR_HIP.
+ *     BT_ERR_WORKSPACE has enqueued nothing -- with one exception, bt_build_offsets
+ *     (and its _stats form), which also reports what only the device can see (a bad
+ *     length or mask entry) after its kernel has run.  A failed launch gives BT_ERR_HIP.
  *   - T == 0 or B == 0 is a valid no-op (BT_OK, no launch).  A sequence of
  *     length 0 is allowed and contributes nothing.
  *   - Weight matrices are [out_features, in_features] row-major (the reduction
@@ -68,12 +70,27 @@ const char* bt_status_string(bt_status s);
  *     stream, as for any other call).  About 20 us less host latency per batch.  Each
  *     thread that calls concurrently needs its own h_total.
  * A length outside [0,S] or a mask entry outside {0,1} is detected on the device and
- * reported as BT_ERR_INVALID_ARG (*h_total = 0, the other outputs are then
- * unspecified).  Requires 1 <= S <= BT_MAX_SEQ, B*S < 2^31.
+ * reported as BT_ERR_INVALID_ARG after the kernel has run (*h_total = 0, the other
+ * outputs are then unspecified).  Requires 1 <= S <= BT_MAX_SEQ, B*S < 2^31.
+ * Because the call waits for a device result it cannot be recorded into a HIP graph:
+ * on a stream that is being captured it returns BT_ERR_UNSUPPORTED and enqueues nothing
+ * (build the offsets before the capture; every other call of this library captures as it is).
  */
 bt_status bt_build_offsets(const int32_t* d_mask, const int32_t* d_lengths, int B, int S,
                            int32_t* d_cu_seqlens, int32_t* d_token_idx, int32_t* h_total,
                            bt_stream stream);
+
+/*
+ * The same call (Sec. III-D), which also hands back the longest sequence of the batch, so that the
+ * caller can pass an exact max_len to the attention and encoder calls:
+ *   h_total_max   host int32 [2]   [0] = T, [1] = max_b L_b (per-sentence valid count)
+ *   d_cu_seqlens  int32 [B+2]      entries 0..B as above; entry B+1 = the same maximum, on the device
+ * Pinned / ordinary host memory, errors and stream capture exactly as for bt_build_offsets
+ * (on an error both host words are 0).
+ */
+bt_status bt_build_offsets_stats(const int32_t* d_mask, const int32_t* d_lengths, int B, int S,
+                                 int32_t* d_cu_seqlens, int32_t* d_token_idx, int32_t* h_total_max,
+                                 bt_stream stream);
 
 /*
  * Pack (remove padding), Sec. III-D: d_packed[i,:] = d_padded[token_idx[i],:]
@@ -107,8 +124,10 @@ bt_status bt_unpack(const bt_half* d_packed, const int32_t* d_token_idx, int T, 
  * ignored because (q+b_q).b_k is constant along a softmax row and cancels exactly, and b_v is added
  * to the output because the probabilities of a row sum to one -- the same function, fewer roundings.
  * d_out: fp16 [T, heads*head_dim], heads concatenated inside a row.
- * max_len: an upper bound on every L_b (sizes the grid; a longer sequence is an
- * error the host cannot see: its extra rows are NOT computed).
+ * T must equal cu_seqlens[B].  max_len: an upper bound on every L_b, 1 <= max_len <= BT_MAX_SEQ
+ * and T <= B*max_len (checked); it only steers the choice among the kernel variants -- the work
+ * list is derived from d_cu_seqlens on the device, so a sequence longer than max_len is still
+ * computed in full (bt_build_offsets_stats returns the exact value).
  * head_dim must be BT_HEAD_DIM.  d_ws/ws_bytes: reserved, may be NULL/0.
  * Logits, softmax statistics and accumulators are fp32; the probabilities enter
  * the second contraction as fp16.
@@ -198,11 +217,15 @@ bt_status bt_encoder_prepare(const bt_layer* layers, int n_layers, float* d_fold
  * holds the ping-pong buffer between layers; d_x is not modified; d_y receives
  * the last layer's output.
  * d_fold == NULL: each layer runs as bt_encoder_layer_fwd does (7 launches per layer).
- * d_fold from bt_encoder_prepare: the LayerNorms are folded into the GEMM epilogues
- * (5 launches per layer plus one normalisation at the end); same function, the
- * results differ from the unfolded path only by fp16 rounding.  Row statistics travel
- * as per-tile partial sums that are added in a fixed order: bit-reproducible, like the
- * unfolded path.
+ * d_fold from bt_encoder_prepare: the library MAY fold the LayerNorms into the GEMM epilogues
+ * (5 launches per layer plus one normalisation at the end) and does so where that is the faster
+ * pipeline: while ceil(T/64) * ceil(H/128) <= 256, i.e. up to about 2 700 tokens at H = 768; for more
+ * tokens it runs the unfolded layers.  Same function either way.  The folded results differ from the
+ * unfolded ones by fp16 rounding (u = gamma (.) z is stored instead of LN(z)) and by how the variance is
+ * formed: from the row sums of z and z^2 in fp32 (E[z^2] - mean^2, clamped at 0), which loses accuracy
+ * when a row's |mean| exceeds its standard deviation by more than about 100x -- post-LN BERT rows have
+ * |mean| << sigma (residual of LayerNorm outputs); for other data leave d_fold NULL.  Row statistics travel as
+ * per-tile partial sums that are added in a fixed order: bit-reproducible, like the unfolded path.
  */
 bt_status bt_encoder_fwd(const bt_layer* layers, int n_layers, const float* d_fold, const bt_half* d_x,
                          const int32_t* d_cu_seqlens, int B, int T, int max_len, bt_half* d_y,

@@ -41,6 +41,8 @@ _SIGNATURES = {
     "bt_status_string": (_c.c_char_p, [_c.c_int]),
     "bt_build_offsets": (_c.c_int, [_c.c_void_p, _c.c_void_p, _c.c_int, _c.c_int, _c.c_void_p, _c.c_void_p,
                                     _c.POINTER(_c.c_int32), _c.c_void_p]),
+    "bt_build_offsets_stats": (_c.c_int, [_c.c_void_p, _c.c_void_p, _c.c_int, _c.c_int, _c.c_void_p, _c.c_void_p,
+                                          _c.POINTER(_c.c_int32), _c.c_void_p]),
     "bt_pack": (_c.c_int, [_c.c_void_p, _c.c_void_p, _c.c_int, _c.c_int, _c.c_void_p, _c.c_void_p]),
     "bt_unpack": (_c.c_int, [_c.c_void_p, _c.c_void_p, _c.c_int, _c.c_int, _c.c_int, _c.c_int, _c.c_void_p,
                              _c.c_void_p]),
@@ -117,17 +119,19 @@ _tls = _threading.local()
 
 
 def _pinned_total():
-    """One pinned int32 per host thread: the device writes the token count there and the host polls it."""
+    """Two pinned int32 per host thread: the device writes the token count (and, for the _stats call, the
+    longest sequence) there and the host polls it."""
     t = getattr(_tls, "total", None)
     if t is None:
-        t = _tls.total = _torch().empty(1, dtype=_torch().int32, pin_memory=True)
+        t = _tls.total = _torch().empty(2, dtype=_torch().int32, pin_memory=True)
     return t
 
 
-def build_offsets(mask=None, lengths=None, S=None, pinned=True):
+def build_offsets(mask=None, lengths=None, S=None, pinned=True, with_max=False):
     """bt_build_offsets.  Returns (cu_seqlens int32[B+1], token_idx int32[T], T).
     pinned=True hands the library a pinned host word for T (no stream synchronisation);
-    pinned=False passes ordinary host memory (copy + one synchronisation)."""
+    pinned=False passes ordinary host memory (copy + one synchronisation).
+    with_max=True calls bt_build_offsets_stats and returns (cu_seqlens, token_idx, T, max_len)."""
     torch = _torch()
     if (mask is None) == (lengths is None):
         raise ValueError("give exactly one of mask / lengths")
@@ -140,19 +144,22 @@ def build_offsets(mask=None, lengths=None, S=None, pinned=True):
         if S is None:
             raise ValueError("S is required with lengths")
         B, dev = lengths.shape[0], lengths.device
-    cu = torch.empty(B + 1, dtype=torch.int32, device=dev)
+    cu = torch.empty(B + 2, dtype=torch.int32, device=dev)
     tok = torch.empty(max(1, B * S), dtype=torch.int32, device=dev)
+    name = "bt_build_offsets_stats" if with_max else "bt_build_offsets"
     if pinned:
         slot = _pinned_total()
-        _call("bt_build_offsets", _ptr(mask), _ptr(lengths), B, int(S), _ptr(cu), _ptr(tok),
+        _call(name, _ptr(mask), _ptr(lengths), B, int(S), _ptr(cu), _ptr(tok),
               _c.cast(slot.data_ptr(), _c.POINTER(_c.c_int32)), _stream())
-        T = int(slot[0])
+        T, mx = int(slot[0]), int(slot[1])
     else:
-        total = _c.c_int32(-1)
-        _call("bt_build_offsets", _ptr(mask), _ptr(lengths), B, int(S), _ptr(cu), _ptr(tok), _c.byref(total),
-              _stream())
-        T = int(total.value)
-    return cu, tok[:T], T
+        res = (_c.c_int32 * 2)(-1, -1)
+        _call(name, _ptr(mask), _ptr(lengths), B, int(S), _ptr(cu), _ptr(tok),
+              _c.cast(res, _c.POINTER(_c.c_int32)), _stream())
+        T, mx = int(res[0]), int(res[1])
+    if with_max:
+        return cu[: B + 1], tok[:T], T, mx
+    return cu[: B + 1], tok[:T], T
 
 
 def pack(padded, token_idx, out=None):

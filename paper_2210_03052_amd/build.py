@@ -1,4 +1,5 @@
-"""Builds libbt.so (the C-ABI HIP library) in-tree with hipcc for gfx950.
+"""Builds libbt.so (the C-ABI HIP library) and libbt_peaks.so (the two measurement kernels behind
+`bench.py --peaks`) in-tree with hipcc for gfx950.
 
     python -m paper_2210_03052_amd.build
 """
@@ -14,6 +15,8 @@ ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.environ.get("BT_LIB_OUT") or os.path.join(PKG, "libbt.so")   # BT_LIB_OUT: build a variant elsewhere
 SOURCES = ["offsets.hip", "gemm.hip", "layernorm.hip", "mha.hip", "layer.hip"]
+PEAKS_LIB = os.path.join(PKG, "libbt_peaks.so")
+PEAKS_SOURCES = ["peaks.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fvisibility=default",
@@ -31,10 +34,9 @@ EXTRA_FLAGS = {"mha.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"]}
 
 
 def _compile(src: str) -> str:
-    obj = os.path.join(PKG, "_build", ("tuning_" if os.environ.get("BT_TUNING") == "1" else "") + src.replace(".hip", ".o"))
+    obj = os.path.join(PKG, "_build", src.replace(".hip", ".o"))
     os.makedirs(os.path.dirname(obj), exist_ok=True)
-    tuning = ["-DBT_TUNING"] if os.environ.get("BT_TUNING") == "1" else []   # sweep hooks + every tile shape
-    cmd = [HIPCC, *FLAGS, *tuning, *EXTRA_FLAGS.get(src, []), "-c", os.path.join(CSRC, src), "-o", obj]
+    cmd = [HIPCC, *FLAGS, *EXTRA_FLAGS.get(src, []), "-c", os.path.join(CSRC, src), "-o", obj]
     r = subprocess.run(cmd, capture_output=True, text=True)
     if r.returncode != 0:
         raise RuntimeError(f"hipcc failed on {src}:\n{r.stdout}\n{r.stderr}")
@@ -43,14 +45,15 @@ def _compile(src: str) -> str:
 
 def build_library(verbose: bool = True) -> str:
     """Compile every HIP source and link libbt.so; always recompiles."""
-    with ThreadPoolExecutor(max_workers=min(8, len(SOURCES))) as ex:
-        objs = list(ex.map(_compile, SOURCES))
-    cmd = [HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs]
-    r = subprocess.run(cmd, capture_output=True, text=True)
-    if r.returncode != 0:
-        raise RuntimeError(f"link failed:\n{r.stdout}\n{r.stderr}")
-    if verbose:
-        print(f"built {LIB}")
+    with ThreadPoolExecutor(max_workers=min(8, len(SOURCES) + len(PEAKS_SOURCES))) as ex:
+        objs = list(ex.map(_compile, SOURCES + PEAKS_SOURCES))
+    for lib, members in ((LIB, objs[:len(SOURCES)]), (PEAKS_LIB, objs[len(SOURCES):])):
+        cmd = [HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", lib, *members]
+        r = subprocess.run(cmd, capture_output=True, text=True)
+        if r.returncode != 0:
+            raise RuntimeError(f"link failed:\n{r.stdout}\n{r.stderr}")
+        if verbose:
+            print(f"built {lib}")
     return LIB
 
 

@@ -360,7 +360,10 @@ __device__ __forceinline__ void load_resid(const half_t* __restrict__ resid, int
 // ---------------------------------------------------------------------------
 // Pipelined kernel: direct-to-LDS slabs, NS stages, WGM x WGN wavefronts.
 // ---------------------------------------------------------------------------
-template <int BM, int BN, int WGM, int WGN, int NS, int ACT, int EPI>
+// SHAPE (0 = fan-out, N >= 2K; 1 = neither; 2 = deep reduction, K >= 2N) changes nothing in the code: it is
+// part of the kernel's name, so that a kernel trace tells the four products of an encoder layer apart
+// (QKV and FFN-up are fan-out, the output projection is square, FFN-down is deep) when they share a tile shape.
+template <int BM, int BN, int WGM, int WGN, int NS, int ACT, int EPI, int SHAPE>
 __global__ __launch_bounds__(WGM* WGN * 64) void gemm_pipe_kernel(
     // Argument order: what the prologue and the K loop need comes first and fits the 14 dwords that are
     // preloaded into SGPRs at wave launch (-amdgpu-kernarg-preload-count), so the first DMA does not
@@ -681,11 +684,6 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_simple_kernel(const half_t*
                                 lane, (wave < 2 ? sA : sB) + (wave & 1) * 32 * 40);
 }
 
-#ifdef BT_TUNING
-int g_gemm_group_m = 0;
-int g_gemm_cfg = -1;
-#endif
-
 // act x epilogue combinations that exist: PLAIN and FOLD with any activation, RESID without one.
 static bt_status launch_simple(const half_t* A, const half_t* W, half_t* C, int M, int N, int K, bt_act act, int epi,
                                GemmEpi ep, hipStream_t st, int* np_out);
@@ -702,12 +700,21 @@ static bt_status launch_pipe(const half_t* A, const half_t* W, half_t* C, int M,
   dim3 grid((unsigned)n_tiles), block(WGM * WGN * 64);
   // strip height: the per-XCD share of tiles (n_tiles/8) should cover a patch with gm*BM ~ gn*BN
   int group_m = (int)(sqrt((double)n_tiles / 8.0 * BN / BM) + 0.5);
-#ifdef BT_TUNING
-  if (g_gemm_group_m > 0) group_m = g_gemm_group_m;
-#endif
   group_m = group_m < 1 ? 1 : (group_m > tiles_m ? tiles_m : group_m);
-#define BT_LAUNCH(ACT, EPI) \
-  gemm_pipe_kernel<BM, BN, WGM, WGN, NS, ACT, EPI><<<grid, block, 0, st>>>(A, W, ep.a_rows, ep.bias, M, N, K, tiles_n, tiles_m, group_m, C, ep)
+#define BT_LAUNCH_S(ACT, EPI, SHAPE) \
+  gemm_pipe_kernel<BM, BN, WGM, WGN, NS, ACT, EPI, SHAPE><<<grid, block, 0, st>>>(A, W, ep.a_rows, ep.bias, M, N, K, tiles_n, tiles_m, group_m, C, ep)
+  // the shape class is spelled out only where two products of a layer can meet in one instantiation
+  // (no activation, plain epilogue); everything else is told apart by ACT / EPI already
+#define BT_LAUNCH(ACT, EPI)                                                     \
+  do {                                                                          \
+    if constexpr ((ACT) == BT_ACT_NONE && (EPI) == EPI_PLAIN) {                 \
+      if (N >= 2 * K) BT_LAUNCH_S(ACT, EPI, 0);                                 \
+      else if (K >= 2 * N) BT_LAUNCH_S(ACT, EPI, 2);                            \
+      else BT_LAUNCH_S(ACT, EPI, 1);                                            \
+    } else {                                                                    \
+      BT_LAUNCH_S(ACT, EPI, 1);                                                 \
+    }                                                                           \
+  } while (0)
   if (epi == EPI_RESID) {
     // only for shapes with one 32x32 block per wavefront (the residual tile lives in registers)
     if constexpr ((BM / WGM) * (BN / WGN) == 32 * 32) BT_LAUNCH(BT_ACT_NONE, EPI_RESID);
@@ -722,6 +729,7 @@ static bt_status launch_pipe(const half_t* A, const half_t* W, half_t* C, int M,
     else BT_LAUNCH(BT_ACT_GELU_TANH, EPI_PLAIN);
   }
 #undef BT_LAUNCH
+#undef BT_LAUNCH_S
   return launch_status();
 }
 
@@ -783,25 +791,6 @@ bt_status gemm_dispatch(const bt_half* A, const bt_half* W, int M, int N, int K,
   if (epi == EPI_RESID && act != BT_ACT_NONE) return BT_ERR_INVALID_ARG;
   if ((K % 64) != 0) return launch_simple(a, w, c, M, N, K, act, epi, ep, st, np_out);
 #define BT_PIPE(BM, BN, WGM, WGN, NS) launch_pipe<BM, BN, WGM, WGN, NS>(a, w, c, M, N, K, act, epi, ep, st, np_out)
-#ifdef BT_TUNING
-  switch (g_gemm_cfg) {  // tile shapes the sweeps compared
-    case 0: return BT_PIPE(128, 128, 2, 2, 4);
-    case 3: return BT_PIPE(128, 64, 2, 2, 4);
-    case 5: return BT_PIPE(64, 64, 2, 2, 4);
-    case 6: return BT_PIPE(256, 128, 2, 2, 3);
-    case 11: return BT_PIPE(256, 128, 4, 2, 3);
-    case 16: return BT_PIPE(128, 64, 4, 2, 4);
-    case 25: return BT_PIPE(192, 128, 2, 4, 3);
-    case 26: return BT_PIPE(128, 256, 2, 4, 3);
-    case 27: return BT_PIPE(128, 128, 2, 4, 4);
-    case 28: return BT_PIPE(64, 128, 2, 4, 4);
-    case 29: return BT_PIPE(128, 128, 2, 4, 2);
-    case 30: return BT_PIPE(128, 128, 2, 2, 2);
-    case 31: return BT_PIPE(128, 64, 4, 2, 3);
-    case 99: return launch_simple(a, w, c, M, N, K, act, epi, ep, st, np_out);
-    default: break;
-  }
-#endif
   const int best = gemm_tile_choice(M, N, K, act, epi);
   switch (best) {
     case 0: return BT_PIPE(256, 128, 4, 2, 3);
@@ -840,18 +829,13 @@ bt_status gemm_splitk_dispatch(const bt_half* A, const bt_half* W, int M, int N,
   ep.ksplit = ksplit;
   int group_m = (int)(sqrt((double)n_tiles / 8.0) + 0.5);
   group_m = group_m < 1 ? 1 : (group_m > tiles_m ? tiles_m : group_m);
-  gemm_pipe_kernel<BM, BN, 2, 2, NS, BT_ACT_NONE, EPI_PARTIAL><<<dim3((unsigned)(n_tiles * ksplit)), dim3(256), 0, st>>>(
+  gemm_pipe_kernel<BM, BN, 2, 2, NS, BT_ACT_NONE, EPI_PARTIAL, 2><<<dim3((unsigned)(n_tiles * ksplit)), dim3(256), 0, st>>>(
       reinterpret_cast<const half_t*>(A), reinterpret_cast<const half_t*>(W), nullptr, nullptr, M, N, K, tiles_n, tiles_m,
       group_m, nullptr, ep);
   return launch_status();
 }
 
 }  // namespace bt
-
-#ifdef BT_TUNING  // sweep hooks, only in builds made with BT_TUNING=1 (never in the shipped library)
-extern "C" void bt_debug_set_gemm_cfg(int cfg) { bt::g_gemm_cfg = cfg; }
-extern "C" void bt_debug_set_gemm_group_m(int g) { bt::g_gemm_group_m = g; }
-#endif
 
 extern "C" bt_status bt_gemm_bias_act(const bt_half* d_A, const bt_half* d_W, const bt_half* d_bias, int M, int N,
                                       int K, bt_act act, bt_half* d_C, bt_stream stream) {

@@ -214,6 +214,15 @@ static bt_status stack_fwd_folded(const bt_layer* layers, int n_layers, const fl
   return ln_finalize_dispatch(in, w.part2, np2, last->ln1_g, last->ln1_b, eps, T, H, y, st);
 }
 
+// Whether the folded pipeline is the faster one for T tokens of width H.  Its residual epilogue exists for
+// the small tile shapes only (64 x 128 for the H-wide products); as long as those tiles fit one round of the
+// 256 compute units the two launches saved per layer win, beyond that the small tiles run in several
+// rounds and the plain 7-launch layer with its larger tiles is faster (measured: -3 % at 2 308 tokens of
+// width 768, +19 % at 9 894).
+static bool folded_pays(int T, int H) {
+  return (long long)((T + 63) / 64) * ((H + 127) / 128) <= 256;
+}
+
 static bt_status check_io(const bt_half* x, const int32_t* cu, int B, int T, int max_len, bt_half* y, void* ws) {
   if (B < 0 || T < 0 || max_len < 0) return BT_ERR_INVALID_ARG;
   if (B == 0 || T == 0) return BT_OK;
@@ -296,7 +305,8 @@ extern "C" bt_status bt_encoder_fwd(const bt_layer* layers, int n_layers, const 
   const Workspace w = carve(d_ws, T, layers[0].H, layers[0].F);
   if (ws_bytes < w.bytes) return BT_ERR_WORKSPACE;
   hipStream_t st = static_cast<hipStream_t>(stream);
-  if (d_fold) return stack_fwd_folded(layers, n_layers, d_fold, d_x, d_cu_seqlens, B, T, max_len, d_y, w, st);
+  if (d_fold && folded_pays(T, layers[0].H))
+    return stack_fwd_folded(layers, n_layers, d_fold, d_x, d_cu_seqlens, B, T, max_len, d_y, w, st);
   const bt_half* in = d_x;
   for (int i = 0; i < n_layers; ++i) {
     bt_half* outp = (i == n_layers - 1) ? d_y : ((i & 1) ? w.pong : w.ping);

@@ -185,15 +185,21 @@ __device__ __forceinline__ void process_tile(const half_t* sk, const half_t* sv,
 // so the workgroups that walk the most key tiles start first and short ones fill the tail -- the
 // work list is never materialised, every wave derives its entry from cu_seqlens with ballots.
 // More than 64 sequences: plain sequence order, prefix sum of per-sequence tile counts, 64 at a time.
-__device__ __forceinline__ bool locate_tile(const int32_t* __restrict__ cu, int B, int BQ, int max_tiles, int qtile,
-                                            int lane, int& tok0, int& L, int& qt) {
+// Tile counts come from cu_seqlens alone (never from the caller's max_len), so every row of every
+// sequence has an owner as long as the grid holds sum ceil(L_b / BQ) <= T / BQ + B workgroups per head.
+__device__ __forceinline__ bool locate_tile(const int32_t* __restrict__ cu, int B, int BQ, int qtile, int lane,
+                                            int& tok0, int& L, int& qt) {
   if (B <= kWave) {
     const int start = lane < B ? cu[lane] : 0;
     const int len = lane < B ? cu[lane + 1] - start : 0;
-    const int nt = min((len + BQ - 1) / BQ, max_tiles);
+    const int nt = (len + BQ - 1) / BQ;
+    int vmax = nt;  // largest tile count present: where the walk over the groups starts
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) vmax = max(vmax, __shfl_xor(vmax, o, kWave));
+    vmax = __builtin_amdgcn_readfirstlane(vmax);
     const unsigned long long below = (1ull << lane) - 1ull;
     int running = 0;
-    for (int v = max_tiles; v >= 1; --v) {
+    for (int v = vmax; v >= 1; --v) {
       const unsigned long long grp = __ballot(nt == v);  // sequences with exactly v q-tiles
       const int c = __popcll(grp);
       if (qtile < running + c * v) {
@@ -215,7 +221,7 @@ __device__ __forceinline__ bool locate_tile(const int32_t* __restrict__ cu, int 
     const int b = b0 + lane;
     const int start = b < B ? cu[b] : 0;
     const int len = b < B ? cu[b + 1] - start : 0;
-    const int nt = min((len + BQ - 1) / BQ, max_tiles);
+    const int nt = (len + BQ - 1) / BQ;
     int incl = nt;
 #pragma unroll
     for (int o = 1; o < kWave; o <<= 1) {
@@ -239,7 +245,7 @@ __device__ __forceinline__ bool locate_tile(const int32_t* __restrict__ cu, int 
 template <int NW, int NS>
 __global__ __launch_bounds__(NW * 64) void varlen_mha_kernel(
     // in the order of first use: the first 14 dwords are preloaded into SGPRs at wave launch
-    const int32_t* __restrict__ cu, int B, int heads, int max_tiles, float scale_log2e, const half_t* __restrict__ Q,
+    const int32_t* __restrict__ cu, int B, int heads, float scale_log2e, const half_t* __restrict__ Q,
     const half_t* __restrict__ K, const half_t* __restrict__ V, int64_t row_stride, half_t* __restrict__ out,
     const half_t* __restrict__ bq, const half_t* __restrict__ bv) {
   constexpr int BQ = NW * 32;
@@ -258,7 +264,7 @@ __global__ __launch_bounds__(NW * 64) void varlen_mha_kernel(
   const int qtile = blockIdx.x / heads;
 
   int tok0 = 0, L = 0, qt = -1;
-  if (!locate_tile(cu, B, BQ, max_tiles, qtile, lane, tok0, L, qt)) return;  // same decision in every wave
+  if (!locate_tile(cu, B, BQ, qtile, lane, tok0, L, qt)) return;  // same decision in every wave
 
   const int q0 = qt * BQ;
   const int hofs = head * kD;
@@ -390,7 +396,7 @@ __global__ __launch_bounds__(NW * 64) void varlen_mha_kernel(
 template <int NK, int NS>
 __global__ __launch_bounds__(NK * 64) void varlen_mha_splitkey_kernel(
     // in the order of first use: the first 14 dwords are preloaded into SGPRs at wave launch
-    const int32_t* __restrict__ cu, int B, int heads, int max_tiles, float scale_log2e, const half_t* __restrict__ Q,
+    const int32_t* __restrict__ cu, int B, int heads, float scale_log2e, const half_t* __restrict__ Q,
     const half_t* __restrict__ K, const half_t* __restrict__ V, int64_t row_stride, half_t* __restrict__ out,
     const half_t* __restrict__ bq, const half_t* __restrict__ bv) {
   constexpr int BQ = 32;
@@ -408,7 +414,7 @@ __global__ __launch_bounds__(NK * 64) void varlen_mha_splitkey_kernel(
   const int qtile = blockIdx.x / heads;
 
   int tok0 = 0, L = 0, qt = -1;
-  if (!locate_tile(cu, B, BQ, max_tiles, qtile, lane, tok0, L, qt)) return;  // same decision in every wave
+  if (!locate_tile(cu, B, BQ, qtile, lane, tok0, L, qt)) return;  // same decision in every wave
 
   const int q0 = qt * BQ;
   const int hofs = head * kD;
@@ -548,13 +554,12 @@ static bt_status launch_mha_splitkey(const half_t* q, const half_t* k, const hal
                                      const half_t* bq, const half_t* bv, const int32_t* cu, int B, int T, int max_len,
                                      int heads, float scale, half_t* out, hipStream_t st) {
   constexpr int BQ = 32;
-  const long long by_len = (long long)B * ((max_len + BQ - 1) / BQ);
-  const long long by_tok = (long long)T / BQ + B;
-  const long long tiles = by_len < by_tok ? by_len : by_tok;
-  const long long blocks = tiles * heads;
+  // q-tiles: sum ceil(L_b/BQ) <= floor(T/BQ) + B, a bound that holds whatever the lengths are (the caller's
+  // max_len is only a hint for the choice of kernel: a sequence longer than it is still computed in full)
+  const long long blocks = ((long long)T / BQ + B) * heads;
   if (blocks > 0x7fffffffLL) return BT_ERR_UNSUPPORTED;
   varlen_mha_splitkey_kernel<NK, NS><<<(unsigned)blocks, NK * 64, 0, st>>>(
-      cu, B, heads, (max_len + BQ - 1) / BQ, scale * 1.4426950408889634f, q, k, v, row_stride, out, bq, bv);
+      cu, B, heads, scale * 1.4426950408889634f, q, k, v, row_stride, out, bq, bv);
   return launch_status();
 }
 
@@ -563,20 +568,12 @@ static bt_status launch_mha(const half_t* q, const half_t* k, const half_t* v, i
                             const half_t* bv, const int32_t* cu, int B, int T, int max_len, int heads, float scale,
                             half_t* out, hipStream_t st) {
   constexpr int BQ = NW * 32;
-  // number of q-tiles: sum ceil(L_b/BQ) <= min(B*ceil(max_len/BQ), floor(T/BQ) + B)
-  const long long by_len = (long long)B * ((max_len + BQ - 1) / BQ);
-  const long long by_tok = (long long)T / BQ + B;
-  const long long tiles = by_len < by_tok ? by_len : by_tok;
-  const long long blocks = tiles * heads;
+  const long long blocks = ((long long)T / BQ + B) * heads;  // see launch_mha_splitkey
   if (blocks > 0x7fffffffLL) return BT_ERR_UNSUPPORTED;
   varlen_mha_kernel<NW, NS><<<(unsigned)blocks, NW * 64, 0, st>>>(
-      cu, B, heads, (max_len + BQ - 1) / BQ, scale * 1.4426950408889634f, q, k, v, row_stride, out, bq, bv);
+      cu, B, heads, scale * 1.4426950408889634f, q, k, v, row_stride, out, bq, bv);
   return launch_status();
 }
-
-#ifdef BT_TUNING
-int g_mha_cfg = -1;
-#endif
 
 bt_status mha_dispatch(const bt_half* q, const bt_half* k, const bt_half* v, int64_t row_stride, const bt_half* bq,
                        const bt_half* bk, const bt_half* bv, const int32_t* cu, int B, int T, int max_len, int heads,
@@ -585,21 +582,6 @@ bt_status mha_dispatch(const bt_half* q, const bt_half* k, const bt_half* v, int
   auto h = [](const bt_half* p) { return reinterpret_cast<const half_t*>(p); };
   half_t* o = reinterpret_cast<half_t*>(out);
 #define BT_MHA_ARGS h(q), h(k), h(v), row_stride, h(bq), h(bv), cu, B, T, max_len, heads, scale, o, st
-#ifdef BT_TUNING
-  switch (g_mha_cfg) {
-    case 4: return launch_mha<4, 3>(BT_MHA_ARGS);
-    case 2: return launch_mha<2, 3>(BT_MHA_ARGS);
-    case 1: return launch_mha<1, 3>(BT_MHA_ARGS);
-    case 42: return launch_mha<4, 2>(BT_MHA_ARGS);
-    case 22: return launch_mha<2, 2>(BT_MHA_ARGS);
-    case 12: return launch_mha<1, 2>(BT_MHA_ARGS);
-    case 141: return launch_mha_splitkey<4, 1>(BT_MHA_ARGS);
-    case 142: return launch_mha_splitkey<4, 2>(BT_MHA_ARGS);
-    case 121: return launch_mha_splitkey<2, 1>(BT_MHA_ARGS);
-    case 122: return launch_mha_splitkey<2, 2>(BT_MHA_ARGS);
-    default: break;
-  }
-#endif
   // Kernel choice.  Tall query tiles (4 waves x 32 rows) re-read K/V least and suit long sequences;
   // 2-wave tiles give more workgroups; with too few of those to occupy the SIMDs, the split-key
   // kernel puts two waves on every 32 query rows.  Two K/V stages (32 KB of LDS per workgroup) rather
@@ -614,10 +596,6 @@ bt_status mha_dispatch(const bt_half* q, const bt_half* k, const bt_half* v, int
 
 }  // namespace bt
 
-#ifdef BT_TUNING  // sweep hook, only in builds made with BT_TUNING=1
-extern "C" void bt_debug_set_mha_cfg(int cfg) { bt::g_mha_cfg = cfg; }
-#endif
-
 extern "C" bt_status bt_varlen_mha(const bt_half* d_q, const bt_half* d_k, const bt_half* d_v, int64_t row_stride,
                                    const bt_half* d_bq, const bt_half* d_bk, const bt_half* d_bv,
                                    const int32_t* d_cu_seqlens, int B, int T, int max_len, int heads, int head_dim,
@@ -630,6 +608,7 @@ extern "C" bt_status bt_varlen_mha(const bt_half* d_q, const bt_half* d_k, const
   if (!(scale > 0.f) || !(scale < INFINITY)) return BT_ERR_INVALID_ARG;
   if (B == 0 || T == 0) return BT_OK;
   if (max_len < 1 || (int64_t)T > (int64_t)B * max_len) return BT_ERR_INVALID_ARG;
+  if (max_len > BT_MAX_SEQ) return BT_ERR_UNSUPPORTED;
   if (!d_q || !d_k || !d_v || !d_cu_seqlens || !d_out) return BT_ERR_INVALID_ARG;
   if (!bt::aligned16(d_q) || !bt::aligned16(d_k) || !bt::aligned16(d_v) || !bt::aligned16(d_out))
     return BT_ERR_INVALID_ARG;

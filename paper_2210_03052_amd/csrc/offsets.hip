@@ -17,14 +17,16 @@ constexpr int kOffsetsThreads = 1024;  // 16 wavefronts, one per sentence at a t
 // A length outside [0,S] or a mask entry outside {0,1} sets cu[B] = -1.
 // host_total (optional): device-visible host memory that receives the total (or -1) as soon as it
 // is known, before the position array is written, so that the host can go on without a stream sync.
+// max_out (optional): device word that receives the largest per-sentence valid count; with host_total
+// it is also stored to host_total[1], before the total, so that a host that sees the total sees it too.
 __global__ __launch_bounds__(kOffsetsThreads) void offsets_kernel(const int32_t* __restrict__ mask,
                                                                  const int32_t* __restrict__ lengths, int B, int S,
                                                                  int32_t* __restrict__ cu,
                                                                  int32_t* __restrict__ token_idx,
-                                                                 int32_t* host_total) {
-  __shared__ int s_bad;
+                                                                 int32_t* host_total, int32_t* max_out) {
+  __shared__ int s_bad, s_max;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nwave = kOffsetsThreads / kWave;
-  if (threadIdx.x == 0) s_bad = 0;
+  if (threadIdx.x == 0) { s_bad = 0; s_max = 0; }
   __syncthreads();
 
   for (int b = wave; b < B; b += nwave) {
@@ -45,6 +47,7 @@ __global__ __launch_bounds__(kOffsetsThreads) void offsets_kernel(const int32_t*
     if (lane == 0) {
       cu[b + 1] = count;
       if (bad) s_bad = 1;
+      atomicMax(&s_max, count);
     }
   }
   __syncthreads();
@@ -65,8 +68,13 @@ __global__ __launch_bounds__(kOffsetsThreads) void offsets_kernel(const int32_t*
     if (lane == 0) cu[0] = 0;
   }
   __syncthreads();
-  if (threadIdx.x == 0 && host_total)
-    __hip_atomic_store(host_total, s_bad ? -1 : cu[B], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+  if (threadIdx.x == 0) {
+    if (max_out) *max_out = s_max;
+    if (host_total) {
+      if (max_out) __hip_atomic_store(host_total + 1, s_max, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+      __hip_atomic_store(host_total, s_bad ? -1 : cu[B], __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
+    }
+  }
 
   for (int b = wave; b < B; b += nwave) {
     const int base = cu[b];
@@ -120,47 +128,72 @@ __global__ __launch_bounds__(256) void unpack_kernel(const uint4_t* __restrict__
 
 using namespace bt;
 
-extern "C" bt_status bt_build_offsets(const int32_t* d_mask, const int32_t* d_lengths, int B, int S,
-                                      int32_t* d_cu_seqlens, int32_t* d_token_idx, int32_t* h_total,
-                                      bt_stream stream) {
+// Shared body of bt_build_offsets / bt_build_offsets_stats.  h_out[0] receives the total; with `stats`
+// h_out[1] receives the largest per-sentence count and d_cu_seqlens has B+2 entries (the last one is
+// the device copy of that maximum).
+static bt_status build_offsets_impl(const int32_t* d_mask, const int32_t* d_lengths, int B, int S,
+                                    int32_t* d_cu_seqlens, int32_t* d_token_idx, int32_t* h_out, bool stats,
+                                    bt_stream stream) {
   if ((d_mask == nullptr) == (d_lengths == nullptr)) return BT_ERR_INVALID_ARG;
-  if (!d_cu_seqlens || !d_token_idx || !h_total || B < 0 || S < 1) return BT_ERR_INVALID_ARG;
+  if (!d_cu_seqlens || !d_token_idx || !h_out || B < 0 || S < 1) return BT_ERR_INVALID_ARG;
   if (S > BT_MAX_SEQ || (int64_t)B * S >= (int64_t)INT32_MAX) return BT_ERR_UNSUPPORTED;
   hipStream_t st = static_cast<hipStream_t>(stream);
-  if (B == 0) {
-    *h_total = 0;
-    if (hipMemsetAsync(d_cu_seqlens, 0, sizeof(int32_t), st) != hipSuccess) return BT_ERR_HIP;
-    return hipStreamSynchronize(st) == hipSuccess ? BT_OK : BT_ERR_HIP;
+  // The call waits for a result on the host: it cannot be recorded into a HIP graph.
+  hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
+  if (hipStreamIsCapturing(st, &cap) != hipSuccess) {
+    (void)hipGetLastError();
+    return BT_ERR_HIP;
   }
-  // Fast path: h_total lies in pinned host memory that the device can write (hipHostMalloc).  The
+  if (cap != hipStreamCaptureStatusNone) return BT_ERR_UNSUPPORTED;
+  // Fast path: h_out lies in pinned host memory that the device can write (hipHostMalloc).  The
   // kernel stores the total there the moment it is known and the host polls for it: no copy, no
   // stream synchronisation, and later launches on the stream are ordered after the kernel anyway.
   hipPointerAttribute_t attr;
   int32_t* h_dev = nullptr;
-  if (hipPointerGetAttributes(&attr, h_total) == hipSuccess && attr.type == hipMemoryTypeHost && attr.devicePointer)
+  if (hipPointerGetAttributes(&attr, h_out) == hipSuccess && attr.type == hipMemoryTypeHost && attr.devicePointer)
     h_dev = static_cast<int32_t*>(attr.devicePointer);
   else
     (void)hipGetLastError();  // ordinary host memory: not an error
   constexpr int32_t kPending = INT32_MIN;
-  volatile int32_t* slot = h_total;
+  volatile int32_t* slot = h_out;
   if (h_dev) *slot = kPending;
-  offsets_kernel<<<1, kOffsetsThreads, 0, st>>>(d_mask, d_lengths, B, S, d_cu_seqlens, d_token_idx, h_dev);
+  // B == 0 runs the same kernel: it writes cu[0] = 0 and a total of 0 (no memset, no special case)
+  offsets_kernel<<<1, kOffsetsThreads, 0, st>>>(d_mask, d_lengths, B, S, d_cu_seqlens, d_token_idx, h_dev,
+                                                stats ? d_cu_seqlens + B + 1 : nullptr);
   if (hipGetLastError() != hipSuccess) return BT_ERR_HIP;
-  int32_t total = kPending;
+  int32_t res[2] = {kPending, 0};
   if (h_dev) {
     const auto t0 = std::chrono::steady_clock::now();
-    for (long spin = 0; (total = *slot) == kPending; ++spin) {
+    for (long spin = 0; (res[0] = slot[0]) == kPending; ++spin) {
       if ((spin & 1023) == 1023 && std::chrono::steady_clock::now() - t0 > std::chrono::milliseconds(200)) break;
       __builtin_ia32_pause();
     }
+    if (res[0] != kPending && stats) {
+      __atomic_thread_fence(__ATOMIC_ACQUIRE);  // the maximum was stored before the total
+      res[1] = slot[1];
+    }
   }
-  if (total == kPending) {  // pageable h_total, or the store has not shown up: copy and synchronise
-    if (hipMemcpyAsync(&total, d_cu_seqlens + B, sizeof(int32_t), hipMemcpyDeviceToHost, st) != hipSuccess)
+  if (res[0] == kPending) {  // pageable h_out, or the store has not shown up: copy and synchronise
+    if (hipMemcpyAsync(res, d_cu_seqlens + B, (stats ? 2 : 1) * sizeof(int32_t), hipMemcpyDeviceToHost, st) !=
+        hipSuccess)
       return BT_ERR_HIP;
     if (hipStreamSynchronize(st) != hipSuccess) return BT_ERR_HIP;
   }
-  *h_total = total < 0 ? 0 : total;
-  return total < 0 ? BT_ERR_INVALID_ARG : BT_OK;
+  h_out[0] = res[0] < 0 ? 0 : res[0];
+  if (stats) h_out[1] = res[0] < 0 ? 0 : res[1];
+  return res[0] < 0 ? BT_ERR_INVALID_ARG : BT_OK;
+}
+
+extern "C" bt_status bt_build_offsets(const int32_t* d_mask, const int32_t* d_lengths, int B, int S,
+                                      int32_t* d_cu_seqlens, int32_t* d_token_idx, int32_t* h_total,
+                                      bt_stream stream) {
+  return build_offsets_impl(d_mask, d_lengths, B, S, d_cu_seqlens, d_token_idx, h_total, false, stream);
+}
+
+extern "C" bt_status bt_build_offsets_stats(const int32_t* d_mask, const int32_t* d_lengths, int B, int S,
+                                            int32_t* d_cu_seqlens, int32_t* d_token_idx, int32_t* h_total_max,
+                                            bt_stream stream) {
+  return build_offsets_impl(d_mask, d_lengths, B, S, d_cu_seqlens, d_token_idx, h_total_max, true, stream);
 }
 
 extern "C" bt_status bt_pack(const bt_half* d_padded, const int32_t* d_token_idx, int T, int H,

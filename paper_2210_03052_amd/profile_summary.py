@@ -1,0 +1,275 @@
+"""Turns rocprofv3 CSV output of `bench.py` runs into the short summaries kept under profiles/.
+
+    python -m paper_2210_03052_amd.profile_summary --workload NAME [--stats DIR] [--pmc DIR ...]
+           [--fetch DIR --write DIR] [--bench-json FILE] --out profiles/NAME.md [--traffic profiles/hbm_traffic.txt]
+
+  --stats   directory of a `rocprofv3 --kernel-trace --stats` run        -> per-kernel call count, avg/min/max us
+  --pmc     directories of `rocprofv3 --pmc <SQ counters>` runs          -> per-kernel counter averages and the
+            MFMA figures derived from them (see `derive`)
+  --fetch / --write  directories of the FETCH_SIZE and WRITE_SIZE runs (bench.py --calibrate-copy), scaled by what
+            the same counter reads for the 1 GiB device copy of that run  -> HBM-side bytes per launch
+  --traffic the machine-readable table bench.py reads its `roofline.traffic` from; the lines of this workload
+            are replaced, other workloads' lines are kept.
+
+Every kernel of the library is mapped to the step of the layer it implements by its name alone: the GEMM
+kernel's template arguments spell out activation, epilogue and shape class, so the four products of a layer
+are distinct kernels in a trace.  Reads CSV, writes text; nothing here touches a GPU.
+"""
+from __future__ import annotations
+
+import argparse
+import collections
+import csv
+import glob
+import json
+import os
+import re
+
+COPY_KIB = 1048576.0     # bench.py --calibrate-copy: one 1 GiB device copy (1 GiB read + 1 GiB written)
+
+
+def template_args(name: str):
+    """Integer template arguments of a kernel name, mangled (`ILi64ELi128ELb0EE`) or demangled (`<64, 128, false>`)."""
+    m = re.search(r"I((?:L[ib]\d+E)+)E", name)
+    if m:
+        return [int(x) for x in re.findall(r"L[ib](\d+)E", m.group(1))]
+    m = re.search(r"<([^<>]*)>", name)
+    if m:
+        out = []
+        for tok in m.group(1).split(","):
+            tok = tok.strip().split("=")[-1].strip()
+            out.append({"true": 1, "false": 0}.get(tok, None) if tok in ("true", "false") else int(re.sub(r"[^0-9-]", "", tok) or 0))
+        return out
+    return []
+
+
+def role_of(name: str):
+    """(step of the layer, short label) for a kernel name of this library, else (None, None)."""
+    a = template_args(name)
+    if "gemm_pipe_kernel" in name and len(a) >= 8:
+        bm, bn, wgm, wgn, ns, act, epi, shape = a[:8]
+        label = f"gemm_pipe<{bm}x{bn},{wgm}x{wgn} waves,{ns} stages,act={act},epi={epi},shape={shape}>"
+        if epi == 3:
+            return ("gemm3_ffn_down" if shape == 2 else "gemm1_proj"), label
+        if act != 0:
+            return "gemm2_bias_gelu", label
+        if epi == 2:
+            return ("gemm3_ffn_down" if shape == 2 else "gemm1_proj"), label
+        return {0: "gemm0_qkv_bias", 1: "gemm1_proj", 2: "gemm3_ffn_down"}.get(shape, "gemm"), label
+    if "gemm_simple_kernel" in name:
+        return "gemm_fallback", "gemm_simple"
+    if "varlen_mha_splitkey_kernel" in name:
+        return "varlen_mha", f"varlen_mha_splitkey<{','.join(map(str, a[:2]))}>"
+    if "varlen_mha_kernel" in name:
+        return "varlen_mha", f"varlen_mha<{','.join(map(str, a[:2]))}>"
+    if "bias_residual_ln_kernel" in name:
+        stream = len(a) >= 3 and a[2] == 1
+        return ("bias_residual_ln_streaming" if stream else "bias_residual_ln"), f"bias_residual_ln<{','.join(map(str, a[:3]))}>"
+    for key, role in (("ln_finalize_kernel", "ln_finalize"), ("unpack_kernel", "unpack"), ("pack_kernel", "pack"),
+                      ("offsets_kernel", "offsets"), ("fold_vectors_kernel", "fold_vectors"),
+                      ("peak_mfma_kernel", "peak_mfma"), ("peak_read_kernel", "peak_read"),
+                      ("copyBuffer", "device_copy")):
+        if key in name:
+            return role, key
+    return None, None
+
+
+def _csv(dirname, suffix):
+    files = glob.glob(os.path.join(dirname, "**", f"*{suffix}"), recursive=True)
+    if not files:
+        raise SystemExit(f"no *{suffix} under {dirname}")
+    rows = []
+    for f in files:
+        rows.extend(csv.DictReader(open(f, newline="")))
+    return rows
+
+
+def read_trace(dirname):
+    """{label: [durations in us]} and {label: role} from a kernel trace."""
+    dur, roles = collections.defaultdict(list), {}
+    for r in _csv(dirname, "kernel_trace.csv"):
+        role, label = role_of(r["Kernel_Name"])
+        if role is None:
+            continue
+        dur[label].append((int(r["End_Timestamp"]) - int(r["Start_Timestamp"])) / 1e3)
+        roles[label] = role
+    return dur, roles
+
+
+def read_counters(dirname):
+    """{label: {counter: average over the dispatches of that kernel}}, {label: role}, {label: dispatches}."""
+    acc, roles, n = collections.defaultdict(lambda: collections.defaultdict(list)), {}, collections.Counter()
+    for r in _csv(dirname, "counter_collection.csv"):
+        role, label = role_of(r["Kernel_Name"])
+        if role is None:
+            continue
+        acc[label][r["Counter_Name"]].append(float(r["Counter_Value"]))
+        roles[label] = role
+    out = {}
+    for label, cs in acc.items():
+        out[label] = {c: sum(v) / len(v) for c, v in cs.items()}
+        n[label] = max(len(v) for v in cs.values())
+    return out, roles, n
+
+
+def derive(c):
+    """MFMA figures from raw SQ counters of one kernel (averages per dispatch).
+    SQ_INSTS_VALU_MFMA_MOPS_F16 counts units of 512 FLOP; SQ_VALU_MFMA_BUSY_CYCLES adds up, over the chip's
+    1024 SIMDs, the cycles their matrix pipe is busy (32 per 32x32x16 fp16 instruction); SQ_BUSY_CU_CYCLES adds
+    up the cycles each compute unit has a wave resident."""
+    d = {}
+    if "SQ_INSTS_VALU_MFMA_MOPS_F16" in c:
+        d["executed_gflop"] = c["SQ_INSTS_VALU_MFMA_MOPS_F16"] * 512 / 1e9
+    if "SQ_VALU_MFMA_BUSY_CYCLES" in c and c.get("SQ_BUSY_CU_CYCLES"):
+        d["mfma_busy_share_of_busy_simd_cycles"] = c["SQ_VALU_MFMA_BUSY_CYCLES"] / (4.0 * c["SQ_BUSY_CU_CYCLES"])
+    if "SQ_VALU_MFMA_BUSY_CYCLES" in c:
+        d["mfma_pipe_us_at_2.4GHz_all_simds"] = c["SQ_VALU_MFMA_BUSY_CYCLES"] / 1024.0 / 2400.0
+    if "SQ_BUSY_CU_CYCLES" in c:
+        d["cu_busy_us_at_2.4GHz_all_cus"] = c["SQ_BUSY_CU_CYCLES"] / 256.0 / 2400.0
+    if c.get("SQ_WAVE_CYCLES") and "SQ_WAIT_INST_ANY" in c:
+        d["wave_cycles_waiting_on_an_instruction"] = c["SQ_WAIT_INST_ANY"] / c["SQ_WAVE_CYCLES"]
+    if c.get("SQ_INSTS_MFMA") and "SQ_INSTS_VALU" in c:
+        d["valu_instructions_per_mfma"] = (c["SQ_INSTS_VALU"] - c["SQ_INSTS_MFMA"]) / c["SQ_INSTS_MFMA"]
+    return d
+
+
+def traffic_from(fetch_dir, write_dir):
+    """{role: (fetch KiB, write KiB, HBM bytes)} per launch, scaled by the 1 GiB copy of the same runs."""
+    out = {}
+    scale = {}
+    per = {}
+    for kind, d in (("FETCH_SIZE", fetch_dir), ("WRITE_SIZE", write_dir)):
+        cs, roles, _ = read_counters(d)
+        copy = [v[kind] for lab, v in cs.items() if roles[lab] == "device_copy" and kind in v]
+        # the calibration copy is by far the largest copyBuffer dispatch; averages would be polluted by small ones
+        big = 0.0
+        for r in _csv(d, "counter_collection.csv"):
+            if "copyBuffer" in r["Kernel_Name"] and r["Counter_Name"] == kind:
+                big = max(big, float(r["Counter_Value"]))
+        scale[kind] = COPY_KIB / big if big > 1000 else 1.0
+        for lab, v in cs.items():
+            if kind in v:
+                per.setdefault(roles[lab], {})[kind] = v[kind]
+    for role, v in per.items():
+        if "FETCH_SIZE" in v and "WRITE_SIZE" in v:
+            hbm = (v["FETCH_SIZE"] * scale["FETCH_SIZE"] + v["WRITE_SIZE"] * scale["WRITE_SIZE"]) * 1024.0
+            out[role] = (v["FETCH_SIZE"], v["WRITE_SIZE"], hbm)
+    return out, scale
+
+
+def update_traffic_file(path, workload, table):
+    head = ["# HBM-side bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of bench.py, each scaled by the",
+            "# same counter's reading of a 1 GiB device copy in the same run.  Written by",
+            "# `python -m paper_2210_03052_amd.profile_summary`; read by bench.py (roofline.traffic).",
+            "# workload kernel fetch_kib write_kib hbm_bytes"]
+    keep = []
+    if os.path.exists(path):
+        for line in open(path):
+            line = line.rstrip("\n")
+            if line and not line.startswith("#") and line.split()[0] != workload:
+                keep.append(line)
+    new = [f"{workload} {role} {f:.1f} {w:.1f} {int(round(h))}" for role, (f, w, h) in sorted(table.items())
+           if role not in ("device_copy",)]
+    with open(path, "w") as fh:
+        fh.write("\n".join(head + sorted(keep + new)) + "\n")
+
+
+def main():
+    ap = argparse.ArgumentParser(description=__doc__, formatter_class=argparse.RawDescriptionHelpFormatter)
+    ap.add_argument("--workload", required=True)
+    ap.add_argument("--stats")
+    ap.add_argument("--pmc", nargs="*", default=[])
+    ap.add_argument("--fetch")
+    ap.add_argument("--write")
+    ap.add_argument("--bench-json", help="the JSON line bench.py printed in the --stats run (useful FLOPs per kernel)")
+    ap.add_argument("--commands", help="text file with the commands that produced the inputs (copied into the summary)")
+    ap.add_argument("--out", required=True)
+    ap.add_argument("--traffic")
+    args = ap.parse_args()
+
+    bench = {}
+    if args.bench_json and os.path.exists(args.bench_json):
+        for line in open(args.bench_json):
+            line = line.strip()
+            if line.startswith("{"):
+                bench = json.loads(line)
+    work = {k["kernel"]: k for k in bench.get("kernels", [])}
+    if "bias_residual_ln0" in work:
+        work["bias_residual_ln"] = work["bias_residual_ln0"]
+
+    md = [f"# rocprofv3 summary: bench.py, workload `{args.workload}`", ""]
+    if bench.get("config"):
+        c = bench["config"]
+        md += [f"Batch {c.get('batch')} x max {c.get('max_seq')}, hidden {c.get('hidden')}, {c.get('layers')} layers, "
+               f"{c.get('valid_tokens')} valid tokens, sum of squared lengths {c.get('sum_len_sq')}.", ""]
+    if args.commands and os.path.exists(args.commands):
+        md += ["Commands (on the MI355X box, from the repository root, after `cd /tmp && export TMPDIR=/tmp`):", ""]
+        md += ["    " + l.rstrip() for l in open(args.commands) if l.strip()] + [""]
+
+    if args.stats:
+        dur, roles = read_trace(args.stats)
+        md += ["## Kernel trace (`--kernel-trace --stats`)", "",
+               "| step | kernel | calls | avg us | min us | max us | useful work / avg time | of peak |", "|---|---|---|---|---|---|---|---|"]
+        tot = sum(sum(v) for v in dur.values())
+        for label, v in sorted(dur.items(), key=lambda kv: -sum(kv[1])):
+            role = roles[label]
+            avg = sum(v) / len(v)
+            w = work.get(role)
+            rate = frac = ""
+            if w and role not in ("bias_residual_ln_streaming",):
+                if w["bound"] == "mfma":
+                    r_ = w["work_per_launch"] / avg / 1e6
+                    rate, frac = f"{r_:.0f} TFLOP/s", f"{r_ / w['peak']:.3f}"
+                else:
+                    r_ = w["work_per_launch"] / avg / 1e3
+                    rate, frac = f"{r_:.0f} GB/s", f"{r_ / w['peak']:.3f}"
+            md.append(f"| {role} | `{label}` | {len(v)} | {avg:.2f} | {min(v):.2f} | {max(v):.2f} | {rate} | {frac} |")
+        md += ["", f"Total GPU time of these kernels in the run: {tot / 1e3:.1f} ms.", ""]
+
+    for d in args.pmc:
+        cs, roles, n = read_counters(d)
+        names = sorted({c for v in cs.values() for c in v})
+        md += [f"## Counters (`--pmc {' '.join(names)}`), averages per dispatch", "",
+               "| step | kernel | dispatches | " + " | ".join(names) + " |", "|---|---|---|" + "---|" * len(names)]
+        derived = []
+        for label in sorted(cs, key=lambda l: roles[l]):
+            if roles[label] in ("device_copy", "offsets", "fold_vectors"):
+                continue
+            v = cs[label]
+            md.append(f"| {roles[label]} | `{label}` | {n[label]} | " + " | ".join(f"{v.get(c, float('nan')):.0f}" for c in names) + " |")
+            dv = derive(v)
+            w = work.get(roles[label])
+            if w and w["bound"] == "mfma" and "executed_gflop" in dv:
+                dv["useful_gflop"] = w["work_per_launch"] / 1e9
+                dv["useful_share_of_executed"] = dv["useful_gflop"] / dv["executed_gflop"]
+            if dv:
+                derived.append((roles[label], label, dv))
+        if derived:
+            md += ["", "Derived:", ""]
+            for role, label, dv in derived:
+                md.append(f"- {role} `{label}`: " + ", ".join(f"{k} = {x:.3f}" for k, x in dv.items()))
+        md.append("")
+
+    if args.fetch and args.write:
+        table, scale = traffic_from(args.fetch, args.write)
+        md += ["## HBM-side traffic (`--pmc FETCH_SIZE`, `--pmc WRITE_SIZE`, one run each)", "",
+               f"Scale factors from the 1 GiB device copy of the same runs: FETCH_SIZE x{scale['FETCH_SIZE']:.3f}, "
+               f"WRITE_SIZE x{scale['WRITE_SIZE']:.3f}.", "",
+               "| step | FETCH_SIZE KiB | WRITE_SIZE KiB | bytes beyond L2 per launch | algorithmic bytes | ratio |", "|---|---|---|---|---|---|"]
+        for role, (f, w_, h) in sorted(table.items()):
+            if role == "device_copy":
+                continue
+            alg = bench.get("algorithmic_bytes", {}).get(role)
+            md.append(f"| {role} | {f:.1f} | {w_:.1f} | {h:.0f} | {alg if alg else ''} | {h / alg:.2f} |" if alg else
+                      f"| {role} | {f:.1f} | {w_:.1f} | {h:.0f} | | |")
+        md.append("")
+        if args.traffic:
+            update_traffic_file(args.traffic, args.workload, table)
+
+    with open(args.out, "w") as fh:
+        fh.write("\n".join(md) + "\n")
+    print(f"wrote {args.out}")
+
+
+if __name__ == "__main__":
+    main()

@@ -48,6 +48,10 @@ def test_argument_errors_before_launch(lib):
     assert lib.bt_build_offsets(one, one, 2, 8, one, one, ctypes.byref(tot), None) == 1
     assert lib.bt_build_offsets(one, None, 2, 0, one, one, ctypes.byref(tot), None) == 1
     assert lib.bt_build_offsets(one, None, 2, 1 << 20, one, one, ctypes.byref(tot), None) == 2
+    two = (ctypes.c_int32 * 2)()
+    assert lib.bt_build_offsets_stats(None, None, 2, 8, one, one, two, None) == 1
+    assert lib.bt_build_offsets_stats(one, None, 2, 8, one, one, None, None) == 1
+    assert lib.bt_build_offsets_stats(one, None, 2, 1 << 20, one, one, two, None) == 2
     # pack / unpack
     assert lib.bt_pack(one, one, 4, 7, one, None) == 1
     assert lib.bt_pack(one, one, -1, 8, one, None) == 1
@@ -61,6 +65,8 @@ def test_argument_errors_before_launch(lib):
     assert lib.bt_varlen_mha(one, one, one, 100, None, None, None, one, 2, 10, 8, 12, 64, f, one, None, 0, None) == 1
     assert lib.bt_varlen_mha(one, one, one, 2304, None, None, None, one, 2, 100, 8, 12, 64, f, one, None, 0, None) == 1
     assert lib.bt_varlen_mha(one, one, one, 2304, None, None, None, one, 0, 0, 8, 12, 64, f, one, None, 0, None) == 0
+    assert lib.bt_varlen_mha(one, one, one, 2304, None, None, None, one, 2, 10, 4097, 12, 64, f, one, None, 0,
+                             None) == 2                          # max_len beyond BT_MAX_SEQ
     assert lib.bt_varlen_mha(one, one, one, 2304, None, None, None, one, 2, 10, 8, 12, 64, ctypes.c_float(-1.0),
                              one, None, 0, None) == 1
     # gemm / layernorm

@@ -71,6 +71,55 @@ def test_offsets_pinned_and_pageable_total(bt):
     assert bt.build_offsets(lengths=dev(L), S=64, pinned=True)[2] == int(L.sum())   # usable again after an error
 
 
+@pytest.mark.parametrize("pinned", [True, False])
+def test_offsets_stats_returns_longest_sequence(bt, pinned):
+    """bt_build_offsets_stats: same offsets, plus the longest sequence on the host and in cu_seqlens[B+1]."""
+    for L, S in (([5, 0, 64, 17], 64), ([0, 0], 8), ([1] * 130, 3), (I.draw_lengths(I.WORKLOADS["bert_large_b32_s512"]), 512)):
+        L = np.asarray(L, np.int32)
+        cu, tok, T, mx = bt.build_offsets(lengths=dev(L), S=S, pinned=pinned, with_max=True)
+        rcu, rtok, rT = O.build_offsets(O.lengths_to_mask(L, S))
+        assert T == rT and mx == int(L.max())
+        assert np.array_equal(host(cu), rcu) and np.array_equal(host(tok), rtok)
+    rng = np.random.default_rng(9)
+    mask = (rng.random((7, 100)) < 0.4).astype(np.int32)
+    cu, tok, T, mx = bt.build_offsets(mask=dev(mask), pinned=pinned, with_max=True)
+    assert mx == int(mask.sum(axis=1).max()) and T == int(mask.sum())
+    with pytest.raises(bt.BtError):
+        bt.build_offsets(lengths=dev(np.array([3, 65], np.int32)), S=64, pinned=pinned, with_max=True)
+
+
+def test_offsets_refused_during_stream_capture(bt):
+    """The call waits for a device result on the host, so it cannot be part of a HIP graph: on a capturing
+    stream it returns BT_ERR_UNSUPPORTED at once, records nothing, and the capture stays valid."""
+    import torch
+    L = dev(np.array([5, 3], np.int32))
+    x = torch.zeros(8, device="cuda:0")
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        x.add_(1.0)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        with pytest.raises(bt.BtError) as e:
+            bt.build_offsets(lengths=L, S=8, pinned=False)
+        x.add_(1.0)
+    assert e.value.code == 2
+    g.replay()
+    torch.cuda.synchronize()
+    assert float(x[0]) == 2.0
+    assert bt.build_offsets(lengths=L, S=8)[2] == 8            # and works again outside the capture
+
+
+def test_varlen_mha_sequence_longer_than_max_len_is_still_computed(bt):
+    """max_len is a hint for the kernel choice only: the work list comes from cu_seqlens, so rows beyond an
+    understated max_len are computed like all others."""
+    lengths = np.array([300, 40, 200, 64], np.int32)
+    for max_len in (151, 256):                                  # T = 604 <= 4 * 151
+        assert _mha_case(bt, lengths, 3, seed=31, max_len=max_len) <= 4e-3
+
+
 def test_offsets_lengths_edge_cases(bt):
     for L, S in (([0, 0, 0], 8), ([8, 0, 8], 8), ([64] * 20, 64), ([1] * 130, 3), ([0, 5, 0, 1, 128], 128)):
         L = np.array(L, np.int32)
@@ -129,10 +178,6 @@ def test_gemm_slab_schedule_all_residues(bt, M, N):
         assert err <= 2e-3 * max(1.0, np.abs(ref).max()), (nk, err)
 
 
-def _gelu_tanh64(x):
-    return 0.5 * x * (1 + np.tanh(np.sqrt(2 / np.pi) * (x + 0.044715 * x ** 3)))
-
-
 @pytest.mark.parametrize("M,N,K,act,bias", [
     (1, 8, 8, 0, False), (5, 16, 40, 0, True), (77, 72, 200, 1, True), (150, 2304, 768, 0, True),
     (129, 768, 3072, 0, False), (300, 3072, 768, 1, True), (2456, 768, 768, 0, True), (2456, 3072, 768, 2, True),
@@ -150,7 +195,7 @@ def test_gemm_bias_act(bt, M, N, K, act, bias):
     if act == 1:
         ref = O.gelu(ref)
     elif act == 2:
-        ref = _gelu_tanh64(ref)
+        ref = O.gelu_tanh(ref)
     err = np.abs(got - ref)
     assert err.max() <= 2e-3 + 1e-3 * np.abs(ref).max(), err.max()
     assert (err <= 1e-3 + 2 ** -10 * np.abs(ref)).mean() > 0.999
@@ -171,7 +216,7 @@ def test_gelu_epilogue_over_every_fp16_input(bt, act):
     a = np.eye(K, dtype=np.float16)
     got = host(bt.gemm_bias_act(dev(a), dev(w), None, act))            # [K, N]
     x = w.T.astype(np.float64)
-    ref = (O.gelu(x) if act == 1 else _gelu_tanh64(x)).astype(np.float16)
+    ref = (O.gelu(x) if act == 1 else O.gelu_tanh(x)).astype(np.float16)
     def line(h):                                                       # fp16 bits -> position on the number line
         b = h.view(np.uint16).astype(np.int32)
         return np.where(b & 0x8000, -(b & 0x7FFF), b)                  # +0 and -0 coincide
@@ -341,6 +386,19 @@ def test_layer_b4_s64(bt, stress):
     assert np.array_equal(got, got2)
 
 
+def test_layer_tanh_gelu(bt):
+    """gelu_kind = 1 (tanh form) through the whole layer against the oracle's tanh-form layer; the erf-form
+    oracle layer must NOT be what it matches best (the two activations differ by up to 4.7e-4 per element)."""
+    wl = I.WORKLOADS["layer_b4_s64"]
+    L = I.draw_lengths(wl)
+    x = I.make_hidden_packed(wl, int(L.sum()))
+    cu, tok, T = bt.build_offsets(lengths=dev(L), S=wl.S)
+    p = I.make_layer_params(wl, 0, True)
+    got = host(bt.encoder_layer_fwd(bt.Layer(p, gelu_kind=1), dev(x), cu, wl.S)).astype(np.float64)
+    ref = _oracle_each(wl, L, x, [O.LayerWeights(**p, gelu_kind="tanh")], [1])[1]
+    assert np.abs(got - ref).max() <= TOL_LAYER
+
+
 def test_layer_zero_length_sequences(bt):
     wl = I.WORKLOADS["layer_b4_s64"]
     L = np.array([0, 17, 0, 64], np.int32)
@@ -378,38 +436,75 @@ def test_stack_bert_base_b16_s256(bt):
     assert err <= TOL_12, err
 
 
-def _sampled_stack(bt, name, tol_mid, tol_end, folded):
+_ORACLE_CACHE = {}
+
+
+def _oracle_each(wl, L, x_packed, ow, checkpoints, key=None):
+    """The oracle stack on EVERY sequence of the batch, each run alone at its own length (sequences never
+    interact, so this is the padded layer's result on the valid tokens at a fraction of the padded cost).
+    Returns {n: packed fp64 [T,H] output after n layers} for n in checkpoints.  `key` caches the result for the
+    other parametrisations of the same workload."""
+    if key is not None and key in _ORACLE_CACHE:
+        return _ORACLE_CACHE[key]
+    cu = np.concatenate([[0], np.cumsum(L)])
+    out = {n: np.zeros((int(cu[-1]), wl.H)) for n in checkpoints}
+    for b in range(len(L)):
+        if L[b] == 0:
+            continue
+        y = x_packed[cu[b]: cu[b + 1]].astype(np.float64)[None]
+        mask = np.ones((1, int(L[b])), np.int32)
+        for i, w in enumerate(ow):
+            y = O.encoder_layer(y, mask, w)
+            if i + 1 in out:
+                out[i + 1][cu[b]: cu[b + 1]] = y[0]
+    if key is not None:
+        _ORACLE_CACHE[key] = out
+    return out
+
+
+def _full_stack(bt, name, tol_mid, tol_end, folded):
+    """Every sequence of the workload against the oracle: end of the stack (and layer 12 of a deeper one), plain
+    or LayerNorm-folded; for the plain pipeline also single layers (first, middle, last) at the per-layer
+    bound, GPU layer i against the oracle applied to the GPU's own layer i-1 output."""
     wl = I.WORKLOADS[name]
     layers, L, x, cu = _run_stack(bt, wl, wl.layers)
     fold = bt.encoder_prepare(layers) if folded else None
-    order = np.argsort(L)
-    seqs = sorted({int(order[0]), int(order[len(order) // 2]), int(order[-1])})
-    full = host(bt.encoder_fwd(layers, dev(x), cu, wl.S, fold=fold)).astype(np.float64)
     ow = oracle_layers(wl, wl.layers)
-    ref, cuh = _oracle_on(wl, L, x, ow, seqs)
-    err = max(np.abs(full[cuh[b]: cuh[b + 1]] - ref[i]).max() for i, b in enumerate(seqs))
+    checkpoints = sorted({min(12, wl.layers), wl.layers})
+    ref = _oracle_each(wl, L, x, ow, checkpoints, key=name)
+    full = host(bt.encoder_fwd(layers, dev(x), cu, wl.S, fold=fold)).astype(np.float64)
+    err = np.abs(full - ref[wl.layers]).max()
     assert err <= tol_end, err
     if wl.layers > 12:
         fold12 = bt.encoder_prepare(layers[:12]) if folded else None
         mid = host(bt.encoder_fwd(layers[:12], dev(x), cu, wl.S, fold=fold12)).astype(np.float64)
-        refm, _ = _oracle_on(wl, L, x, ow[:12], seqs)
-        errm = max(np.abs(mid[cuh[b]: cuh[b + 1]] - refm[i]).max() for i, b in enumerate(seqs))
+        errm = np.abs(mid - ref[12]).max()
         assert errm <= tol_mid, errm
-    # LayerNorm with gamma=1, beta=0: every output row has mean 0 and variance 1 (property, all rows)
-    assert np.abs(full.mean(axis=1)).max() < 5e-3 and np.abs(full.var(axis=1) - 1).max() < 2e-2
+    if not folded:
+        cur, prev_host, worst = dev(x), x, 0.0
+        probe = (0, wl.layers // 2, wl.layers - 1)
+        for i in range(wl.layers):
+            nxt = bt.encoder_layer_fwd(layers[i], cur, cu, wl.S)
+            g = host(nxt)
+            if i in probe:
+                one = _oracle_each(wl, L, prev_host, [ow[i]], [1])[1]
+                worst = max(worst, np.abs(g.astype(np.float64) - one).max())
+            cur, prev_host = nxt, g
+        assert worst <= TOL_LAYER, worst
+        assert np.array_equal(prev_host.astype(np.float64), full)      # stack == layer by layer, bit for bit
 
 
 @pytest.mark.parametrize("folded", [False, True])
-def test_stack_bert_base_b16_s1024_sampled(bt, folded):
-    """12 layers, batch 16, max 1024: shortest / median / longest sequence through
-    the fp64 oracle (sequences are independent), plus a property on all rows."""
-    _sampled_stack(bt, "bert_base_b16_s1024", TOL_12, TOL_12, folded)
+def test_stack_bert_base_b16_s1024_all_sequences(bt, folded):
+    """12 layers, batch 16, max 1024: all 16 sequences through the fp64 oracle."""
+    _full_stack(bt, "bert_base_b16_s1024", TOL_12, TOL_12, folded)
 
 
 @pytest.mark.parametrize("folded", [False, True])
-def test_stack_bert_large_b32_s512_sampled(bt, folded):
-    """24 layers of the large shape, skewed lengths: 5e-2 at layer 12, 1e-1 at 24."""
-    _sampled_stack(bt, "bert_large_b32_s512", TOL_12, TOL_24, folded)
+def test_stack_bert_large_b32_s512_all_sequences(bt, folded):
+    """24 layers of the large shape, skewed lengths, all 32 sequences: 5e-2 at layer 12; the bound at layer
+    24 (1e-1) is an extrapolation of the stated 1e-2 per layer / 5e-2 after 12, not a stated figure."""
+    _full_stack(bt, "bert_large_b32_s512", TOL_12, TOL_24, folded)
 
 
 @pytest.mark.parametrize("name,n_layers,stress", [("layer_b4_s64", 1, True), ("layer_b4_s64", 2, True),
@@ -490,14 +585,14 @@ def test_encoder_fwd_padded_all_padding(bt):
 
 
 @pytest.mark.parametrize("name", ["albert_b16_s256", "distilbert_b16_s256"])
-def test_stack_table4_shape_variants_sampled(bt, name):
+def test_stack_table4_shape_variants(bt, name):
     """Stack variants of Table IV: 12 layers sharing one parameter set (16 heads, hidden 1024) and a
-    6-layer BERT-base-shaped stack; shortest / median / longest sequence through the oracle."""
+    6-layer BERT-base-shaped stack; every sequence through the oracle."""
     wl = I.WORKLOADS[name]
     if wl.shared_weights:
         p0, p5 = I.make_layer_params(wl, 0), I.make_layer_params(wl, 5)
         assert all(np.array_equal(p0[k], p5[k]) for k in ("w_qkv", "w_o", "w_1", "w_2"))
-    _sampled_stack(bt, name, TOL_12, TOL_12, False)
+    _full_stack(bt, name, TOL_12, TOL_12, False)
 
 
 # ------------------------------------------------------------------ LayerNorm folded into the GEMM epilogues
