@@ -228,18 +228,19 @@ def sweep(args):
 
 def timed_steps(torch, step, steps, warmup):
     """Runs `warmup` untimed and `steps` timed steps.  Returns (seconds for all timed steps, per-step seconds).
-    The total is the wall clock between two device synchronisations around exactly `steps` steps.  A step begins
-    with a call that waits on the host for a device result that is ordered behind the previous step's kernels
-    (the token count of bt_build_offsets), so the host timestamps taken at the top of each step are paced by the
-    GPU and their differences are per-step durations without any extra synchronisation."""
+    The total is the wall clock between two device synchronisations around exactly `steps` steps.
+    Per-step durations need no extra synchronisation: every step begins with bt_build_offsets, which returns
+    only when its kernel has run, i.e. when everything the previous step enqueued on the stream is complete;
+    `step(mark)` calls mark() right after that call, so the differences of consecutive marks are the GPU's
+    time for one whole step (forward of step i plus the prefix-sum kernel of step i+1)."""
     for _ in range(warmup):
-        step()
+        step(lambda: None)
     torch.cuda.synchronize()
     stamps = []
+    mark = lambda: stamps.append(time.perf_counter())
     t0 = time.perf_counter()
     for _ in range(steps):
-        stamps.append(time.perf_counter())
-        step()
+        step(mark)
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     stamps.append(t1)
@@ -422,18 +423,20 @@ def main():
     y_padded = torch.empty((wl.B, wl.S, H), dtype=torch.float16, device="cuda:0")
     y_padded_sep = torch.empty_like(y_padded)
 
-    def step_separate(out_=y_padded_sep):
+    def step_separate(mark, out_=y_padded_sep):
         cu, tok, t = bt.build_offsets(lengths=lengths_d, S=wl.S)
+        mark()
         xp = bt.pack(x_padded, tok, out=x_packed[:t])
         yp = bt.encoder_fwd(layers, xp, cu, wl.S, out=y_packed[:t], ws=ws, fold=fold)
         bt.unpack(yp, tok, wl.B, wl.S, out=out_)
 
-    def step_fused():
+    def step_fused(mark):
         cu, tok, t = bt.build_offsets(lengths=lengths_d, S=wl.S)
+        mark()
         bt.encoder_fwd_padded(layers, x_padded, tok, cu, out=y_padded, ws=ws)
 
     separate = args.separate_pack_unpack or fold is not None     # the padded entry point takes no fold vectors
-    step = (lambda: step_separate(y_padded)) if separate else step_fused
+    step = (lambda mark: step_separate(mark, y_padded)) if separate else step_fused
     step_name = "build_offsets+pack+encoder_fwd+unpack" if separate else "build_offsets+encoder_fwd_padded"
     dt, per = timed_steps(torch, step, args.steps, args.warmup)
     stats = step_stats(wl.B, dt, per)
@@ -479,8 +482,9 @@ def main():
         with torch.cuda.graph(graph):
             body()
 
-        def step_graph():
+        def step_graph(mark):
             bt.build_offsets(lengths=lengths_d, S=wl.S)      # same offsets every step here; still computed and waited for
+            mark()
             graph.replay()
 
         dtg, perg = timed_steps(torch, step_graph, args.steps, max(args.warmup // 2, 2))
@@ -558,14 +562,32 @@ def main():
         mha = bind(lib.bt_varlen_mha, C.c_void_p(qb), C.c_void_p(qb + 2 * HD), C.c_void_p(qb + 4 * HD), 3 * HD, None, None,
                    None, ptr(cu), wl.B, T, wl.S, wl.heads, wl.head_dim, C.c_float(wl.head_dim ** -0.5), ptr(attn), None,
                    0, st)
+        # GEMM #1 / #3 and the LayerNorms as the layer runs them: K slices (fp32) where the library splits K
+        nsl = C.c_int(0)
+        sl_bytes = max(int(lib.bt_gemm_kslices_bytes(T, H, H)), int(lib.bt_gemm_kslices_bytes(T, H, F)), 16)
+        slices = torch.empty(sl_bytes // 4, dtype=torch.float32, device="cuda:0")
+        def gemm_ks(a, w, K, c):
+            return bind(lib.bt_gemm_kslices, ptr(a), ptr(w), T, H, K, ptr(c), ptr(slices), C.c_size_t(sl_bytes),
+                        C.byref(nsl), st)
+        def ln_after(gemm_fn, b, r, ga, be, y_):
+            if gemm_fn() != 0:
+                raise RuntimeError("bt_gemm_kslices failed")
+            if nsl.value == 0:
+                return lnk(proj, b, r, ga, be, y_), 0
+            return bind(lib.bt_add_bias_residual_layernorm_kslices, ptr(slices), nsl.value, ptr(b), ptr(r), ptr(ga),
+                        ptr(be), eps, T, H, ptr(y_), st), nsl.value
+        g1, g3 = gemm_ks(attn, P["w_o"], H, proj), gemm_ks(g, P["w_2"], F, proj)
+        ln0, ks1 = ln_after(g1, P["b_o"], xp, P["ln0_g"], P["ln0_b"], y1)
+        ln1, ks3 = ln_after(g3, P["b_2"], y1, P["ln1_g"], P["ln1_b"], y2)
+        out["k_slices"] = {"gemm1_proj": ks1, "gemm3_ffn_down": ks3}
         steps = [
             ("gemm0_qkv_bias", "mfma", 6.0 * T * H * H, gemm(xp, P["w_qkv"], P["b_qkv"], T, 3 * H, H, 0, qkv)),
             ("varlen_mha", "mfma", 4.0 * sum_l2 * H, mha),
-            ("gemm1_proj", "mfma", 2.0 * T * H * H, gemm(attn, P["w_o"], None, T, H, H, 0, proj)),
-            ("bias_residual_ln0", "hbm", 6.0 * T * H, lnk(proj, P["b_o"], xp, P["ln0_g"], P["ln0_b"], y1)),
+            ("gemm1_proj", "mfma", 2.0 * T * H * H, g1),
+            ("bias_residual_ln0", "hbm", 6.0 * T * H, ln0),
             ("gemm2_bias_gelu", "mfma", 2.0 * T * H * F, gemm(y1, P["w_1"], P["b_1"], T, F, H, 1, g)),
-            ("gemm3_ffn_down", "mfma", 2.0 * T * H * F, gemm(g, P["w_2"], None, T, H, F, 0, proj)),
-            ("bias_residual_ln1", "hbm", 6.0 * T * H, lnk(proj, P["b_2"], y1, P["ln1_g"], P["ln1_b"], y2)),
+            ("gemm3_ffn_down", "mfma", 2.0 * T * H * F, g3),
+            ("bias_residual_ln1", "hbm", 6.0 * T * H, ln1),
             ("pack", "hbm", 4.0 * T * H, bind(lib.bt_pack, ptr(x_padded), ptr(tok), T, H, ptr(x_packed), st)),
             ("unpack", "hbm", 2.0 * T * H + 2.0 * wl.B * wl.S * H,
              bind(lib.bt_unpack, ptr(y2), ptr(tok), T, wl.B, wl.S, H, ptr(y_padded_sep), st)),
@@ -591,7 +613,7 @@ def main():
             kernels.append({"kernel": name, "bound": bound, "us": round(us, 2), "launches_per_step": per_step,
                             "achieved": round(ach, 2), "peak": peak, "unit": unit, "frac": round(ach / peak, 4),
                             "work_per_launch": work})
-            if name in gemm_shapes:
+            if name in gemm_shapes and not out["k_slices"].get(name, 0):
                 # tile-quantisation ceiling of this product: useful share of the tiles' area times the share of
                 # the 256 compute units that the last round of tiles occupies
                 M_, N_, K_, act_ = gemm_shapes[name]

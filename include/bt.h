@@ -167,6 +167,27 @@ bt_status bt_add_bias_residual_layernorm(const bt_half* d_x, const bt_half* d_bi
                                          bt_half* d_y, bt_stream stream);
 
 /*
+ * The output projection and the FFN-down product as the encoder layer runs them (Table II, GEMM #1 and #3;
+ * Sec. III-C1 for what follows them): a product whose consumer is the add-bias + residual + LayerNorm
+ * kernel may leave its reduction over K unfinished.  bt_gemm_kslices decides from the shape alone
+ * whether to split K (it does when the tokens are so few that whole tiles would leave most of the chip idle):
+ *   *n_slices == 0  the product was written to d_C, fp16 [M,N], as bt_gemm_bias_act without bias writes it;
+ *   *n_slices == s  (2..8) d_slices holds s fp32 slices [s][M][N] whose sum is the product (d_C untouched);
+ *                   slice i covers K range [i K/s, (i+1) K/s).
+ * d_slices: device, 16-byte aligned, at least bt_gemm_kslices_bytes(M, N, K) bytes (0 when the shape is not
+ * split; then d_slices may be NULL); BT_ERR_WORKSPACE if it is missing or too small.  n_slices: host.
+ * bt_add_bias_residual_layernorm_kslices is bt_add_bias_residual_layernorm with x given as such slices,
+ * added in slice order in fp32 (no rounding of the product to fp16 in between); 1 <= n_slices <= 8.
+ */
+size_t bt_gemm_kslices_bytes(int M, int N, int K);
+bt_status bt_gemm_kslices(const bt_half* d_A, const bt_half* d_W, int M, int N, int K, bt_half* d_C,
+                          float* d_slices, size_t slices_bytes, int* n_slices, bt_stream stream);
+bt_status bt_add_bias_residual_layernorm_kslices(const float* d_slices, int n_slices, const bt_half* d_bias,
+                                                 const bt_half* d_residual, const bt_half* d_gamma,
+                                                 const bt_half* d_beta, float eps, int T, int H, bt_half* d_y,
+                                                 bt_stream stream);
+
+/*
  * One encoder layer's parameters (device pointers, fp16).  Shapes:
  *   w_qkv [3H,H]  rows 0..H-1 produce Q, H..2H-1 K, 2H..3H-1 V;   b_qkv [3H]
  *   w_o [H,H], b_o [H];  ln0_g, ln0_b [H]

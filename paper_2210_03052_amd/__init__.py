@@ -53,6 +53,12 @@ _SIGNATURES = {
                                     _c.c_void_p, _c.c_void_p]),
     "bt_add_bias_residual_layernorm": (_c.c_int, [_c.c_void_p, _c.c_void_p, _c.c_void_p, _c.c_void_p, _c.c_void_p,
                                                   _c.c_float, _c.c_int, _c.c_int, _c.c_void_p, _c.c_void_p]),
+    "bt_gemm_kslices_bytes": (_c.c_size_t, [_c.c_int, _c.c_int, _c.c_int]),
+    "bt_gemm_kslices": (_c.c_int, [_c.c_void_p, _c.c_void_p, _c.c_int, _c.c_int, _c.c_int, _c.c_void_p, _c.c_void_p,
+                                   _c.c_size_t, _c.POINTER(_c.c_int), _c.c_void_p]),
+    "bt_add_bias_residual_layernorm_kslices": (_c.c_int, [_c.c_void_p, _c.c_int, _c.c_void_p, _c.c_void_p, _c.c_void_p,
+                                                          _c.c_void_p, _c.c_float, _c.c_int, _c.c_int, _c.c_void_p,
+                                                          _c.c_void_p]),
     "bt_layer_workspace_bytes": (_c.c_size_t, [_c.POINTER(bt_layer), _c.c_int, _c.c_int, _c.c_int]),
     "bt_encoder_layer_fwd": (_c.c_int, [_c.POINTER(bt_layer), _c.c_void_p, _c.c_void_p, _c.c_int, _c.c_int,
                                         _c.c_int, _c.c_void_p, _c.c_void_p, _c.c_size_t, _c.c_void_p]),
@@ -260,6 +266,40 @@ def add_bias_residual_layernorm(x, bias, residual, gamma, beta, eps, out=None):
         out = torch.empty_like(x)
     _call("bt_add_bias_residual_layernorm", _ptr(x), _ptr(bias), _ptr(residual), _ptr(gamma), _ptr(beta),
           float(eps), T, H, _ptr(out), _stream())
+    return out
+
+
+def gemm_kslices(a, w, out=None, slices=None):
+    """bt_gemm_kslices: a [M,K] @ w[N,K]^T with the reduction over K possibly left to the consumer.
+    Returns (c fp16 [M,N] or None, slices fp32 [s,M,N] or None): exactly one of the two is not None."""
+    torch = _torch()
+    _chk(a, torch.float16, "a", 2)
+    _chk(w, torch.float16, "w", 2)
+    M, K = a.shape
+    N = w.shape[0]
+    nbytes = int(load_library().bt_gemm_kslices_bytes(M, N, K))
+    if slices is None and nbytes:
+        slices = torch.empty(nbytes // 4, dtype=torch.float32, device=a.device)
+    if out is None and not nbytes:
+        out = torch.empty((M, N), dtype=torch.float16, device=a.device)
+    n = _c.c_int(-1)
+    _call("bt_gemm_kslices", _ptr(a), _ptr(w), M, N, K, _ptr(out), _ptr(slices),
+          slices.numel() * 4 if slices is not None else 0, _c.byref(n), _stream())
+    if n.value == 0:
+        return out, None
+    return None, slices[: n.value * M * N].view(n.value, M, N)
+
+
+def add_bias_residual_layernorm_kslices(slices, bias, residual, gamma, beta, eps, out=None):
+    """bt_add_bias_residual_layernorm_kslices: x given as fp32 K slices [s,T,H]."""
+    torch = _torch()
+    _chk(slices, torch.float32, "slices", 3)
+    _chk(residual, torch.float16, "residual", 2)
+    n, T, H = slices.shape
+    if out is None:
+        out = torch.empty_like(residual)
+    _call("bt_add_bias_residual_layernorm_kslices", _ptr(slices), n, _ptr(bias), _ptr(residual), _ptr(gamma),
+          _ptr(beta), float(eps), T, H, _ptr(out), _stream())
     return out
 
 

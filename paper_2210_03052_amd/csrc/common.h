@@ -76,6 +76,11 @@ __device__ __forceinline__ void store_through(half_t* gptr, const uint2_t& v) {
                ::"v"((half_t __attribute__((address_space(1)))*)gptr), "v"(v) : "memory");
 }
 
+__device__ __forceinline__ void store_through(float* gptr, const float4_t& v) {
+  asm volatile("global_store_dwordx4 %0, %1, off sc1\n\ts_nop 1"
+               ::"v"((float __attribute__((address_space(1)))*)gptr), "v"(v) : "memory");
+}
+
 // Butterfly reductions over the 64 lanes of a wavefront.
 __device__ __forceinline__ float wave_sum(float v) {
 #pragma unroll

@@ -246,24 +246,36 @@ __device__ __forceinline__ void store_tile(const float16_t (&acc)[MI][NI], const
   }
 }
 
-// Split-K epilogue: the fp32 accumulators as they are, 16 bytes per lane and column group.
+// Split-K epilogue: the fp32 accumulators of this wave's tile, one 32-row block at a time through a private
+// LDS region (rows padded by 4 floats) so that they leave as whole row segments, 16 bytes per lane, WN/4
+// lanes per row, instead of 16-byte pieces scattered over 32 rows.
 template <int MI, int NI>
 __device__ __forceinline__ void store_partial(const float16_t (&acc)[MI][NI], float* __restrict__ P, int M, int N,
-                                              int m_base, int n_base, int l32, int hf) {
+                                              int m_base, int n_base, int lane,
+                                              float* stage /* this wave's LDS region: 32 x (NI*32+4) floats */) {
+  constexpr int WN = NI * 32, LD = WN + 4;
+  constexpr int LPR = WN / 4, RPP = 64 / LPR;  // lanes per row, rows per pass
+  const int l32 = lane & 31, hf = lane >> 5;
+  const int rr = lane / LPR, cc = (lane % LPR) * 4;
 #pragma unroll
-  for (int i = 0; i < MI; ++i)
+  for (int i = 0; i < MI; ++i) {
 #pragma unroll
     for (int j = 0; j < NI; ++j)
 #pragma unroll
       for (int g = 0; g < 4; ++g) {
-        const int m = m_base + i * 32 + l32, n = n_base + j * 32 + 8 * g + 4 * hf;
-        if (m < M && n < N) {
-          float4_t v;
+        float4_t v;
 #pragma unroll
-          for (int t = 0; t < 4; ++t) v[t] = acc[i][j][4 * g + t];
-          *reinterpret_cast<float4_t*>(P + (size_t)m * N + n) = v;
-        }
+        for (int t = 0; t < 4; ++t) v[t] = acc[i][j][4 * g + t];
+        *reinterpret_cast<float4_t*>(stage + l32 * LD + j * 32 + 8 * g + 4 * hf) = v;
       }
+    // same wavefront reads what it wrote: LDS operations of a wave complete in order
+#pragma unroll
+    for (int r0 = 0; r0 < 32; r0 += RPP) {
+      const int mr = m_base + i * 32 + r0 + rr, n = n_base + cc;
+      const float4_t v = *reinterpret_cast<const float4_t*>(stage + (r0 + rr) * LD + cc);
+      if (mr < M && n < N) store_through(P + ((size_t)mr * N + n), v);  // N % 8 == 0: 4 columns all in or all out
+    }
+  }
 }
 
 // Mean and 1/sigma of the rows m_base + i*32 + l32 from their partial sums, in two steps so that the
@@ -383,7 +395,8 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_pipe_kernel(
   static_assert(LA * RPI * NWAVES == BM && LB * RPI * NWAVES == BN, "tile rows must split evenly over the waves");
   static_assert(NS >= 2 && (NS - 1) * TOT < 64, "vmcnt range");
 
-  constexpr int STAGE_HALVES = WM * (WN + 8);  // per-wave epilogue staging
+  // per-wave epilogue staging: the fp16 wave tile, or (split-K) one 32-row block of fp32 accumulators
+  constexpr int STAGE_HALVES = EPI == EPI_PARTIAL ? 2 * 32 * (WN + 4) : WM * (WN + 8);
   constexpr int PIPE_HALVES = NS * (BM + BN) * BK;
   constexpr int LDS_HALVES = PIPE_HALVES > NWAVES * STAGE_HALVES ? PIPE_HALVES : NWAVES * STAGE_HALVES;
   __shared__ __attribute__((aligned(1024))) half_t smem[LDS_HALVES];
@@ -612,7 +625,9 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_pipe_kernel(
   }
   if constexpr (EPI == EPI_FOLD || EPI == EPI_RESID) load_epi_vecs<NI, EPI>(ep, bias, N, n0 + wn * WN, hf, vec);
   if constexpr (EPI == EPI_PARTIAL) {
-    store_partial<MI, NI>(acc, ep.partial + (size_t)split * M * N, M, N, m0 + wm * WM, n0 + wn * WN, l32, hf);
+    __builtin_amdgcn_s_barrier();  // every wave is done reading the last slab: LDS becomes staging space
+    store_partial<MI, NI>(acc, ep.partial + (size_t)split * M * N, M, N, m0 + wm * WM, n0 + wn * WN, lane,
+                          reinterpret_cast<float*>(smem + wave * STAGE_HALVES));
   } else {
     __builtin_amdgcn_s_barrier();  // every wave is done reading the last slab: LDS becomes staging space
     store_tile<MI, NI, WGN, ACT, EPI>(acc, ep, vec, mu, rstd, rres, tn, wn, wm * WM, red, BM, C, M, N, m0 + wm * WM,
@@ -804,9 +819,15 @@ bt_status gemm_dispatch(const bt_half* A, const bt_half* W, int M, int N, int K,
 }
 
 // Split-K for token counts so small that the tile grid leaves most compute units idle and every tile
-// walks the whole K alone (Sec. IV-E, small batches): how many K slices to use for an M x N x K product
-// (1 = do not split).  Slices times tiles stays within one round of the chip; a slice keeps at least the
-// three slabs the pipeline needs; the slices divide K/64 evenly.  slices * M * N <= kSplitKFloats.
+// walks the whole K alone (Sec. IV-E, small batches): workgroup (tile, s) multiplies K slice s and stores
+// fp32 partial sums; the add-bias + residual + LayerNorm kernel that consumes the product adds the slices.
+// gemm_splitk_choice: how many K slices to use for an M x N x K product (1 = do not split).  Slices times
+// tiles stays within one round of the chip; a slice keeps at least the three slabs the pipeline needs; the
+// slices divide K/64 evenly.  slices * M * N <= kSplitKFloats (256 tiles of 64 x 64).
+// Larger tiles over K slices for the deep FFN-down product at a few thousand tokens (fewer operand bytes per
+// compute unit) were measured and are not used: at 2 308 x 768 x 3072, 128 x 128 tiles x 2 slices run 18.4 us
+// against 16.0 us unsplit -- the K loop halves but 14 MB of fp32 slices leave through the write path
+// (and the LayerNorm kernel reads them back), which costs more than the shorter loop saves.
 int gemm_splitk_choice(int M, int N, int K) {
   if ((K % 64) != 0 || M < 1) return 1;
   const long long t64 = (long long)((M + 63) / 64) * ((N + 63) / 64);
@@ -848,6 +869,32 @@ extern "C" bt_status bt_gemm_bias_act(const bt_half* d_A, const bt_half* d_W, co
   bt::GemmEpi ep;
   ep.bias = reinterpret_cast<const bt::half_t*>(d_bias);
   return bt::gemm_dispatch(d_A, d_W, M, N, K, act, bt::EPI_PLAIN, ep, d_C, static_cast<hipStream_t>(stream), nullptr);
+}
+
+extern "C" size_t bt_gemm_kslices_bytes(int M, int N, int K) {
+  if (M < 1 || N < 8 || K < 8) return 0;
+  const int sl = bt::gemm_splitk_choice(M, N, K);
+  return sl > 1 ? (size_t)sl * (size_t)M * (size_t)N * sizeof(float) : 0;
+}
+
+extern "C" bt_status bt_gemm_kslices(const bt_half* d_A, const bt_half* d_W, int M, int N, int K, bt_half* d_C,
+                                     float* d_slices, size_t slices_bytes, int* n_slices, bt_stream stream) {
+  if (M < 0 || N < 8 || K < 8 || (N % 8) != 0 || (K % 8) != 0 || !n_slices) return BT_ERR_INVALID_ARG;
+  *n_slices = 0;
+  if (M == 0) return BT_OK;
+  if (!d_A || !d_W || !bt::aligned16(d_A) || !bt::aligned16(d_W)) return BT_ERR_INVALID_ARG;
+  const int sl = bt::gemm_splitk_choice(M, N, K);
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  if (sl > 1) {
+    if (!d_slices || (reinterpret_cast<uintptr_t>(d_slices) & 15u)) return BT_ERR_WORKSPACE;
+    if (slices_bytes < (size_t)sl * (size_t)M * (size_t)N * sizeof(float)) return BT_ERR_WORKSPACE;
+    const bt_status r = bt::gemm_splitk_dispatch(d_A, d_W, M, N, K, sl, d_slices, st);
+    if (r == BT_OK) *n_slices = sl;
+    return r;
+  }
+  if (!d_C || !bt::aligned16(d_C)) return BT_ERR_INVALID_ARG;
+  bt::GemmEpi ep;
+  return bt::gemm_dispatch(d_A, d_W, M, N, K, BT_ACT_NONE, bt::EPI_PLAIN, ep, d_C, st, nullptr);
 }
 
 extern "C" bt_status bt_gemm_tile_shape(int M, int N, int K, bt_act act, int* bm, int* bn) {

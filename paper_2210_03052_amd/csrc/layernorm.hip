@@ -241,3 +241,18 @@ extern "C" bt_status bt_add_bias_residual_layernorm(const bt_half* d_x, const bt
   return bt::layernorm_dispatch(d_x, nullptr, 0, d_bias, d_residual, d_gamma, d_beta, eps, T, H, d_y,
                                 static_cast<hipStream_t>(stream), nullptr, nullptr, 0);
 }
+
+extern "C" bt_status bt_add_bias_residual_layernorm_kslices(const float* d_slices, int n_slices, const bt_half* d_bias,
+                                                            const bt_half* d_residual, const bt_half* d_gamma,
+                                                            const bt_half* d_beta, float eps, int T, int H,
+                                                            bt_half* d_y, bt_stream stream) {
+  if (T < 0 || H < 8 || (H % 8) != 0 || !(eps >= 0.f) || n_slices < 1 || n_slices > 8) return BT_ERR_INVALID_ARG;
+  if (H > 8192) return BT_ERR_UNSUPPORTED;
+  if (T == 0) return BT_OK;
+  if (!d_slices || !d_residual || !d_gamma || !d_beta || !d_y) return BT_ERR_INVALID_ARG;
+  if (!bt::aligned16(d_slices) || !bt::aligned16(d_residual) || !bt::aligned16(d_gamma) || !bt::aligned16(d_beta) ||
+      !bt::aligned16(d_y) || (d_bias && !bt::aligned16(d_bias)))
+    return BT_ERR_INVALID_ARG;
+  return bt::layernorm_dispatch(nullptr, d_slices, n_slices, d_bias, d_residual, d_gamma, d_beta, eps, T, H, d_y,
+                                static_cast<hipStream_t>(stream), nullptr, nullptr, 0);
+}

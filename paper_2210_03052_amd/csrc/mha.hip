@@ -582,13 +582,16 @@ bt_status mha_dispatch(const bt_half* q, const bt_half* k, const bt_half* v, int
   auto h = [](const bt_half* p) { return reinterpret_cast<const half_t*>(p); };
   half_t* o = reinterpret_cast<half_t*>(out);
 #define BT_MHA_ARGS h(q), h(k), h(v), row_stride, h(bq), h(bv), cu, B, T, max_len, heads, scale, o, st
-  // Kernel choice.  Tall query tiles (4 waves x 32 rows) re-read K/V least and suit long sequences;
-  // 2-wave tiles give more workgroups; with too few of those to occupy the SIMDs, the split-key
-  // kernel puts two waves on every 32 query rows.  Two K/V stages (32 KB of LDS per workgroup) rather
-  // than three: the 120 VGPRs of the kernel allow four waves per SIMD and the third stage would cap
-  // residency at three; measured 2-8 % faster from 256 to 1024 keys, never slower.
+  // Kernel choice.  Tall query tiles (4 waves x 32 rows) re-read K/V least and start the fewest workgroups
+  // (every workgroup pays the search of its work item, the Q load and the first K/V round trip before its
+  // first MFMA); they win as soon as there is about one such workgroup per compute unit (measured: 7.7 us
+  // against 8.5 us with 2-wave tiles at 16 sequences of up to 256 tokens, 408 workgroups; 39 against 55 us
+  // at 16 x up to 1024).  2-wave tiles give more workgroups below that; with too few of those to occupy the
+  // SIMDs, the split-key kernel puts two waves on every 32 query rows.  Two K/V stages (32 KB of LDS per
+  // workgroup) rather than three: the 120 VGPRs of the kernel allow four waves per SIMD and the third
+  // stage would cap residency at three; measured 2-8 % faster from 256 to 1024 keys, never slower.
   auto blocks = [&](int bqt) { return ((long long)T / bqt + B) * heads; };
-  if (max_len > 128 && blocks(128) >= 512) return launch_mha<4, 2>(BT_MHA_ARGS);
+  if (max_len > 128 && blocks(128) >= 256) return launch_mha<4, 2>(BT_MHA_ARGS);
   if (blocks(64) >= 512) return launch_mha<2, 2>(BT_MHA_ARGS);
   return launch_mha_splitkey<2, 1>(BT_MHA_ARGS);
 #undef BT_MHA_ARGS

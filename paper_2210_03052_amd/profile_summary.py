@@ -43,9 +43,14 @@ def template_args(name: str):
     return []
 
 
-def role_of(name: str):
+STREAMING_GRID = 20_000_000     # threads: bench.py's 262 144-token pack launches 25 M of them, the workloads < 2 M
+
+
+def role_of(name: str, grid: int = 0):
     """(step of the layer, short label) for a kernel name of this library, else (None, None)."""
     a = template_args(name)
+    if "unpack_kernel" not in name and "pack_kernel" in name and grid >= STREAMING_GRID:
+        return "pack_streaming", "pack_kernel (262144 tokens)"
     if "gemm_pipe_kernel" in name and len(a) >= 8:
         bm, bn, wgm, wgn, ns, act, epi, shape = a[:8]
         label = f"gemm_pipe<{bm}x{bn},{wgm}x{wgn} waves,{ns} stages,act={act},epi={epi},shape={shape}>"
@@ -88,7 +93,7 @@ def read_trace(dirname):
     """{label: [durations in us]} and {label: role} from a kernel trace."""
     dur, roles = collections.defaultdict(list), {}
     for r in _csv(dirname, "kernel_trace.csv"):
-        role, label = role_of(r["Kernel_Name"])
+        role, label = role_of(r["Kernel_Name"], int(r.get("Grid_Size_X") or 0))
         if role is None:
             continue
         dur[label].append((int(r["End_Timestamp"]) - int(r["Start_Timestamp"])) / 1e3)
@@ -100,7 +105,7 @@ def read_counters(dirname):
     """{label: {counter: average over the dispatches of that kernel}}, {label: role}, {label: dispatches}."""
     acc, roles, n = collections.defaultdict(lambda: collections.defaultdict(list)), {}, collections.Counter()
     for r in _csv(dirname, "counter_collection.csv"):
-        role, label = role_of(r["Kernel_Name"])
+        role, label = role_of(r["Kernel_Name"], int(r.get("Grid_Size") or 0))
         if role is None:
             continue
         acc[label][r["Counter_Name"]].append(float(r["Counter_Value"]))
@@ -118,6 +123,10 @@ def derive(c):
     1024 SIMDs, the cycles their matrix pipe is busy (32 per 32x32x16 fp16 instruction); SQ_BUSY_CU_CYCLES adds
     up the cycles each compute unit has a wave resident."""
     d = {}
+    if not c.get("SQ_INSTS_VALU_MFMA_MOPS_F16") and not c.get("SQ_VALU_MFMA_BUSY_CYCLES") and not c.get("SQ_INSTS_MFMA"):
+        if c.get("SQ_WAVE_CYCLES") and "SQ_WAIT_INST_ANY" in c:
+            d["wave_cycles_waiting_on_an_instruction"] = c["SQ_WAIT_INST_ANY"] / c["SQ_WAVE_CYCLES"]
+        return d
     if "SQ_INSTS_VALU_MFMA_MOPS_F16" in c:
         d["executed_gflop"] = c["SQ_INSTS_VALU_MFMA_MOPS_F16"] * 512 / 1e9
     if "SQ_VALU_MFMA_BUSY_CYCLES" in c and c.get("SQ_BUSY_CU_CYCLES"):
@@ -216,7 +225,7 @@ def main():
             avg = sum(v) / len(v)
             w = work.get(role)
             rate = frac = ""
-            if w and role not in ("bias_residual_ln_streaming",):
+            if w and role not in ("bias_residual_ln_streaming", "pack_streaming"):
                 if w["bound"] == "mfma":
                     r_ = w["work_per_launch"] / avg / 1e6
                     rate, frac = f"{r_:.0f} TFLOP/s", f"{r_ / w['peak']:.3f}"

@@ -77,6 +77,19 @@ def test_argument_errors_before_launch(lib):
     assert lib.bt_add_bias_residual_layernorm(one, None, one, one, one, ctypes.c_float(1e-12), 4, 12, one, None) == 1
     assert lib.bt_add_bias_residual_layernorm(one, None, one, one, one, ctypes.c_float(1e-12), 4, 16384, one,
                                               None) == 2
+    # K slices: which shapes are split is a host decision; too small a slice buffer is refused before any launch
+    n = ctypes.c_int(-1)
+    assert lib.bt_gemm_kslices_bytes(186, 768, 3072) % (186 * 768 * 4) == 0
+    assert lib.bt_gemm_kslices_bytes(186, 768, 3072) >= 2 * 186 * 768 * 4
+    assert lib.bt_gemm_kslices_bytes(2308, 768, 3072) == 0            # enough tiles to fill the chip: not split
+    assert lib.bt_gemm_kslices(one, one, 186, 768, 3072, one, one, 16, ctypes.byref(n), None) == 3
+    assert lib.bt_gemm_kslices(one, one, 186, 768, 3072, one, None, 0, ctypes.byref(n), None) == 3
+    assert lib.bt_gemm_kslices(one, one, 0, 768, 3072, one, None, 0, ctypes.byref(n), None) == 0 and n.value == 0
+    assert lib.bt_gemm_kslices(one, one, 186, 768, 3072, one, one, 1 << 30, None, None) == 1
+    assert lib.bt_add_bias_residual_layernorm_kslices(one, 9, None, one, one, one, ctypes.c_float(1e-12), 4, 16,
+                                                      one, None) == 1
+    assert lib.bt_add_bias_residual_layernorm_kslices(None, 2, None, one, one, one, ctypes.c_float(1e-12), 4, 16,
+                                                      one, None) == 1
 
 
 def test_layer_checks(lib):

@@ -241,6 +241,33 @@ def test_bias_residual_layernorm(bt, T, H, bias):
     assert np.abs(got.astype(np.float64) - ref).max() <= 4e-3
 
 
+@pytest.mark.parametrize("M,N,K,split", [(186, 768, 3072, True), (186, 768, 768, True), (500, 1024, 4096, True),
+                                          (2308, 768, 3072, False), (64, 768, 128, False)])
+def test_gemm_kslices_and_layernorm_over_slices(bt, M, N, K, split):
+    """Output projection / FFN-down as the layer runs them: with few tokens the product comes back as fp32 K
+    slices whose sum is the product, and the add-bias + residual + LayerNorm kernel adds them; otherwise as one
+    fp16 tensor.  Both against fp64: the product, and LN(product + bias + residual)."""
+    rng = np.random.default_rng(M + N + K)
+    a = rng.normal(0, 1, (M, K)).astype(np.float16)
+    w = rng.normal(0, 0.03, (N, K)).astype(np.float16)
+    b, g, be = (rng.normal(m, 0.3, N).astype(np.float16) for m in (0.0, 1.0, 0.0))
+    r = rng.normal(0, 1, (M, N)).astype(np.float16)
+    c, slices = bt.gemm_kslices(dev(a), dev(w))
+    ref = a.astype(np.float64) @ w.astype(np.float64).T
+    assert (slices is not None) == split and (c is None) == split
+    pre = ref + b.astype(np.float64) + r.astype(np.float64)
+    want = O.layer_norm(pre, g, be, 1e-12)
+    if split:
+        assert 2 <= slices.shape[0] <= 8 and tuple(slices.shape[1:]) == (M, N)
+        got = host(slices).astype(np.float64).sum(axis=0)
+        assert np.abs(got - ref).max() <= 1e-4 * max(1.0, np.abs(ref).max())          # fp32 accumulation only
+        y = host(bt.add_bias_residual_layernorm_kslices(slices, dev(b), dev(r), dev(g), dev(be), 1e-12))
+    else:
+        assert np.abs(host(c).astype(np.float64) - ref).max() <= 2e-3 * max(1.0, np.abs(ref).max())
+        y = host(bt.add_bias_residual_layernorm(c, dev(b), dev(r), dev(g), dev(be), 1e-12))
+    assert np.abs(y.astype(np.float64) - want).max() <= 4e-3 + 2 ** -10 * np.abs(want).max()
+
+
 def test_layernorm_streaming_shape_sampled(bt):
     """The launch configuration the bench times at 262 144 tokens (tensors larger than the memory-side
     cache: the kernel switches to non-temporal loads and stores): sampled rows against the oracle."""
