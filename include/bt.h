@@ -19,7 +19,8 @@
  *     length 0 is allowed and contributes nothing.
  *   - Weight matrices are [out_features, in_features] row-major (the reduction
  *     dimension is contiguous), so y = x W^T + b.
- *   - The calls are re-entrant: no global state.
+ *   - The calls are re-entrant: no global state (one exception, stated at
+ *     bt_encoder_layer_fwd_static).
  */
 #ifndef BT_H_
 #define BT_H_
@@ -214,6 +215,26 @@ size_t bt_layer_workspace_bytes(const bt_layer* layer, int T, int B, int max_len
 bt_status bt_encoder_layer_fwd(const bt_layer* layer, const bt_half* d_x, const int32_t* d_cu_seqlens,
                                int B, int T, int max_len, bt_half* d_y, void* d_ws, size_t ws_bytes,
                                bt_stream stream);
+
+/*
+ * bt_encoder_layer_fwd for callers that cannot allocate device memory or pass a workspace: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same layer, same kernels, same
+ * bits; the workspace is a fixed array of BT_STATIC_SCRATCH_BYTES inside the library's code object (one
+ * per GPU, held until the process ends) instead of an argument.  The call allocates and frees nothing.
+ *   - Limit: bt_layer_workspace_bytes(layer, T, B, max_len) <= BT_STATIC_SCRATCH_BYTES, i.e. about 3 300
+ *     tokens for H = 768, F = 3072 and about 2 500 for H = 1024, F = 4096; beyond it the call returns
+ *     BT_ERR_WORKSPACE and enqueues nothing.
+ *   - The device that owns `stream` must be current.  The first call on a device looks the array's address
+ *     up once (hipGetSymbolAddress); make that call outside a stream capture.
+ *   - All calls on one GPU share the array: calls that overlap in time on the same GPU (two streams,
+ *     two threads) race and give wrong results; calls on one stream are ordered and safe.  Nothing has
+ *     to start at zero: every region is written in full by the kernel that produces it before any
+ *     kernel reads it, so the previous call's contents never matter.
+ * Everything else (argument checks, T == 0, errors) as for bt_encoder_layer_fwd.
+ */
+#define BT_STATIC_SCRATCH_BYTES (64u << 20)
+bt_status bt_encoder_layer_fwd_static(const bt_layer* layer, const bt_half* d_x, const int32_t* d_cu_seqlens,
+                                      int B, int T, int max_len, bt_half* d_y, bt_stream stream);
 
 /*
  * LayerNorm folding (optional, for bt_encoder_fwd).  A LayerNorm followed by a linear layer satisfies

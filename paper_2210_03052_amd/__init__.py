@@ -62,6 +62,8 @@ _SIGNATURES = {
     "bt_layer_workspace_bytes": (_c.c_size_t, [_c.POINTER(bt_layer), _c.c_int, _c.c_int, _c.c_int]),
     "bt_encoder_layer_fwd": (_c.c_int, [_c.POINTER(bt_layer), _c.c_void_p, _c.c_void_p, _c.c_int, _c.c_int,
                                         _c.c_int, _c.c_void_p, _c.c_void_p, _c.c_size_t, _c.c_void_p]),
+    "bt_encoder_layer_fwd_static": (_c.c_int, [_c.POINTER(bt_layer), _c.c_void_p, _c.c_void_p, _c.c_int, _c.c_int,
+                                               _c.c_int, _c.c_void_p, _c.c_void_p]),
     "bt_encoder_fold_bytes": (_c.c_size_t, [_c.POINTER(bt_layer), _c.c_int]),
     "bt_encoder_prepare": (_c.c_int, [_c.POINTER(bt_layer), _c.c_int, _c.c_void_p, _c.c_size_t, _c.c_void_p]),
     "bt_encoder_fwd": (_c.c_int, [_c.POINTER(bt_layer), _c.c_int, _c.c_void_p, _c.c_void_p, _c.c_void_p, _c.c_int,
@@ -345,6 +347,19 @@ def encoder_layer_fwd(layer: Layer, x, cu_seqlens, max_len, out=None, ws=None):
         ws, _ = _workspace(layer, T, B, max_len, x.device)
     _call("bt_encoder_layer_fwd", _c.byref(layer.desc), _ptr(x), _ptr(cu_seqlens), B, T, int(max_len), _ptr(out),
           _ptr(ws), ws.numel(), _stream())
+    return out
+
+
+def encoder_layer_fwd_static(layer: Layer, x, cu_seqlens, max_len, out):
+    """bt_encoder_layer_fwd_static: the same layer with the library's fixed workspace; `out` is required
+    (this call is for callers that must not allocate)."""
+    torch = _torch()
+    _chk(x, torch.float16, "x", 2)
+    _chk(out, torch.float16, "out", 2)
+    _chk(cu_seqlens, torch.int32, "cu_seqlens", 1)
+    T, B = x.shape[0], cu_seqlens.shape[0] - 1
+    _call("bt_encoder_layer_fwd_static", _c.byref(layer.desc), _ptr(x), _ptr(cu_seqlens), B, T, int(max_len),
+          _ptr(out), _stream())
     return out
 
 

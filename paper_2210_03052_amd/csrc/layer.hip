@@ -12,6 +12,8 @@
 //   LN(z) W^T + b = rstd (u W^T - mu c) + d,   c = W gamma,  d = W beta + b,
 // and the residual branches rebuild LN(z) = rstd (u - mu gamma) + beta on the fly.  One explicit
 // normalisation remains, at the end of the stack.
+#include <atomic>
+
 #include "common.h"
 
 namespace bt {
@@ -234,6 +236,36 @@ static bt_status check_io(const bt_half* x, const int32_t* cu, int B, int T, int
 
 }  // namespace bt
 
+// Workspace of bt_encoder_layer_fwd_static: one array per GPU, created when the code object is loaded on
+// that GPU and held until the process ends.  In host code this name is only a handle for
+// hipGetSymbolAddress -- it is NOT a device address and is never passed to a kernel or a memory call.
+static __device__ __align__(256) unsigned char scratch[BT_STATIC_SCRATCH_BYTES];
+
+namespace bt {
+// Device address of `scratch` on each GPU, resolved once per device on the first call made with that
+// device current (every GPU holds its own copy of the array at its own address).
+constexpr int kMaxDevices = 64;
+static std::atomic<void*> g_scratch_ptr[kMaxDevices];
+
+static bt_status static_scratch(void** out) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) {
+    (void)hipGetLastError();
+    return BT_ERR_HIP;
+  }
+  void* p = g_scratch_ptr[dev].load(std::memory_order_acquire);
+  if (!p) {
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) {
+      (void)hipGetLastError();
+      return BT_ERR_HIP;
+    }
+    g_scratch_ptr[dev].store(p, std::memory_order_release);  // racing first calls resolve the same address
+  }
+  *out = p;
+  return BT_OK;
+}
+}  // namespace bt
+
 using namespace bt;
 
 extern "C" const char* bt_status_string(bt_status s) {
@@ -263,6 +295,21 @@ extern "C" bt_status bt_encoder_layer_fwd(const bt_layer* layer, const bt_half* 
   if (B == 0 || T == 0) return BT_OK;
   const Workspace w = carve(d_ws, T, layer->H, layer->F);
   if (ws_bytes < w.bytes) return BT_ERR_WORKSPACE;
+  return layer_fwd(layer, d_x, d_cu_seqlens, B, T, max_len, d_y, w, static_cast<hipStream_t>(stream));
+}
+
+extern "C" bt_status bt_encoder_layer_fwd_static(const bt_layer* layer, const bt_half* d_x,
+                                                 const int32_t* d_cu_seqlens, int B, int T, int max_len,
+                                                 bt_half* d_y, bt_stream stream) {
+  bt_status s = check_layer(layer);
+  if (s != BT_OK) return s;
+  // any non-null 256-byte aligned value passes the workspace checks; the real address is resolved below
+  if ((s = check_io(d_x, d_cu_seqlens, B, T, max_len, d_y, reinterpret_cast<void*>(uintptr_t(256)))) != BT_OK) return s;
+  if (B == 0 || T == 0) return BT_OK;
+  if (carve(nullptr, T, layer->H, layer->F).bytes > (size_t)BT_STATIC_SCRATCH_BYTES) return BT_ERR_WORKSPACE;
+  void* ws = nullptr;
+  if ((s = static_scratch(&ws)) != BT_OK) return s;
+  const Workspace w = carve(ws, T, layer->H, layer->F);
   return layer_fwd(layer, d_x, d_cu_seqlens, B, T, max_len, d_y, w, static_cast<hipStream_t>(stream));
 }
 
