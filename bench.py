@@ -148,16 +148,36 @@ def sweep(args):
                        "note": "layer only = bt_encoder_layer_fwd (HIP events); whole step = build_offsets + "
                                "encoder_fwd_padded (pack / unpack fused into the first / last kernels)"})
     # Kernel fusion at the headline shape -- the shape of the add-bias + LayerNorm and add-bias + GELU figures
-    # (Sec. IV-A, IV-B).  "Separate" runs the same arithmetic as one launch per element-wise operation, with
-    # torch's element-wise kernels standing in for the unfused ones (they are not part of the library).
+    # (Sec. IV-A, IV-B) and of the step-wise encoder-layer figure (Sec. IV-D), all with this repository's own
+    # kernels: "unfused" runs the same arithmetic with the element-wise steps as kernels of their own
+    # (csrc/unfused.hip in the measurement library; never part of the encoder path).
+    import ctypes as C
+    aux = C.CDLL(os.path.join(ROOT, "paper_2210_03052_amd", "libbt_peaks.so"))
+    vp = C.c_void_p
+    aux.bt_unfused_add_bias_residual.argtypes = [vp, vp, vp, C.c_int, C.c_int, vp, vp]
+    aux.bt_unfused_bias_gelu.argtypes = [vp, vp, C.c_int, C.c_int, vp, vp]
+    aux.bt_unfused_layernorm.argtypes = [vp, vp, vp, C.c_float, C.c_int, C.c_int, vp, vp]
+    cur = lambda: vp(torch.cuda.current_stream().cuda_stream)
+    P_ = lambda t: vp(t.data_ptr()) if t is not None else vp(0)
+
+    def unfused_ln(x_, b_, r_, g_, be_, tmp, y_):            # two trips over memory (Sec. IV-A baseline)
+        assert aux.bt_unfused_add_bias_residual(P_(x_), P_(b_), P_(r_), x_.shape[0], x_.shape[1], P_(tmp), cur()) == 0
+        assert aux.bt_unfused_layernorm(P_(tmp), P_(g_), P_(be_), 1e-12, x_.shape[0], x_.shape[1], P_(y_), cur()) == 0
+
+    def unfused_gelu(a_, w_, b_, tmp, y_):                    # GEMM, then bias + activation as its own kernel (Sec. IV-B)
+        bt.gemm_bias_act(a_, w_, None, 0, out=tmp)
+        assert aux.bt_unfused_bias_gelu(P_(tmp), P_(b_), tmp.shape[0], tmp.shape[1], P_(y_), cur()) == 0
+
     wl = I.WORKLOADS["bert_base_b16_s256"]
-    T = int(I.draw_lengths(wl).sum())
+    Lh = I.draw_lengths(wl)
+    T = int(Lh.sum())
     F = wl.F
     rng = np.random.default_rng(I.BASE_SEED)
     h16 = lambda *shape, s=1.0: dev(rng.normal(0, s, shape).astype(np.float16))
     x, r, a = h16(T, H), h16(T, H), h16(T, H)
     b_h, g_h, be_h, b_f, w1 = h16(H, s=0.5), h16(H), h16(H), h16(F, s=0.5), h16(F, H, s=0.03)
     y_h, y_f = torch.empty_like(x), torch.empty((T, F), dtype=torch.float16, device="cuda:0")
+    t_h, t_f = torch.empty_like(x), torch.empty_like(y_f)
     nn = torch.nn.functional
     def graph_us(fn, per_graph=20, replays=20):
         """GPU time of one call: `per_graph` calls captured in a HIP graph (no host launch cost in the
@@ -184,13 +204,51 @@ def sweep(args):
         return e0.elapsed_time(e1) * 1e3 / (per_graph * replays)
 
     ln_fused = graph_us(lambda: bt.add_bias_residual_layernorm(x, b_h, r, g_h, be_h, 1e-12, out=y_h))
-    ln_separate = graph_us(lambda: nn.layer_norm((x + b_h) + r, (H,), g_h, be_h, 1e-12))
+    ln_separate = graph_us(lambda: unfused_ln(x, b_h, r, g_h, be_h, t_h, y_h))
     gelu_fused = graph_us(lambda: bt.gemm_bias_act(a, w1, b_f, 1, out=y_f))
-    gelu_separate = graph_us(lambda: nn.gelu(bt.gemm_bias_act(a, w1, None, 0, out=y_f) + b_f))
+    gelu_separate = graph_us(lambda: unfused_gelu(a, w1, b_f, t_f, y_f))
+
+    # One encoder layer step by step (the shape of the step-wise figure of Sec. IV-D), composed from C-ABI calls:
+    #   padded, unfused -> + fused LayerNorm -> + fused GELU -> + zero padding (packed tokens, variable-length MHA)
+    # "padded" runs every sequence at the full length S (what a padded pipeline computes); the attention of the
+    # padded rungs is this library's fused kernel at full length (the paper's padded baseline has an unfused
+    # attention on top of that, which is not rebuilt here).
+    Pm = layers[0].tensors
+    def layer_variant(Tn, cu_, S_, fused_ln, fused_gelu):
+        xin = h16(Tn, H)
+        qkv_, at_, pr_, y1_, g_, y2_ = (torch.empty((Tn, n_), dtype=torch.float16, device="cuda:0")
+                                        for n_ in (3 * H, H, H, H, F, H))
+        tmp_h, tmp_f = torch.empty_like(pr_), torch.empty_like(g_)
+        def run():
+            bt.gemm_bias_act(xin, Pm["w_qkv"], Pm["b_qkv"], 0, out=qkv_)
+            bt.varlen_mha(qkv_, cu_, S_, base.heads, out=at_)
+            bt.gemm_bias_act(at_, Pm["w_o"], None, 0, out=pr_)
+            if fused_ln: bt.add_bias_residual_layernorm(pr_, Pm["b_o"], xin, Pm["ln0_g"], Pm["ln0_b"], 1e-12, out=y1_)
+            else: unfused_ln(pr_, Pm["b_o"], xin, Pm["ln0_g"], Pm["ln0_b"], tmp_h, y1_)
+            if fused_gelu: bt.gemm_bias_act(y1_, Pm["w_1"], Pm["b_1"], 1, out=g_)
+            else: unfused_gelu(y1_, Pm["w_1"], Pm["b_1"], tmp_f, g_)
+            bt.gemm_bias_act(g_, Pm["w_2"], None, 0, out=pr_)
+            if fused_ln: bt.add_bias_residual_layernorm(pr_, Pm["b_2"], y1_, Pm["ln1_g"], Pm["ln1_b"], 1e-12, out=y2_)
+            else: unfused_ln(pr_, Pm["b_2"], y1_, Pm["ln1_g"], Pm["ln1_b"], tmp_h, y2_)
+        return graph_us(run, per_graph=5, replays=10)
+    stepwise = []
+    for wname in ("bert_base_b16_s256", "bert_base_b16_s1024"):
+        w = I.WORKLOADS[wname]
+        Lw = I.draw_lengths(w)
+        cu_pad = dev((np.arange(w.B + 1) * w.S).astype(np.int32))
+        cu_var = dev(np.concatenate([[0], np.cumsum(Lw)]).astype(np.int32))
+        rungs = [("padded, unfused", layer_variant(w.B * w.S, cu_pad, w.S, False, False)),
+                 ("+ fused add-bias/residual/LayerNorm", layer_variant(w.B * w.S, cu_pad, w.S, True, False)),
+                 ("+ fused add-bias/GELU", layer_variant(w.B * w.S, cu_pad, w.S, True, True)),
+                 ("+ zero padding and variable-length MHA", layer_variant(int(Lw.sum()), cu_var, w.S, True, True))]
+        stepwise.append({"workload": wname, "padded_tokens": w.B * w.S, "valid_tokens": int(Lw.sum()),
+                         "us_per_layer": [{"variant": n_, "us": round(u_, 1)} for n_, u_ in rungs],
+                         "speedup_over_first_rung": round(rungs[0][1] / rungs[-1][1], 2)})
     # Attention (the shape of the fused-MHA figures, Sec. IV-C): the variable-length fused kernel on the packed
     # batch against padded attention through torch -- three launches with the S x S logits in memory
     # (batched product, masked softmax, batched product), and torch's own fused padded kernel where this
-    # torch build has one.  Stand-ins again; same lengths, heads and head size.
+    # torch build has one.  torch is a stand-in here (a batched padded attention is not part of this library);
+    # same lengths, heads and head size.
     attention = []
     for wname in ("bert_base_b16_s256", "bert_base_b16_s1024"):
         w = I.WORKLOADS[wname]
@@ -213,13 +271,14 @@ def sweep(args):
         except Exception as e:                                                     # no such kernel in this build
             row["padded_torch_fused_us"] = None
         attention.append(row)
-    fusion = {"tokens": T, "hidden": H, "ffn": F, "attention": attention,
-              "add_bias_residual_layernorm_us": {"fused": round(ln_fused, 2), "separate_3_launches": round(ln_separate, 2),
+    fusion = {"tokens": T, "hidden": H, "ffn": F, "attention": attention, "encoder_layer_stepwise": stepwise,
+              "add_bias_residual_layernorm_us": {"fused": round(ln_fused, 2), "unfused_2_launches": round(ln_separate, 2),
                                                  "saved": round(1 - ln_fused / ln_separate, 3)},
-              "gemm_add_bias_gelu_us": {"fused": round(gelu_fused, 2), "separate_3_launches": round(gelu_separate, 2),
+              "gemm_add_bias_gelu_us": {"fused": round(gelu_fused, 2), "unfused_2_launches": round(gelu_separate, 2),
                                         "saved": round(1 - gelu_fused / gelu_separate, 3)},
-              "note": "separate = torch element-wise kernels as stand-ins for unfused ones; paper (A100): "
-                      "LayerNorm fusion 61-69 % of that step, GELU fusion 24 % of GEMM+bias+GELU"}
+              "note": "unfused = this repository's own element-wise kernels (csrc/unfused.hip); padded attention "
+                      "rows use torch as a stand-in; paper (A100): LayerNorm fusion 61-69 % of that step, GELU "
+                      "fusion 24 % of GEMM+bias+GELU"}
     print(json.dumps({"metric": "ms per BERT-base forward (12 layers, fp16), packed vs all tokens valid",
                       "kernel_fusion": fusion,
                       "unit": "ms", "n_gpus": 1, "dtype": "f16", "data": "synthetic", "higher_is_better": False,

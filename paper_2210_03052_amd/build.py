@@ -1,5 +1,6 @@
-"""Builds libbt.so (the C-ABI HIP library) and libbt_peaks.so (the two measurement kernels behind
-`bench.py --peaks`) in-tree with hipcc for gfx950.
+"""Builds libbt.so (the C-ABI HIP library) and libbt_peaks.so (measurement-only kernels: the two peak probes
+behind `bench.py --peaks` and the unfused element-wise baselines behind `bench.py --sweep`) in-tree with
+hipcc for gfx950.
 
     python -m paper_2210_03052_amd.build
 """
@@ -16,7 +17,7 @@ CSRC = os.path.join(PKG, "csrc")
 LIB = os.environ.get("BT_LIB_OUT") or os.path.join(PKG, "libbt.so")   # BT_LIB_OUT: build a variant elsewhere
 SOURCES = ["offsets.hip", "gemm.hip", "layernorm.hip", "mha.hip", "layer.hip"]
 PEAKS_LIB = os.path.join(PKG, "libbt_peaks.so")
-PEAKS_SOURCES = ["peaks.hip"]
+PEAKS_SOURCES = ["peaks.hip", "unfused.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fvisibility=default",

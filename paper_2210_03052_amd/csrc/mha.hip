@@ -37,6 +37,12 @@ __device__ __forceinline__ void mha_dma16(const void* gptr, uint32_t lds_base) {
   asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_base), "v"(gptr)
                : "memory", "m0");
 }
+// The same DMA with the address split into a wave-uniform base (SGPR pair) and a per-lane 32-bit byte offset:
+// walking the key tiles of a sequence then only moves the scalar base, no vector arithmetic per tile.
+__device__ __forceinline__ void mha_dma16_sv(const void* sbase, uint32_t voff, uint32_t lds_base) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds_base), "v"(voff), "s"(sbase)
+               : "memory", "m0");
+}
 template <int N>
 __device__ __forceinline__ void mha_wait_vmcnt() {
   static_assert(N >= 0 && N < 64, "vmcnt is 6 bits");
@@ -133,16 +139,24 @@ __device__ __forceinline__ void softmax_max(const float16_t (&s)[2], float scale
 
 __device__ __forceinline__ void softmax_exp(const float16_t (&s)[2], float scale_log2e, float m_run, float& l_run,
                                             half8_t (&pf)[2][2]) {
-  float psum = 0.f;
+  // The row sum is taken over the fp16 probabilities, the values the second product multiplies, two per
+  // instruction (dot product with (1, 1), fp32 accumulate) instead of one fp32 add per probability.
+  typedef __fp16 fp16x2_t __attribute__((ext_vector_type(2)));
+  const fp16x2_t ones = {(__fp16)1.0f, (__fp16)1.0f};
+  float psum0 = 0.f, psum1 = 0.f;
 #pragma unroll
   for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-    for (int r = 0; r < 16; ++r) {
-      const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(s[kb][r], scale_log2e, -m_run));
-      psum += p;
-      pf[kb][r >> 3][r & 7] = (half_t)p;
+    for (int r = 0; r < 16; r += 2) {
+      const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(s[kb][r], scale_log2e, -m_run));
+      const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(s[kb][r + 1], scale_log2e, -m_run));
+      const half2_t h = {(half_t)p0, (half_t)p1};
+      pf[kb][r >> 3][r & 7] = h[0];
+      pf[kb][r >> 3][(r & 7) + 1] = h[1];
+      if (kb == 0) psum0 = __builtin_amdgcn_fdot2(__builtin_bit_cast(fp16x2_t, h), ones, psum0, false);
+      else psum1 = __builtin_amdgcn_fdot2(__builtin_bit_cast(fp16x2_t, h), ones, psum1, false);
     }
-  l_run += psum;
+  l_run += psum0 + psum1;
 }
 
 // O^T += V^T P^T ; 16-key step ks covers S^T registers 8*(ks%2)..+7 of block ks/2, i.e. keys
@@ -287,21 +301,35 @@ __global__ __launch_bounds__(NW * 64) void varlen_mha_kernel(
   const half_t* kbase = K + (size_t)tok0 * row_stride + hofs;
   const half_t* vbase = V + (size_t)tok0 * row_stride + hofs;
   int k_chunk[PER], v_chunk[PER], t_row[PER];
+  uint32_t k_off[PER], v_off[PER];  // byte offsets of this lane's 16 bytes inside a tile that lies fully inside the sequence
 #pragma unroll
   for (int p = 0; p < PER; ++p) {
     const int r = (wave * PER + p) * 8 + (lane >> 3);
     t_row[p] = r;
     k_chunk[p] = ((lane & 7) ^ ((r >> 1) & 7)) * 8;
     v_chunk[p] = ((lane & 7) ^ (((r >> 1) & 1) << 2)) * 8;
+    k_off[p] = (uint32_t)(((int64_t)r * row_stride + k_chunk[p]) * 2);  // < 64 rows x row pitch: fits 32 bits (checked by the host)
+    v_off[p] = (uint32_t)(((int64_t)r * row_stride + v_chunk[p]) * 2);
   }
   const uint32_t lds_k = (uint32_t)(uintptr_t)(BT_AS3 const void*)sK + wave * PER * 1024;
   const uint32_t lds_v = (uint32_t)(uintptr_t)(BT_AS3 const void*)sV + wave * PER * 1024;
+  const int64_t tile_pitch = (int64_t)kKT * row_stride;  // elements between consecutive key tiles
   auto issue_tile = [&](int kt, int stage) {
+    if ((kt + 1) * kKT <= L) {  // wave-uniform: the whole tile lies inside the sequence -> scalar base, fixed lane offsets
+      const half_t* kb_ = kbase + kt * tile_pitch;
+      const half_t* vb_ = vbase + kt * tile_pitch;
 #pragma unroll
-    for (int p = 0; p < PER; ++p) {
-      const size_t row = (size_t)min(kt * kKT + t_row[p], L - 1) * row_stride;  // rows past L: clamped, masked later
-      mha_dma16(kbase + row + k_chunk[p], lds_k + stage * (TILE * 2) + p * 1024);
-      mha_dma16(vbase + row + v_chunk[p], lds_v + stage * (TILE * 2) + p * 1024);
+      for (int p = 0; p < PER; ++p) {
+        mha_dma16_sv(kb_, k_off[p], lds_k + stage * (TILE * 2) + p * 1024);
+        mha_dma16_sv(vb_, v_off[p], lds_v + stage * (TILE * 2) + p * 1024);
+      }
+    } else {
+#pragma unroll
+      for (int p = 0; p < PER; ++p) {
+        const size_t row = (size_t)min(kt * kKT + t_row[p], L - 1) * row_stride;  // rows past L: clamped, masked later
+        mha_dma16(kbase + row + k_chunk[p], lds_k + stage * (TILE * 2) + p * 1024);
+        mha_dma16(vbase + row + v_chunk[p], lds_v + stage * (TILE * 2) + p * 1024);
+      }
     }
   };
 #pragma unroll
@@ -608,6 +636,7 @@ extern "C" bt_status bt_varlen_mha(const bt_half* d_q, const bt_half* d_k, const
   if (B < 0 || T < 0 || max_len < 0 || heads < 1 || head_dim < 1) return BT_ERR_INVALID_ARG;
   if (head_dim != BT_HEAD_DIM) return BT_ERR_UNSUPPORTED;
   if (row_stride < (int64_t)heads * head_dim || (row_stride % 8) != 0) return BT_ERR_INVALID_ARG;
+  if (row_stride > (int64_t)1 << 24) return BT_ERR_UNSUPPORTED;  // a 64-row tile is addressed with 32-bit byte offsets
   if (!(scale > 0.f) || !(scale < INFINITY)) return BT_ERR_INVALID_ARG;
   if (B == 0 || T == 0) return BT_OK;
   if (max_len < 1 || (int64_t)T > (int64_t)B * max_len) return BT_ERR_INVALID_ARG;
