@@ -261,8 +261,9 @@ bt_status bt_encoder_prepare(const bt_layer* layers, int n_layers, float* d_fold
  * d_fold == NULL: each layer runs as bt_encoder_layer_fwd does (7 launches per layer).
  * d_fold from bt_encoder_prepare: the library MAY fold the LayerNorms into the GEMM epilogues
  * (5 launches per layer plus one normalisation at the end) and does so where that is the faster
- * pipeline: while ceil(T/64) * ceil(H/128) <= 256, i.e. up to about 2 700 tokens at H = 768; for more
- * tokens it runs the unfolded layers.  Same function either way.  The folded results differ from the
+ * pipeline: while ceil(T/64) * ceil(H/128) <= 256 (up to about 2 700 tokens at H = 768) and there are
+ * enough tokens that the unfolded layer would not split K (more than about 600 at H = 768); outside that
+ * range it runs the unfolded layers.  Same function either way.  The folded results differ from the
  * unfolded ones by fp16 rounding (u = gamma (.) z is stored instead of LN(z)) and by how the variance is
  * formed: from the row sums of z and z^2 in fp32 (E[z^2] - mean^2, clamped at 0), which loses accuracy
  * when a row's |mean| exceeds its standard deviation by more than about 100x -- post-LN BERT rows have
@@ -278,14 +279,16 @@ bt_status bt_encoder_fwd(const bt_layer* layers, int n_layers, const float* d_fo
  * neighbouring kernels instead of running as kernels of its own: the first GEMM and the first
  * residual read gather their rows of d_x_padded [B*S,H] through d_token_idx (pack), the last
  * LayerNorm scatters its rows into d_y_padded [B*S,H] and zero-fills every padding row (unpack).
- * d_token_idx / d_cu_seqlens / T come from bt_build_offsets for the same B and S.  Results are
- * bit-identical to bt_pack + bt_encoder_fwd (without fold vectors) + bt_unpack; two launches fewer.
- * d_x_padded is not modified and must not alias d_y_padded.  T == 0 zero-fills d_y_padded.
+ * d_token_idx / d_cu_seqlens / T come from bt_build_offsets for the same B and S.  d_fold: NULL, or the
+ * fold vectors of bt_encoder_prepare (same meaning and the same choice of pipeline by token count as for
+ * bt_encoder_fwd).  Results are bit-identical to bt_pack + bt_encoder_fwd (same d_fold) + bt_unpack; two
+ * launches fewer.  d_x_padded is not modified and must not alias d_y_padded.  T == 0 zero-fills d_y_padded.
  * Workspace as for bt_encoder_fwd (bt_layer_workspace_bytes with this T).
  */
-bt_status bt_encoder_fwd_padded(const bt_layer* layers, int n_layers, const bt_half* d_x_padded,
-                                const int32_t* d_token_idx, const int32_t* d_cu_seqlens, int B, int T, int S,
-                                bt_half* d_y_padded, void* d_ws, size_t ws_bytes, bt_stream stream);
+bt_status bt_encoder_fwd_padded(const bt_layer* layers, int n_layers, const float* d_fold,
+                                const bt_half* d_x_padded, const int32_t* d_token_idx,
+                                const int32_t* d_cu_seqlens, int B, int T, int S, bt_half* d_y_padded, void* d_ws,
+                                size_t ws_bytes, bt_stream stream);
 
 #ifdef __cplusplus
 }

@@ -70,8 +70,8 @@ _SIGNATURES = {
                                   _c.c_int, _c.c_int, _c.c_void_p, _c.c_void_p, _c.c_size_t, _c.c_void_p]),
     "bt_gemm_tile_shape": (_c.c_int, [_c.c_int, _c.c_int, _c.c_int, _c.c_int, _c.POINTER(_c.c_int), _c.POINTER(_c.c_int)]),
     "bt_encoder_fwd_padded": (_c.c_int, [_c.POINTER(bt_layer), _c.c_int, _c.c_void_p, _c.c_void_p, _c.c_void_p,
-                                         _c.c_int, _c.c_int, _c.c_int, _c.c_void_p, _c.c_void_p, _c.c_size_t,
-                                         _c.c_void_p]),
+                                         _c.c_void_p, _c.c_int, _c.c_int, _c.c_int, _c.c_void_p, _c.c_void_p,
+                                         _c.c_size_t, _c.c_void_p]),
 }
 EXPORTED = tuple(_SIGNATURES)
 
@@ -394,9 +394,9 @@ def encoder_fwd(layers, x, cu_seqlens, max_len, out=None, ws=None, fold=None):
     return out
 
 
-def encoder_fwd_padded(layers, x_padded, token_idx, cu_seqlens, out=None, ws=None):
+def encoder_fwd_padded(layers, x_padded, token_idx, cu_seqlens, out=None, ws=None, fold=None):
     """bt_encoder_fwd_padded: padded fp16 [B,S,H] in, padded fp16 [B,S,H] out (pads zero); pack and
-    unpack run inside the first and last kernels of the stack."""
+    unpack run inside the first and last kernels of the stack.  `fold` from encoder_prepare as for encoder_fwd."""
     torch = _torch()
     _chk(x_padded, torch.float16, "x_padded", 3)
     _chk(token_idx, torch.int32, "token_idx", 1)
@@ -408,6 +408,8 @@ def encoder_fwd_padded(layers, x_padded, token_idx, cu_seqlens, out=None, ws=Non
     if ws is None:
         ws, _ = _workspace(layers[0], max(T, 1), B, S, x_padded.device)
     arr = (bt_layer * len(layers))(*[l.desc for l in layers])
-    _call("bt_encoder_fwd_padded", arr, len(layers), _ptr(x_padded), _ptr(token_idx), _ptr(cu_seqlens), B, T, S,
-          _ptr(out), _ptr(ws), ws.numel(), _stream())
+    if fold is not None:
+        _chk(fold, torch.float32, "fold", 1)
+    _call("bt_encoder_fwd_padded", arr, len(layers), _ptr(fold), _ptr(x_padded), _ptr(token_idx), _ptr(cu_seqlens),
+          B, T, S, _ptr(out), _ptr(ws), ws.numel(), _stream())
     return out

@@ -50,6 +50,8 @@ struct GemmEpi {
   float inv_h = 0.f, eps = 0.f;     // 1/width and epsilon of that LayerNorm (also used by RESID)
   // RESID: v = acc + bias + residual; C = out_gamma (.) v; part_out[m][p] = (sum v, sum v^2) over column tile p
   const half_t* resid = nullptr;        // [M][N]: plain residual, or u_r if resid_part is set
+  const int32_t* resid_rows = nullptr;  // plain residual only: row m of the residual is row resid_rows[m] of `resid`
+                                        // (the padded input tensor: pack fused into the read)
   const float2* resid_part = nullptr;   // [M][resid_np] or null
   int resid_np = 0;
   const half_t* resid_gamma = nullptr;  // [N] (with resid_part): residual = rstd (u_r - mu gamma) + beta

@@ -337,16 +337,18 @@ __device__ __forceinline__ void finish_row_sums(const float2* __restrict__ part,
 // (addresses clamped into the matrix; positions outside it are ignored by the epilogue): the K loop counts
 // outstanding memory instructions by hand and must know this number.
 template <int MI, int NI>
-__device__ __forceinline__ void request_resid(const half_t* __restrict__ resid, int M, int N, int m_base, int n_base,
-                                              int l32, int hf, half4_t (&rres)[MI][NI][4]) {
+__device__ __forceinline__ void request_resid(const half_t* __restrict__ resid, const int (&rrow)[MI], int N, int n_base,
+                                              int hf, half4_t (&rres)[MI][NI][4]) {
+  // rrow[i]: the residual row of accumulator row block i of this lane (clamped into the matrix, and already
+  // translated through resid_rows where the residual is the padded input tensor)
 #pragma unroll
   for (int i = 0; i < MI; ++i)
 #pragma unroll
     for (int j = 0; j < NI; ++j)
 #pragma unroll
       for (int g = 0; g < 4; ++g) {
-        const int m = min(m_base + i * 32 + l32, M - 1), n = min(n_base + j * 32 + 8 * g + 4 * hf, N - 4);
-        const half_t* src = resid + (size_t)m * N + n;
+        const int n = min(n_base + j * 32 + 8 * g + 4 * hf, N - 4);
+        const half_t* src = resid + (size_t)rrow[i] * N + n;
         half4_t t;
         asm volatile("global_load_dwordx2 %0, %1, off" : "=v"(t) : "v"(src) : "memory");
         rres[i][j][g] = t;
@@ -355,8 +357,8 @@ __device__ __forceinline__ void request_resid(const half_t* __restrict__ resid, 
 
 // The residual tile of EPI_RESID in accumulator layout (zero outside the matrix).
 template <int MI, int NI>
-__device__ __forceinline__ void load_resid(const half_t* __restrict__ resid, int M, int N, int m_base, int n_base,
-                                           int l32, int hf, half4_t (&rres)[MI][NI][4]) {
+__device__ __forceinline__ void load_resid(const half_t* __restrict__ resid, const int32_t* __restrict__ rows, int M,
+                                           int N, int m_base, int n_base, int l32, int hf, half4_t (&rres)[MI][NI][4]) {
   const half4_t zero = {(half_t)0.f, (half_t)0.f, (half_t)0.f, (half_t)0.f};
 #pragma unroll
   for (int i = 0; i < MI; ++i)
@@ -365,7 +367,9 @@ __device__ __forceinline__ void load_resid(const half_t* __restrict__ resid, int
 #pragma unroll
       for (int g = 0; g < 4; ++g) {
         const int m = m_base + i * 32 + l32, n = n_base + j * 32 + 8 * g + 4 * hf;
-        rres[i][j][g] = (m < M && n < N) ? *reinterpret_cast<const half4_t*>(resid + (size_t)m * N + n) : zero;
+        rres[i][j][g] = (m < M && n < N)
+                            ? *reinterpret_cast<const half4_t*>(resid + (size_t)(rows ? rows[m] : m) * N + n)
+                            : zero;
       }
 }
 
@@ -457,6 +461,17 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_pipe_kernel(
     const int r = (wave * LB + q) * RPI + lane / CPR;
     const int c = (lane % CPR) ^ ((r >> 1) & (CPR - 1));
     gb[q] = W + (size_t)min(n0 + r, N - 1) * K + k_off + c * 8;
+  }
+  // Residual rows of this lane's accumulator rows (EPI_RESID): resolved here, with the operand row indices and
+  // before the first DMA, so that the late residual requests need no dependent index load.
+  int rrow[MI];
+#pragma unroll
+  for (int i = 0; i < MI; ++i) {
+    const int m = min(m0 + wm * WM + i * 32 + l32, M - 1);
+    rrow[i] = (EPI == EPI_RESID && ep.resid_rows) ? ep.resid_rows[m] : m;
+    // collected here: the wait for this load must not end up in the K loop, where the compiler cannot see
+    // the DMA instructions in flight and would wait for all of them
+    if constexpr (EPI == EPI_RESID) asm volatile("" : "+v"(rrow[i]));
   }
   const uint32_t lds_a = lds_addr(sA) + wave * LA * RPI * BK * 2;  // bytes
   const uint32_t lds_b = lds_addr(sB) + wave * LB * RPI * BK * 2;
@@ -577,7 +592,7 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_pipe_kernel(
 #pragma unroll
   for (int i = 0; i < MI; ++i) { mu[i] = 0.f; rstd[i] = 1.f; }
   auto late_requests = [&]() {
-    if constexpr (EPI == EPI_RESID) request_resid<MI, NI>(ep.resid, M, N, m0 + wm * WM, n0 + wn * WN, l32, hf, rres);
+    if constexpr (EPI == EPI_RESID) request_resid<MI, NI>(ep.resid, rrow, N, n0 + wn * WN, hf, rres);
     if constexpr (kStats) request_row_sums<MI>(stat_part, stat_np, M, m0 + wm * WM, l32, hf, psum);
   };
   auto late_collect = [&]() {
@@ -692,7 +707,7 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_simple_kernel(const half_t*
     wait_vmcnt<0>();
     finish_row_sums<1>(stat_part, stat_np, M, m0 + wm * 32, l32, hf, ep.inv_h, ep.eps, psum, mu, rstd);
   }
-  if constexpr (EPI == EPI_RESID) load_resid<1, 1>(ep.resid, M, N, m0 + wm * 32, n0 + wn * 32, l32, hf, rres);
+  if constexpr (EPI == EPI_RESID) load_resid<1, 1>(ep.resid, ep.resid_rows, M, N, m0 + wm * 32, n0 + wn * 32, l32, hf, rres);
   EpiVecs<1> vec;
   load_epi_vecs<1, EPI>(ep, ep.bias, N, n0 + wn * 32, hf, vec);
   store_tile<1, 1, 2, ACT, EPI>(acc, ep, vec, mu, rstd, rres, tn, wn, wm * 32, red, BM, C, M, N, m0 + wm * 32, n0 + wn * 32,
@@ -850,9 +865,14 @@ bt_status gemm_splitk_dispatch(const bt_half* A, const bt_half* W, int M, int N,
   ep.ksplit = ksplit;
   int group_m = (int)(sqrt((double)n_tiles / 8.0) + 0.5);
   group_m = group_m < 1 ? 1 : (group_m > tiles_m ? tiles_m : group_m);
-  gemm_pipe_kernel<BM, BN, 2, 2, NS, BT_ACT_NONE, EPI_PARTIAL, 2><<<dim3((unsigned)(n_tiles * ksplit)), dim3(256), 0, st>>>(
-      reinterpret_cast<const half_t*>(A), reinterpret_cast<const half_t*>(W), nullptr, nullptr, M, N, K, tiles_n, tiles_m,
-      group_m, nullptr, ep);
+  const dim3 grid((unsigned)(n_tiles * ksplit)), block(256);
+  const half_t* a = reinterpret_cast<const half_t*>(A);
+  const half_t* w = reinterpret_cast<const half_t*>(W);
+  // shape class as in launch_pipe: a trace tells the split FFN-down product (deep) from the split projection
+  if (K >= 2 * N)
+    gemm_pipe_kernel<BM, BN, 2, 2, NS, BT_ACT_NONE, EPI_PARTIAL, 2><<<grid, block, 0, st>>>(a, w, nullptr, nullptr, M, N, K, tiles_n, tiles_m, group_m, nullptr, ep);
+  else
+    gemm_pipe_kernel<BM, BN, 2, 2, NS, BT_ACT_NONE, EPI_PARTIAL, 1><<<grid, block, 0, st>>>(a, w, nullptr, nullptr, M, N, K, tiles_n, tiles_m, group_m, nullptr, ep);
   return launch_status();
 }
 

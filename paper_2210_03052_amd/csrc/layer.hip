@@ -29,7 +29,8 @@ bt_status gemm_splitk_dispatch(const bt_half* A, const bt_half* W, int M, int N,
 // slices * M * N of any split gemm_splitk_choice allows: at most 256 tiles of 64 x 64 outputs
 constexpr size_t kSplitKFloats = (size_t)256 * 64 * 64;
 bt_status ln_finalize_dispatch(const bt_half* u, const float2* part, int np, const bt_half* gamma,
-                               const bt_half* beta, float eps, int T, int H, bt_half* y, hipStream_t st);
+                               const bt_half* beta, float eps, int T, int H, bt_half* y, hipStream_t st,
+                               const int32_t* out_idx, int out_rows);
 bt_status fold_vectors_dispatch(const bt_half* W, const bt_half* gamma, const bt_half* beta, const bt_half* bias,
                                 int N, int K, float* c, float* d, hipStream_t st);
 bt_status mha_dispatch(const bt_half* q, const bt_half* k, const bt_half* v, int64_t row_stride, const bt_half* bq,
@@ -156,9 +157,12 @@ static bt_status layer_fwd(const bt_layer* l, const bt_half* x, const int32_t* c
 // Folded stack.  Between layers the activation lives as (u2 = gamma1 (.) z2, part2); inside a layer
 // as (u1 = gamma0 (.) z1, part1).  Each part buffer is rewritten in full by the GEMM that produces it
 // (one slot per row and producing wavefront), after its last reader has run: nothing to clear.
+// io: with in_rows, x is the padded tensor and packed row i is its row in_rows[i] (gathered by the first GEMM's
+// operand load and by the first residual read); with out_idx, y is the padded tensor and the final
+// normalisation scatters its rows there and zero-fills the rest.
 static bt_status stack_fwd_folded(const bt_layer* layers, int n_layers, const float* fold, const bt_half* x,
                                   const int32_t* cu, int B, int T, int max_len, bt_half* y, const Workspace& w,
-                                  hipStream_t st) {
+                                  hipStream_t st, const LayerIo& io = LayerIo()) {
   const int H = layers[0].H, F = layers[0].F;
   const float inv_h = 1.0f / (float)H, eps = layers[0].ln_eps;
   const float scale = 1.0f / sqrtf((float)layers[0].head_dim);
@@ -177,6 +181,7 @@ static bt_status stack_fwd_folded(const bt_layer* layers, int n_layers, const fl
         ep.ln_part = w.part2; ep.ln_np = np2; ep.fold_c = fv; ep.fold_d = fv + 3 * H; ep.inv_h = inv_h; ep.eps = eps;
       } else {
         ep.bias = hp(l->b_qkv);
+        ep.a_rows = io.in_rows;
       }
       if ((s = gemm_dispatch(in, l->w_qkv, T, 3 * H, H, BT_ACT_NONE, prev ? EPI_FOLD : EPI_PLAIN, ep, w.qkv, st,
                              nullptr)) != BT_OK)
@@ -191,6 +196,8 @@ static bt_status stack_fwd_folded(const bt_layer* layers, int n_layers, const fl
       ep.resid = hp(in);
       if (prev) {
         ep.resid_part = w.part2; ep.resid_np = np2; ep.resid_gamma = hp(prev->ln1_g); ep.resid_beta = hp(prev->ln1_b);
+      } else {
+        ep.resid_rows = io.in_rows;
       }
       ep.out_gamma = hp(l->ln0_g); ep.part_out = w.part1;
       if ((s = gemm_dispatch(w.attn, l->w_o, T, H, H, BT_ACT_NONE, EPI_RESID, ep, w.y1, st, &np1)) != BT_OK) return s;
@@ -213,16 +220,18 @@ static bt_status stack_fwd_folded(const bt_layer* layers, int n_layers, const fl
     in = u2;
   }
   const bt_layer* last = &layers[n_layers - 1];
-  return ln_finalize_dispatch(in, w.part2, np2, last->ln1_g, last->ln1_b, eps, T, H, y, st);
+  return ln_finalize_dispatch(in, w.part2, np2, last->ln1_g, last->ln1_b, eps, T, H, y, st, io.out_idx, io.out_rows);
 }
 
-// Whether the folded pipeline is the faster one for T tokens of width H.  Its residual epilogue exists for
-// the small tile shapes only (64 x 128 for the H-wide products); as long as those tiles fit one round of the
-// 256 compute units the two launches saved per layer win, beyond that the small tiles run in several
-// rounds and the plain 7-launch layer with its larger tiles is faster (measured: -3 % at 2 308 tokens of
-// width 768, +19 % at 9 894).
-static bool folded_pays(int T, int H) {
-  return (long long)((T + 63) / 64) * ((H + 127) / 128) <= 256;
+// Whether the folded pipeline is the faster one for T tokens (hidden width H, FFN width F).  Its residual
+// epilogue exists for the small tile shapes only (64 x 128 for the H-wide products); as long as those tiles fit
+// one round of the 256 compute units the two launches saved per layer win, beyond that the small tiles run in
+// several rounds and the plain 7-launch layer with its larger tiles is faster (measured: -2.3 ... -3 % at
+// 2 308 tokens of width 768, +19 % at 9 894).  With so few tokens that the plain layer splits K of its
+// H-wide products, the plain layer wins again (the folded epilogue has no split-K form: +1.5 % at 186 tokens).
+static bool folded_pays(int T, int H, int F) {
+  if ((long long)((T + 63) / 64) * ((H + 127) / 128) > 256) return false;
+  return gemm_splitk_choice(T, H, F) == 1 && gemm_splitk_choice(T, H, H) == 1;
 }
 
 static bt_status check_io(const bt_half* x, const int32_t* cu, int B, int T, int max_len, bt_half* y, void* ws) {
@@ -352,7 +361,7 @@ extern "C" bt_status bt_encoder_fwd(const bt_layer* layers, int n_layers, const 
   const Workspace w = carve(d_ws, T, layers[0].H, layers[0].F);
   if (ws_bytes < w.bytes) return BT_ERR_WORKSPACE;
   hipStream_t st = static_cast<hipStream_t>(stream);
-  if (d_fold && folded_pays(T, layers[0].H))
+  if (d_fold && folded_pays(T, layers[0].H, layers[0].F))
     return stack_fwd_folded(layers, n_layers, d_fold, d_x, d_cu_seqlens, B, T, max_len, d_y, w, st);
   const bt_half* in = d_x;
   for (int i = 0; i < n_layers; ++i) {
@@ -363,13 +372,14 @@ extern "C" bt_status bt_encoder_fwd(const bt_layer* layers, int n_layers, const 
   return BT_OK;
 }
 
-extern "C" bt_status bt_encoder_fwd_padded(const bt_layer* layers, int n_layers, const bt_half* d_x_padded,
-                                           const int32_t* d_token_idx, const int32_t* d_cu_seqlens, int B, int T,
-                                           int S, bt_half* d_y_padded, void* d_ws, size_t ws_bytes,
-                                           bt_stream stream) {
+extern "C" bt_status bt_encoder_fwd_padded(const bt_layer* layers, int n_layers, const float* d_fold,
+                                           const bt_half* d_x_padded, const int32_t* d_token_idx,
+                                           const int32_t* d_cu_seqlens, int B, int T, int S, bt_half* d_y_padded,
+                                           void* d_ws, size_t ws_bytes, bt_stream stream) {
   bt_status s = check_stack(layers, n_layers);
   if (s != BT_OK) return s;
   if (B < 0 || T < 0 || S < 0) return BT_ERR_INVALID_ARG;
+  if (d_fold && (reinterpret_cast<uintptr_t>(d_fold) & 15u)) return BT_ERR_INVALID_ARG;
   if (B == 0 || S == 0) return BT_OK;
   if ((int64_t)T > (int64_t)B * S || (int64_t)B * S >= (int64_t)INT32_MAX) return BT_ERR_INVALID_ARG;
   if (!d_x_padded || !d_y_padded || d_x_padded == d_y_padded || !aligned16(d_x_padded) || !aligned16(d_y_padded))
@@ -382,6 +392,13 @@ extern "C" bt_status bt_encoder_fwd_padded(const bt_layer* layers, int n_layers,
   if (!d_ws || (reinterpret_cast<uintptr_t>(d_ws) & 255u)) return BT_ERR_WORKSPACE;
   const Workspace w = carve(d_ws, T, H, layers[0].F);
   if (ws_bytes < w.bytes) return BT_ERR_WORKSPACE;
+  if (d_fold && folded_pays(T, H, layers[0].F)) {
+    LayerIo io;
+    io.in_rows = d_token_idx;
+    io.out_idx = d_token_idx;
+    io.out_rows = B * S;
+    return stack_fwd_folded(layers, n_layers, d_fold, d_x_padded, d_cu_seqlens, B, T, S, d_y_padded, w, st, io);
+  }
   const bt_half* in = d_x_padded;
   for (int i = 0; i < n_layers; ++i) {
     const bool last = i == n_layers - 1;

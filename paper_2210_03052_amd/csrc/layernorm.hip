@@ -121,10 +121,32 @@ __global__ __launch_bounds__(256) void bias_residual_ln_kernel(
 __global__ __launch_bounds__(256) void ln_finalize_kernel(const half_t* __restrict__ u, const float2* __restrict__ part,
                                                           int np, const half_t* __restrict__ gamma,
                                                           const half_t* __restrict__ beta, float eps, int T, int H,
-                                                          half_t* __restrict__ y) {
+                                                          half_t* __restrict__ y, const int32_t* __restrict__ out_idx,
+                                                          int out_rows) {
+  // out_idx: y is the padded tensor [out_rows, H]; this wave owns padded row r, which is packed row `lo` if
+  // out_idx[lo] == r and a zero row otherwise (unpack fused into the store, as in bias_residual_ln_kernel).
   const int lane = threadIdx.x & 63;
-  const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
-  if (row >= T) return;
+  int row = blockIdx.x * 4 + (threadIdx.x >> 6);
+  size_t obase;
+  if (out_idx) {
+    const int r = row;
+    if (r >= out_rows) return;
+    int lo = 0, hi = T;
+    while (lo < hi) {
+      const int mid = (lo + hi) >> 1;
+      if (out_idx[mid] < r) lo = mid + 1; else hi = mid;
+    }
+    obase = (size_t)r * H;
+    if (!(lo < T && out_idx[lo] == r)) {
+      const half8_t z = {(half_t)0.f, (half_t)0.f, (half_t)0.f, (half_t)0.f, (half_t)0.f, (half_t)0.f, (half_t)0.f, (half_t)0.f};
+      for (int c = lane; c < (H >> 3); c += kWave) *reinterpret_cast<half8_t*>(y + obase + c * 8) = z;
+      return;
+    }
+    row = lo;
+  } else {
+    if (row >= T) return;
+    obase = (size_t)row * H;
+  }
   const float inv_h = 1.0f / (float)H;
   const int half_np = (np + 1) >> 1;
   float a0 = 0.f, b0 = 0.f, a1 = 0.f, b1 = 0.f;
@@ -146,7 +168,7 @@ __global__ __launch_bounds__(256) void ln_finalize_kernel(const half_t* __restri
     half8_t o;
 #pragma unroll
     for (int e = 0; e < 8; ++e) o[e] = (half_t)(rstd * ((float)a[e] - mu * (float)g[e]) + (float)b[e]);
-    *reinterpret_cast<half8_t*>(y + base + c * 8) = o;
+    *reinterpret_cast<half8_t*>(y + obase + c * 8) = o;
   }
 }
 
@@ -180,11 +202,11 @@ __global__ __launch_bounds__(256) void fold_vectors_kernel(const half_t* __restr
 }
 
 bt_status ln_finalize_dispatch(const bt_half* u, const float2* part, int np, const bt_half* gamma,
-                               const bt_half* beta, float eps, int T, int H, bt_half* y, hipStream_t st) {
-  ln_finalize_kernel<<<(T + 3) / 4, 256, 0, st>>>(reinterpret_cast<const half_t*>(u), part, np,
-                                                  reinterpret_cast<const half_t*>(gamma),
-                                                  reinterpret_cast<const half_t*>(beta), eps, T, H,
-                                                  reinterpret_cast<half_t*>(y));
+                               const bt_half* beta, float eps, int T, int H, bt_half* y, hipStream_t st,
+                               const int32_t* out_idx, int out_rows) {
+  ln_finalize_kernel<<<((out_idx ? out_rows : T) + 3) / 4, 256, 0, st>>>(
+      reinterpret_cast<const half_t*>(u), part, np, reinterpret_cast<const half_t*>(gamma),
+      reinterpret_cast<const half_t*>(beta), eps, T, H, reinterpret_cast<half_t*>(y), out_idx, out_rows);
   return launch_status();
 }
 

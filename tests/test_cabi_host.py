@@ -115,11 +115,13 @@ def test_layer_checks(lib):
     assert lib.bt_encoder_fwd(arr, 2, None, x, cu, 4, 100, 64, y, ws, n, None) == 1  # mixed shapes
     assert lib.bt_encoder_fwd(arr, 0, None, x, cu, 4, 100, 64, y, ws, n, None) == 1
     pad = lambda T=100, x_=x, y_=y, ws_=ws, nb=n: lib.bt_encoder_fwd_padded(
-        (bt.bt_layer * 1)(good), 1, x_, cu, cu, 4, T, 64, y_, ws_, nb, None)
+        (bt.bt_layer * 1)(good), 1, None, x_, cu, cu, 4, T, 64, y_, ws_, nb, None)
     assert pad(T=4 * 64 + 1) == 1                              # more tokens than B*S
     assert pad(y_=x) == 1                                      # in-place not allowed
     assert pad(x_=None) == 1
     assert pad(ws_=None) == 3 and pad(nb=n - 1) == 3
+    assert lib.bt_encoder_fwd_padded((bt.bt_layer * 1)(good), 1, ctypes.c_void_p(4), x, cu, cu, 4, 100, 64, y, ws, n,
+                                     None) == 1                 # misaligned fold vectors
     same = (bt.bt_layer * 2)(good, good)
     fb = lib.bt_encoder_fold_bytes(same, 2)
     assert fb == 2 * (6 * 768 + 2 * 3072) * 4

@@ -534,11 +534,13 @@ def test_stack_bert_large_b32_s512_all_sequences(bt, folded):
     _full_stack(bt, "bert_large_b32_s512", TOL_12, TOL_24, folded)
 
 
+@pytest.mark.parametrize("folded", [False, True])
 @pytest.mark.parametrize("name,n_layers,stress", [("layer_b4_s64", 1, True), ("layer_b4_s64", 2, True),
                                                   ("bert_base_b16_s256", 3, False), ("bert_large_b32_s512", 2, True)])
-def test_encoder_fwd_padded_equals_pack_fwd_unpack(bt, name, n_layers, stress):
-    """Pack fused into the first GEMM / residual read and unpack fused into the last LayerNorm: the
-    result is the same bits as the three separate calls, pads are zero, the input is untouched."""
+def test_encoder_fwd_padded_equals_pack_fwd_unpack(bt, name, n_layers, stress, folded):
+    """Pack fused into the first GEMM / residual read and unpack fused into the last LayerNorm (or, with fold
+    vectors, into the final normalisation): the result is the same bits as the three separate calls with the
+    same fold vectors, pads are zero, the input is untouched."""
     import torch
     wl = I.WORKLOADS[name]
     L = I.draw_lengths(wl)
@@ -547,11 +549,12 @@ def test_encoder_fwd_padded_equals_pack_fwd_unpack(bt, name, n_layers, stress):
     xpad = dev(I.pad_rows(I.make_hidden_packed(wl, T), L, wl.S, fill=7.0))   # junk in the pads must not matter
     keep = xpad.clone()
     layers = [bt.Layer(I.make_layer_params(wl, i, stress)) for i in range(n_layers)]
+    fold = bt.encoder_prepare(layers) if folded else None
     cu, tok, t = bt.build_offsets(lengths=dev(L), S=wl.S)
     assert t == T
-    want = bt.unpack(bt.encoder_fwd(layers, bt.pack(xpad, tok), cu, wl.S), tok, wl.B, wl.S)
+    want = bt.unpack(bt.encoder_fwd(layers, bt.pack(xpad, tok), cu, wl.S, fold=fold), tok, wl.B, wl.S)
     got = torch.full_like(xpad, 3.0)
-    bt.encoder_fwd_padded(layers, xpad, tok, cu, out=got)
+    bt.encoder_fwd_padded(layers, xpad, tok, cu, out=got, fold=fold)
     assert torch.equal(got, want) and torch.equal(xpad, keep)
     mask = O.lengths_to_mask(L, wl.S).astype(bool)
     assert float(got[torch.from_numpy(~mask).to("cuda:0")].abs().sum()) == 0.0
@@ -668,3 +671,30 @@ def test_folded_stack_vs_oracle(bt, name, n_layers, stress):
     b = host(bt.encoder_fwd(layers, dev(x), cu, wl.S, fold=fold, ws=ws)).astype(np.float64)
     assert np.array_equal(a, b) and np.array_equal(a, got)
     assert max(np.abs(b[cuh[i]: cuh[i + 1]] - ref[i]).max() for i in seqs) <= tol
+
+
+def test_folded_stack_large_shape_in_its_token_range(bt):
+    """Hidden 1024 / FFN 4096 / 16 heads with 1 455 tokens: inside the range where fold vectors select the folded
+    pipeline at this width (enough tokens not to split K, few enough for one round of 64 x 128 tiles).  Every
+    sequence against the oracle after 3 layers, the plain pipeline beside it, and the padded entry point with
+    the same fold vectors bit for bit."""
+    import torch
+    wl = I.WORKLOADS["bert_large_b32_s512"]
+    L = I.uniform_lengths(8, 64, 300, seed=77)
+    T = int(L.sum())
+    assert 700 < T <= 2048
+    x = I.make_hidden_packed(wl, T)
+    n_layers = 3
+    layers = [bt.Layer(I.make_layer_params(wl, i, True)) for i in range(n_layers)]
+    fold = bt.encoder_prepare(layers)
+    cu, tok, t = bt.build_offsets(lengths=dev(L), S=300)
+    assert t == T
+    got = host(bt.encoder_fwd(layers, dev(x), cu, 300, fold=fold)).astype(np.float64)
+    plain = host(bt.encoder_fwd(layers, dev(x), cu, 300)).astype(np.float64)
+    assert not np.array_equal(got, plain)                      # the folded kernels did run
+    ref = _oracle_each(wl, L, x, oracle_layers(wl, n_layers, True), [n_layers])[n_layers]
+    assert np.abs(got - ref).max() <= 3 * TOL_LAYER and np.abs(plain - ref).max() <= 3 * TOL_LAYER
+    xpad = dev(I.pad_rows(x, L, 300, fill=5.0))
+    out = bt.encoder_fwd_padded(layers, xpad, tok, cu, fold=fold)
+    want = bt.unpack(dev(got.astype(np.float16)), tok, 8, 300)
+    assert torch.equal(out, want)
