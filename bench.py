@@ -510,127 +510,15 @@ def main():
         bt.encoder_fwd_padded(layers, x_padded, tok, cu, out=y_padded, ws=ws, fold=fold)
 
     separate = args.separate_pack_unpack
-    step = (lambda mark: step_separate(mark, y_padded)) if separate else step_fused
-    step_name = "build_offsets+pack+encoder_fwd+unpack" if separate else "build_offsets+encoder_fwd_padded"
-    dt, per = timed_steps(torch, step, args.steps, args.warmup)
-    stats = step_stats(wl.B, dt, per)
-    flops_step = nl * (24.0 * T * H * H + 4.0 * sum_l2 * H)
-
-    out = {
-        "metric": "sequences/s BERT-base fp16 varlen (b16, max256)" if args.workload == "bert_base_b16_s256"
-                  else f"sequences/s {args.workload} fp16 varlen",
-        "value": stats["value"], "unit": "sequences/s", "n_gpus": 1, "steps": args.steps,
-        "warmup": args.warmup, "ms_per_step": stats["ms_per_step"], "ms_per_step_median": stats["ms_per_step_median"],
-        "ms_per_step_min": stats["ms_per_step_min"], "higher_is_better": True, "scaling": "weak",
-        "vs_baseline": None, "dtype": "f16", "data": "synthetic",
-        "config": {"workload": args.workload, "batch": wl.B, "max_seq": wl.S, "hidden": H, "heads": wl.heads,
-                   "ffn": F, "layers": nl, "length_law": wl.length_law, "valid_tokens": T, "sum_len_sq": sum_l2,
-                   "step": step_name, "layernorm_fold_vectors_given": fold is not None},
-        "useful_tflops_per_s": round(flops_step / (stats["ms_per_step"] * 1e-3) / 1e12, 2),
-    }
-
-    # ---------------- the same step with the fold vectors handed over (extra point; see --fold)
-    if not separate and fold is None:
-        y_padded_f = torch.empty_like(y_padded)
-
-        def step_fold(mark):
-            cu, tok, t = bt.build_offsets(lengths=lengths_d, S=wl.S)
-            mark()
-            bt.encoder_fwd_padded(layers, x_padded, tok, cu, out=y_padded_f, ws=ws, fold=fold_vectors)
-
-        dtf, perf_ = timed_steps(torch, step_fold, args.steps, max(args.warmup // 2, 2))
-        out["layernorm_fold_vectors"] = dict(
-            step_stats(wl.B, dtf, perf_), unit="sequences/s", step="build_offsets+encoder_fwd_padded(d_fold)",
-            max_abs_diff_to_value_path=round(float((y_padded_f.float() - y_padded.float()).abs().max()), 5),
-            note="LayerNorms folded into the GEMM epilogues where the library finds that faster (a few hundred to "
-                 "about 2 700 tokens at hidden 768), else the same kernels as `value`")
-
-    # ---------------- the same work with pack / unpack as kernels of their own (extra point; same bits)
-    if not separate:
-        dts, pers = timed_steps(torch, step_separate, args.steps, max(args.warmup // 2, 2))
-        out["separate_pack_unpack"] = dict(step_stats(wl.B, dts, pers), unit="sequences/s",
-                                           step="build_offsets+pack+encoder_fwd+unpack",
-                                           outputs_equal=bool(torch.equal(y_padded_sep, y_padded)))
-
-    # ---------------- the same step with the forward replayed from a HIP graph (extra point)
-    # One graph launch instead of ~85 kernel launches per step: if this is faster than `value`, the host of
-    # this box did not keep ahead of the GPU in the eager loop; on a quiet host the two agree.
-    if not separate:
-        y_padded3 = torch.empty_like(y_padded)
-        cu_g, tok_g, t_g = bt.build_offsets(lengths=lengths_d, S=wl.S)
-
-        def body():
-            bt.encoder_fwd_padded(layers, x_padded, tok_g, cu_g, out=y_padded3, ws=ws, fold=fold)
-
-        side = torch.cuda.Stream()
-        side.wait_stream(torch.cuda.current_stream())
-        with torch.cuda.stream(side):
-            body()
-        torch.cuda.current_stream().wait_stream(side)
-        torch.cuda.synchronize()
-        graph = torch.cuda.CUDAGraph()
-        with torch.cuda.graph(graph):
-            body()
-
-        def step_graph(mark):
-            bt.build_offsets(lengths=lengths_d, S=wl.S)      # same offsets every step here; still computed and waited for
-            mark()
-            graph.replay()
-
-        dtg, perg = timed_steps(torch, step_graph, args.steps, max(args.warmup // 2, 2))
-        out["graph_replay"] = dict(step_stats(wl.B, dtg, perg), unit="sequences/s",
-                                   step="build_offsets + one HIP graph of encoder_fwd_padded",
-                                   outputs_equal=bool(torch.equal(y_padded3, y_padded)))
-
-    # ---------------- throughput with two batches in flight (extra point, not `value`)
-    # One batch at a time leaves the GPU idle at every kernel boundary (~2.5 us per dependent launch) and
-    # while the host waits for the token count in build_offsets.  A server keeps a second batch in flight
-    # on another stream, which fills those holes; each batch has its own buffers and its own host thread,
-    # the library keeps no state between calls.  Same steps, same kernels, same results.
-    if not args.no_pipelined and not separate:
-        import threading
-
-        class Batch:
-            def __init__(self):
-                self.stream = torch.cuda.Stream()
-                self.x_padded = x_padded.clone()
-                self.lengths_d = lengths_d.clone()
-                self.ws = torch.empty_like(ws)
-                self.y_padded = torch.empty_like(y_padded)
-
-            def run(self, n):
-                torch.cuda.set_device(0)
-                with torch.cuda.stream(self.stream):
-                    for _ in range(n):
-                        cu, tok, t = bt.build_offsets(lengths=self.lengths_d, S=wl.S)
-                        bt.encoder_fwd_padded(layers, self.x_padded, tok, cu, out=self.y_padded, ws=self.ws, fold=fold)
-
-        batches = [Batch(), Batch()]
-        per_b = max(args.steps // 2, 1)
-
-        def both(n):
-            th = [threading.Thread(target=b.run, args=(n,)) for b in batches]
-            for t_ in th:
-                t_.start()
-            for t_ in th:
-                t_.join()
-            torch.cuda.synchronize()
-
-        both(max(args.warmup // 2, 2))
-        t0 = time.perf_counter()
-        both(per_b)
-        dt2 = time.perf_counter() - t0
-        same = bool(torch.equal(batches[0].y_padded, y_padded) and torch.equal(batches[1].y_padded, y_padded))
-        out["two_batches_in_flight"] = {"value": round(wl.B * 2 * per_b / dt2, 1), "unit": "sequences/s",
-                                        "steps": 2 * per_b, "ms_per_step": round(dt2 * 1e3 / (2 * per_b), 4),
-                                        "streams": 2, "outputs_equal_single_stream": same}
-        del batches
 
     # ---------------- per-kernel timing (HIP events on the launch stream)
     # Each kernel of the layer is launched `kernel_iters` times back to back through the C ABI (raw
     # ctypes calls with prebuilt arguments, ~1 us of host time each) between two HIP events recorded
-    # on the stream the kernels run on; the average includes the inter-launch gap.
-    if not args.no_kernels:
+    # on the stream the kernels run on; the average includes the inter-launch gap.  This pass runs BEFORE the
+    # step timing: a few thousand launches also bring the device to its steady clocks, which the W warm-up
+    # steps of a short run (W = 5: 4 ms of work) do not.
+    def kernel_leg():
+        out = {}
         import ctypes as C
         lib = bt.load_library()
         cu, tok, _ = bt.build_offsets(lengths=lengths_d, S=wl.S)
@@ -754,6 +642,127 @@ def main():
                 "pack": {"us": round(us_pk, 1), "GBps": round(4.0 * Ts * H / us_pk / 1e3, 1),
                          "frac_hbm_peak": round(4.0 * Ts * H / us_pk / 1e3 / PEAK_HBM, 4)}}
             del xs, rs, ys
+
+
+        return out
+
+    kernel_results = {} if args.no_kernels else kernel_leg()
+    step = (lambda mark: step_separate(mark, y_padded)) if separate else step_fused
+    step_name = "build_offsets+pack+encoder_fwd+unpack" if separate else "build_offsets+encoder_fwd_padded"
+    dt, per = timed_steps(torch, step, args.steps, args.warmup)
+    stats = step_stats(wl.B, dt, per)
+    flops_step = nl * (24.0 * T * H * H + 4.0 * sum_l2 * H)
+
+    out = {
+        "metric": "sequences/s BERT-base fp16 varlen (b16, max256)" if args.workload == "bert_base_b16_s256"
+                  else f"sequences/s {args.workload} fp16 varlen",
+        "value": stats["value"], "unit": "sequences/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": stats["ms_per_step"], "ms_per_step_median": stats["ms_per_step_median"],
+        "ms_per_step_min": stats["ms_per_step_min"], "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f16", "data": "synthetic",
+        "config": {"workload": args.workload, "batch": wl.B, "max_seq": wl.S, "hidden": H, "heads": wl.heads,
+                   "ffn": F, "layers": nl, "length_law": wl.length_law, "valid_tokens": T, "sum_len_sq": sum_l2,
+                   "step": step_name, "layernorm_fold_vectors_given": fold is not None},
+        "useful_tflops_per_s": round(flops_step / (stats["ms_per_step"] * 1e-3) / 1e12, 2),
+    }
+    out.update(kernel_results)
+
+    # ---------------- the same step with the fold vectors handed over (extra point; see --fold)
+    if not separate and fold is None:
+        y_padded_f = torch.empty_like(y_padded)
+
+        def step_fold(mark):
+            cu, tok, t = bt.build_offsets(lengths=lengths_d, S=wl.S)
+            mark()
+            bt.encoder_fwd_padded(layers, x_padded, tok, cu, out=y_padded_f, ws=ws, fold=fold_vectors)
+
+        dtf, perf_ = timed_steps(torch, step_fold, args.steps, max(args.warmup // 2, 2))
+        out["layernorm_fold_vectors"] = dict(
+            step_stats(wl.B, dtf, perf_), unit="sequences/s", step="build_offsets+encoder_fwd_padded(d_fold)",
+            max_abs_diff_to_value_path=round(float((y_padded_f.float() - y_padded.float()).abs().max()), 5),
+            note="LayerNorms folded into the GEMM epilogues where the library finds that faster (a few hundred to "
+                 "about 2 700 tokens at hidden 768), else the same kernels as `value`")
+
+    # ---------------- the same work with pack / unpack as kernels of their own (extra point; same bits)
+    if not separate:
+        dts, pers = timed_steps(torch, step_separate, args.steps, max(args.warmup // 2, 2))
+        out["separate_pack_unpack"] = dict(step_stats(wl.B, dts, pers), unit="sequences/s",
+                                           step="build_offsets+pack+encoder_fwd+unpack",
+                                           outputs_equal=bool(torch.equal(y_padded_sep, y_padded)))
+
+    # ---------------- the same step with the forward replayed from a HIP graph (extra point)
+    # One graph launch instead of ~85 kernel launches per step: if this is faster than `value`, the host of
+    # this box did not keep ahead of the GPU in the eager loop; on a quiet host the two agree.
+    if not separate:
+        y_padded3 = torch.empty_like(y_padded)
+        cu_g, tok_g, t_g = bt.build_offsets(lengths=lengths_d, S=wl.S)
+
+        def body():
+            bt.encoder_fwd_padded(layers, x_padded, tok_g, cu_g, out=y_padded3, ws=ws, fold=fold)
+
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            body()
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            body()
+
+        def step_graph(mark):
+            bt.build_offsets(lengths=lengths_d, S=wl.S)      # same offsets every step here; still computed and waited for
+            mark()
+            graph.replay()
+
+        dtg, perg = timed_steps(torch, step_graph, args.steps, max(args.warmup // 2, 2))
+        out["graph_replay"] = dict(step_stats(wl.B, dtg, perg), unit="sequences/s",
+                                   step="build_offsets + one HIP graph of encoder_fwd_padded",
+                                   outputs_equal=bool(torch.equal(y_padded3, y_padded)))
+
+    # ---------------- throughput with two batches in flight (extra point, not `value`)
+    # One batch at a time leaves the GPU idle at every kernel boundary (~2.5 us per dependent launch) and
+    # while the host waits for the token count in build_offsets.  A server keeps a second batch in flight
+    # on another stream, which fills those holes; each batch has its own buffers and its own host thread,
+    # the library keeps no state between calls.  Same steps, same kernels, same results.
+    if not args.no_pipelined and not separate:
+        import threading
+
+        class Batch:
+            def __init__(self):
+                self.stream = torch.cuda.Stream()
+                self.x_padded = x_padded.clone()
+                self.lengths_d = lengths_d.clone()
+                self.ws = torch.empty_like(ws)
+                self.y_padded = torch.empty_like(y_padded)
+
+            def run(self, n):
+                torch.cuda.set_device(0)
+                with torch.cuda.stream(self.stream):
+                    for _ in range(n):
+                        cu, tok, t = bt.build_offsets(lengths=self.lengths_d, S=wl.S)
+                        bt.encoder_fwd_padded(layers, self.x_padded, tok, cu, out=self.y_padded, ws=self.ws, fold=fold)
+
+        batches = [Batch(), Batch()]
+        per_b = max(args.steps // 2, 1)
+
+        def both(n):
+            th = [threading.Thread(target=b.run, args=(n,)) for b in batches]
+            for t_ in th:
+                t_.start()
+            for t_ in th:
+                t_.join()
+            torch.cuda.synchronize()
+
+        both(max(args.warmup // 2, 2))
+        t0 = time.perf_counter()
+        both(per_b)
+        dt2 = time.perf_counter() - t0
+        same = bool(torch.equal(batches[0].y_padded, y_padded) and torch.equal(batches[1].y_padded, y_padded))
+        out["two_batches_in_flight"] = {"value": round(wl.B * 2 * per_b / dt2, 1), "unit": "sequences/s",
+                                        "steps": 2 * per_b, "ms_per_step": round(dt2 * 1e3 / (2 * per_b), 4),
+                                        "streams": 2, "outputs_equal_single_stream": same}
+        del batches
 
     if args.peaks:
         mp = measure_peaks(torch)
