@@ -319,6 +319,15 @@ def test_varlen_mha_long_ragged_tall_tiles(bt):
     assert _mha_case(bt, lengths, 12, seed=77) <= 4e-3
 
 
+def test_varlen_mha_long_sequences_many_heads(bt):
+    """Long sequences with all heads (the tall-tile kernel at full occupancy): lengths on, just under and just
+    over its 128-row query tiles and 64-key tiles, the maximum length, and single-tile sequences in between."""
+    lengths = [2048, 1500, 300, 257, 1024, 4096, 65, 511, 256, 129]
+    assert sum(lengths) >= 256 * len(lengths)
+    assert _mha_case(bt, lengths, 12, seed=91) <= 4e-3
+    assert _mha_case(bt, [700, 1023, 641, 1, 3000], 16, seed=92, with_bias=True) <= 4e-3
+
+
 def test_varlen_mha_maximum_length(bt):
     """The longest sequence the offsets accept (4096), one token short of it, and a short neighbour; two
     heads (the oracle builds a 4096 x 4096 score matrix per head)."""
