@@ -264,10 +264,12 @@ bt_status bt_encoder_prepare(const bt_layer* layers, int n_layers, float* d_fold
  * pipeline: while ceil(T/64) * ceil(H/128) <= 256 (up to about 2 700 tokens at H = 768) and there are
  * enough tokens that the unfolded layer would not split K (more than about 600 at H = 768); outside that
  * range it runs the unfolded layers.  Same function either way.  The folded results differ from the
- * unfolded ones by fp16 rounding (u = gamma (.) z is stored instead of LN(z)) and by how the variance is
- * formed: from the row sums of z and z^2 in fp32 (E[z^2] - mean^2, clamped at 0), which loses accuracy
- * when a row's |mean| exceeds its standard deviation by more than about 100x -- post-LN BERT rows have
- * |mean| << sigma (residual of LayerNorm outputs); for other data leave d_fold NULL.  Row statistics travel as
+ * unfolded ones in two ways: u = gamma (.) z is stored in fp16 instead of LN(z), so every stored value carries
+ * a rounding error of 2^-11 |u| that the normalisation then divides by the row's standard deviation; and the
+ * variance is formed from the row sums of z and z^2 in fp32 (E[z^2] - mean^2, clamped at 0).  Both are
+ * harmless while a row's |mean| stays within about 10 standard deviations -- post-LN BERT rows have
+ * |mean| << sigma (a residual of LayerNorm outputs) -- and lose accuracy beyond; for such data leave d_fold
+ * NULL.  Row statistics travel as
  * per-tile partial sums that are added in a fixed order: bit-reproducible, like the unfolded path.
  */
 bt_status bt_encoder_fwd(const bt_layer* layers, int n_layers, const float* d_fold, const bt_half* d_x,

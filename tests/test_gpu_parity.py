@@ -707,3 +707,24 @@ def test_folded_stack_large_shape_in_its_token_range(bt):
     out = bt.encoder_fwd_padded(layers, xpad, tok, cu, fold=fold)
     want = bt.unpack(dev(got.astype(np.float16)), tok, 8, 300)
     assert torch.equal(out, want)
+
+
+def test_folded_stack_rows_with_a_large_common_offset(bt):
+    """The folded pipeline stores the un-normalised u = gamma (.) z in fp16 and forms the variance as
+    E[z^2] - mean^2 in fp32 from partial row sums.  Rows whose mean is 8 standard deviations away from zero
+    (hidden states N(8, 1): far outside what a post-LN encoder produces, at the edge of the documented range)
+    must still match the oracle within the bound of the plain pipeline."""
+    wl = I.WORKLOADS["bert_base_b16_s256"]
+    L = I.uniform_lengths(8, 100, 200, seed=5)
+    T = int(L.sum())
+    assert 600 < T <= 2700                                      # inside the folded pipeline's token range
+    x = (I.make_hidden_packed(wl, T).astype(np.float32) + 8.0).astype(np.float16)
+    layers = [bt.Layer(I.make_layer_params(wl, i, True)) for i in range(2)]
+    fold = bt.encoder_prepare(layers)
+    cu, tok, t = bt.build_offsets(lengths=dev(L), S=200)
+    got = host(bt.encoder_fwd(layers, dev(x), cu, 200, fold=fold)).astype(np.float64)
+    plain = host(bt.encoder_fwd(layers, dev(x), cu, 200)).astype(np.float64)
+    assert not np.array_equal(got, plain)
+    ref = _oracle_each(wl, L, x, oracle_layers(wl, 2, True), [2])[2]
+    assert np.abs(plain - ref).max() <= 2 * TOL_LAYER
+    assert np.abs(got - ref).max() <= 2 * TOL_LAYER
