@@ -470,6 +470,13 @@ def test_stack_bert_base_b16_s256(bt):
     ref, cuh = _oracle_on(wl, L, x, ow, seqs)
     err = max(np.abs(full[cuh[b]: cuh[b + 1]].astype(np.float64) - ref[b]).max() for b in seqs)
     assert err <= TOL_12, err
+    # the step bench.py times: offsets, then the stack on padded tensors (pack / unpack inside the first / last
+    # kernels), all 12 layers -- against the oracle on every sequence, pads zero
+    _, tok, _ = bt.build_offsets(lengths=dev(L), S=wl.S)
+    ypad = host(bt.encoder_fwd_padded(layers, dev(I.pad_rows(x, L, wl.S)), tok, cu)).astype(np.float64)
+    for b in seqs:
+        assert np.abs(ypad[b, : L[b]] - ref[b]).max() <= TOL_12
+        assert not ypad[b, L[b]:].any()
 
 
 _ORACLE_CACHE = {}
