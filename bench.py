@@ -7,8 +7,10 @@ A step is one pass of the whole hot path over one synthetic batch that is
 already resident in HBM: bt_build_offsets (prefix sum; its token count is waited
 for on the host) -> bt_encoder_fwd_padded (all layers; the pack is fused into
 the first GEMM's operand load and the first residual read, the unpack into the
-last LayerNorm's store).  Prints ONE JSON line: sequences/s (whole job; mean over
-the timed steps, with the median and the minimum step beside it), plus
+last LayerNorm's store).  Before the W warm-up steps the step is repeated for about
+half a second, untimed, so that the device clocks have settled (--settle).  Prints ONE
+JSON line: sequences/s (whole job; mean over the timed steps, with the median and the
+minimum step beside it), plus
   "roofline"     the dominant kernel's achieved rate against MI355X's published
                  peak, from HIP-event timing of that kernel in this process
                  (--peaks adds the rates this GPU sustains in an MFMA-only loop
@@ -71,6 +73,8 @@ def parse():
                          "single-layer batch-1 points of Table III, plus fused against separate element-wise launches "
                          "(LayerNorm, GELU) at the headline shape; prints one JSON line")
     ap.add_argument("--calibrate-copy", action="store_true", help="also run one 1 GiB device copy (counter scaling)")
+    ap.add_argument("--settle", type=float, default=0.5,
+                    help="seconds of untimed steps before the warm-up steps, to let the device clocks settle (0 = none)")
     ap.add_argument("--peaks", action="store_true",
                     help="also measure what this GPU sustains in an MFMA-only fp16 loop and in a read-only stream, and "
                          "report the roofline against those measured rates as well as the published ones")
@@ -409,6 +413,11 @@ def bench_mha_alone(args, torch, bt, I, wl):
                                    C.c_float(wl.head_dim ** -0.5), C.c_void_p(o.data_ptr()), None, 0, st)
     if fn() != 0:
         raise RuntimeError("bt_varlen_mha failed")
+    t_settle = time.perf_counter()
+    while time.perf_counter() - t_settle < args.settle:     # let the device clocks settle (see main)
+        for _ in range(100):
+            fn()
+        torch.cuda.synchronize()
     for _ in range(args.warmup):
         fn()
     torch.cuda.synchronize()
@@ -514,9 +523,7 @@ def main():
     # ---------------- per-kernel timing (HIP events on the launch stream)
     # Each kernel of the layer is launched `kernel_iters` times back to back through the C ABI (raw
     # ctypes calls with prebuilt arguments, ~1 us of host time each) between two HIP events recorded
-    # on the stream the kernels run on; the average includes the inter-launch gap.  This pass runs BEFORE the
-    # step timing: a few thousand launches also bring the device to its steady clocks, which the W warm-up
-    # steps of a short run (W = 5: 4 ms of work) do not.
+    # on the stream the kernels run on; the average includes the inter-launch gap.  Runs after the step timing.
     def kernel_leg():
         out = {}
         import ctypes as C
@@ -646,9 +653,18 @@ def main():
 
         return out
 
-    kernel_results = {} if args.no_kernels else kernel_leg()
     step = (lambda mark: step_separate(mark, y_padded)) if separate else step_fused
     step_name = "build_offsets+pack+encoder_fwd+unpack" if separate else "build_offsets+encoder_fwd_padded"
+    # Device warm-up, before the W warm-up steps and outside every timed region: the GPU's power management takes
+    # tens of milliseconds of sustained load to settle its clocks (20 timed steps right after 5 warm-up steps read
+    # 5 % slower than the same steps later in the process), so the step is repeated for about `--settle` seconds
+    # first.  It changes no result, only when the clock starts.
+    n_settle = 0
+    t_settle = time.perf_counter()
+    while time.perf_counter() - t_settle < args.settle:
+        step(lambda: None)
+        n_settle += 1
+    torch.cuda.synchronize()
     dt, per = timed_steps(torch, step, args.steps, args.warmup)
     stats = step_stats(wl.B, dt, per)
     flops_step = nl * (24.0 * T * H * H + 4.0 * sum_l2 * H)
@@ -662,10 +678,10 @@ def main():
         "vs_baseline": None, "dtype": "f16", "data": "synthetic",
         "config": {"workload": args.workload, "batch": wl.B, "max_seq": wl.S, "hidden": H, "heads": wl.heads,
                    "ffn": F, "layers": nl, "length_law": wl.length_law, "valid_tokens": T, "sum_len_sq": sum_l2,
-                   "step": step_name, "layernorm_fold_vectors_given": fold is not None},
+                   "step": step_name, "layernorm_fold_vectors_given": fold is not None,
+                   "device_settle_steps_before_warmup": n_settle},
         "useful_tflops_per_s": round(flops_step / (stats["ms_per_step"] * 1e-3) / 1e12, 2),
     }
-    out.update(kernel_results)
 
     # ---------------- the same step with the fold vectors handed over (extra point; see --fold)
     if not separate and fold is None:
@@ -763,6 +779,9 @@ def main():
                                         "steps": 2 * per_b, "ms_per_step": round(dt2 * 1e3 / (2 * per_b), 4),
                                         "streams": 2, "outputs_equal_single_stream": same}
         del batches
+
+    if not args.no_kernels:
+        out.update(kernel_leg())
 
     if args.peaks:
         mp = measure_peaks(torch)
