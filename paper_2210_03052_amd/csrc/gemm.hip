@@ -104,14 +104,16 @@ __device__ __forceinline__ void static_for(F&& f) {
 // issued in the epilogue would sit fully exposed at the end of every tile.  Unused members are dead code.
 template <int NI>
 struct EpiVecs {
-  half4_t bias[NI][4];             // PLAIN / RESID
+  half4_t bias[NI][4];             // PLAIN / RESID (accumulator layout: this lane's 4*NI groups of 4 columns)
   float4_t fc[NI][4], fd[NI][4];   // FOLD: W gamma, W beta + bias
-  half4_t og[NI][4], rg[NI][4], rb[NI][4];  // RESID: output gamma; gamma / beta of a folded residual
+  // RESID, in the layout of the row-contiguous store pass (this lane's 8 consecutive columns):
+  half8_t og8, rg8, rb8;           // output gamma; gamma / beta of a folded residual
 };
 
 template <int NI, int EPI>
 __device__ __forceinline__ void load_epi_vecs(const GemmEpi& ep, const half_t* bias /* = ep.bias */, int N,
-                                              int n_base, int hf, EpiVecs<NI>& v) {
+                                              int n_base, int lane, EpiVecs<NI>& v) {
+  const int hf = lane >> 5;
   const half4_t zero = {(half_t)0.f, (half_t)0.f, (half_t)0.f, (half_t)0.f};
 #pragma unroll
   for (int j = 0; j < NI; ++j)
@@ -124,20 +126,30 @@ __device__ __forceinline__ void load_epi_vecs(const GemmEpi& ep, const half_t* b
       } else {
         v.bias[j][g] = bias ? *reinterpret_cast<const half4_t*>(bias + nc) : zero;
       }
-      if constexpr (EPI == EPI_RESID) {
-        v.og[j][g] = *reinterpret_cast<const half4_t*>(ep.out_gamma + nc);
-        if (ep.resid_part) {
-          v.rg[j][g] = *reinterpret_cast<const half4_t*>(ep.resid_gamma + nc);
-          v.rb[j][g] = *reinterpret_cast<const half4_t*>(ep.resid_beta + nc);
-        }
-      }
     }
+  if constexpr (EPI == EPI_RESID) {
+    constexpr int LPR = NI * 4;  // lanes per row of the store pass
+    const int nc = min(n_base + (lane % LPR) * 8, N - 8);
+    v.og8 = *reinterpret_cast<const half8_t*>(ep.out_gamma + nc);
+    if (ep.resid_part) {
+      v.rg8 = *reinterpret_cast<const half8_t*>(ep.resid_gamma + nc);
+      v.rb8 = *reinterpret_cast<const half8_t*>(ep.resid_beta + nc);
+    }
+  }
 }
+
+// Number of row-contiguous store passes over a wave tile of MI x NI blocks, and the residual tile of EPI_RESID in
+// that layout: pass p, lane (rr, cc) holds the 8 residual values of row p*RPP + rr, columns cc .. cc+7.
+template <int MI, int NI>
+struct ResidTile {
+  static constexpr int LPR = NI * 4, RPP = 64 / LPR, P = MI * 32 / RPP;
+  uint4_t r[P];
+};
 
 template <int MI, int NI, int WGN, int ACT, int EPI>
 __device__ __forceinline__ void store_tile(const float16_t (&acc)[MI][NI], const GemmEpi& ep, const EpiVecs<NI>& vec,
                                            const float (&mu)[MI], const float (&rstd)[MI],
-                                           const half4_t (&rres)[MI][NI][4], int tile_n,
+                                           const ResidTile<MI, NI>& rres, int tile_n,
                                            int wn, int row_in_tile, float2* red /* LDS [WGN][rows of the tile] */,
                                            int tile_rows, half_t* __restrict__ C, int M, int N, int m_base,
                                            int n_base, int lane,
@@ -145,24 +157,22 @@ __device__ __forceinline__ void store_tile(const float16_t (&acc)[MI][NI], const
   constexpr int WN = NI * 32, LD = WN + 8;
   const int l32 = lane & 31, hf = lane >> 5;
   const bool folded_resid = EPI == EPI_RESID && ep.resid_part != nullptr;
-  float s0[MI], s1[MI];
-#pragma unroll
-  for (int i = 0; i < MI; ++i) s0[i] = s1[i] = 0.f;
   // rows of this wave's tile in the store pass: WN/8 lanes per row
   constexpr int LPR = WN / 8, RPP = 64 / LPR;  // lanes per row, rows per pass
   const int rr = lane / LPR, cc = (lane % LPR) * 8;
-  // One 32-row block at a time: arithmetic on the accumulators, fp16 block to LDS, then (except with
-  // EPI_RESID, whose partial sums go out first) straight to memory -- the stores of block i drain while
-  // the arithmetic of block i+1 runs.
+  // One 32-row block at a time: arithmetic on the accumulators, fp16 block to LDS, then the row-contiguous
+  // pass straight to memory -- the stores of block i drain while the arithmetic of block i+1 runs.
+  // EPI_RESID: the accumulator pass only adds the bias; the residual, the row sums and the output scale live
+  // in the row pass, where the residual arrives as whole 16-byte pieces of a row (requested like that, 8 lanes
+  // per 128-byte line, instead of 8-byte pieces gathered in accumulator layout) and a row's partial sums are
+  // an exchange among the LPR neighbouring lanes that share the row.
 #pragma unroll
   for (int i = 0; i < MI; ++i) {
-    const int m = m_base + i * 32 + l32;
 #pragma unroll
     for (int j = 0; j < NI; ++j) {
 #pragma unroll
       for (int g = 0; g < 4; ++g) {
         const int nl = j * 32 + 8 * g + 4 * hf;
-        const bool n_ok = n_base + nl < N;  // N % 8 == 0: the 4 columns are all in or all out
         float v[4];
 #pragma unroll
         for (int t = 0; t < 4; ++t) v[t] = acc[i][j][4 * g + t];
@@ -173,20 +183,7 @@ __device__ __forceinline__ void store_tile(const float16_t (&acc)[MI][NI], const
 #pragma unroll
           for (int t = 0; t < 4; ++t) v[t] += (float)vec.bias[j][g][t];
         }
-        if constexpr (EPI == EPI_RESID) {
-          const half4_t r4 = rres[i][j][g];
-          const bool ok = n_ok && m < M;
-#pragma unroll
-          for (int t = 0; t < 4; ++t) {
-            const float r = folded_resid
-                                ? __builtin_fmaf(rstd[i], (float)r4[t] - mu[i] * (float)vec.rg[j][g][t], (float)vec.rb[j][g][t])
-                                : (float)r4[t];
-            v[t] = ok ? v[t] + r : 0.f;
-            s0[i] += v[t];
-            s1[i] = __builtin_fmaf(v[t], v[t], s1[i]);
-            v[t] *= (float)vec.og[j][g][t];
-          }
-        } else {
+        if constexpr (EPI != EPI_RESID) {
 #pragma unroll
           for (int t = 0; t < 4; ++t) {
             if (ACT == BT_ACT_GELU_ERF) v[t] = gelu_erf(v[t]);
@@ -199,23 +196,46 @@ __device__ __forceinline__ void store_tile(const float16_t (&acc)[MI][NI], const
         *reinterpret_cast<half4_t*>(stage + (i * 32 + l32) * LD + nl) = o;
       }
     }
-    if constexpr (EPI != EPI_RESID) {
 #pragma unroll
-      for (int r0 = i * 32; r0 < (i + 1) * 32; r0 += RPP) {
-        const int mr = m_base + r0 + rr, n = n_base + cc;
-        const uint4_t v = *reinterpret_cast<const uint4_t*>(stage + (r0 + rr) * LD + cc);
-        if (mr < M && n < N) store_through(C + ((size_t)mr * N + n), v);
+    for (int r0 = i * 32; r0 < (i + 1) * 32; r0 += RPP) {
+      const int mr = m_base + r0 + rr, n = n_base + cc;
+      uint4_t out4 = *reinterpret_cast<const uint4_t*>(stage + (r0 + rr) * LD + cc);
+      const bool ok = mr < M && n < N;
+      if constexpr (EPI == EPI_RESID) {
+        const half8_t h8 = __builtin_bit_cast(half8_t, out4);
+        const half8_t r8 = __builtin_bit_cast(half8_t, rres.r[r0 / RPP]);
+        // mean and 1/sigma of the residual's row: lane (r0+rr) % 32 holds them in accumulator layout
+        const float mu_r = __shfl(mu[i], (r0 + rr) & 31, kWave), rstd_r = __shfl(rstd[i], (r0 + rr) & 31, kWave);
+        float s0 = 0.f, s1 = 0.f;
+        half8_t u8;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          const float r = folded_resid
+                              ? __builtin_fmaf(rstd_r, (float)r8[e] - mu_r * (float)vec.rg8[e], (float)vec.rb8[e])
+                              : (float)r8[e];
+          const float v = ok ? (float)h8[e] + r : 0.f;
+          s0 += v;
+          s1 = __builtin_fmaf(v, v, s1);
+          u8[e] = (half_t)(v * (float)vec.og8[e]);
+        }
+        out4 = __builtin_bit_cast(uint4_t, u8);
+#pragma unroll
+        for (int o = 1; o < LPR; o <<= 1) {  // the LPR lanes of a row are neighbours
+          s0 += __shfl_xor(s0, o, kWave);
+          s1 += __shfl_xor(s1, o, kWave);
+        }
+        if ((lane % LPR) == 0) red[wn * tile_rows + row_in_tile + r0 + rr] = make_float2(s0, s1);
       }
+      // Device-scope (write-through) stores: the tile leaves the L2 as it is produced.  Plain stores leave
+      // 1-2 MB of dirty lines in every XCD's L2 and the kernel then ends with their write-back, ~3 us for
+      // a 14 MB product with every CU idle; written through, that overlaps the tail of the computation
+      // (3 % off a 12-layer forward).  Non-temporal stores save the same but the next kernel reads slower.
+      if (ok) store_through(C + ((size_t)mr * N + n), out4);
     }
   }
   if constexpr (EPI == EPI_RESID) {
-    // Row sums of this wave's columns -> LDS; after the barrier the wavefronts of tile column 0 add the
+    // Row sums of this wave's columns are in LDS; after the barrier the wavefronts of tile column 0 add the
     // WGN contributions in order and store ONE partial per row and column tile.
-#pragma unroll
-    for (int i = 0; i < MI; ++i) {  // the two 32-lane halves hold the two column halves of the same row
-      const float t0 = s0[i] + __shfl_xor(s0[i], 32, kWave), t1 = s1[i] + __shfl_xor(s1[i], 32, kWave);
-      if (hf == 0) red[wn * tile_rows + row_in_tile + i * 32 + l32] = make_float2(t0, t1);
-    }
     __syncthreads();
     if (wn == 0 && hf == 0) {
 #pragma unroll
@@ -230,18 +250,6 @@ __device__ __forceinline__ void store_tile(const float16_t (&acc)[MI][NI], const
         }
         if (m < M) ep.part_out[(size_t)m * ep.part_np + tile_n] = t;
       }
-    }
-  }
-  // Device-scope (write-through) stores: the tile leaves the L2 as it is produced.  Plain stores leave
-  // 1-2 MB of dirty lines in every XCD's L2 and the kernel then ends with their write-back, ~3 us for
-  // a 14 MB product with every CU idle; written through, that overlaps the tail of the computation
-  // (3 % off a 12-layer forward).  Non-temporal stores save the same but the next kernel reads slower.
-  if constexpr (EPI == EPI_RESID) {
-#pragma unroll
-    for (int r0 = 0; r0 < MI * 32; r0 += RPP) {
-      const int mr = m_base + r0 + rr, n = n_base + cc;
-      const uint4_t v = *reinterpret_cast<const uint4_t*>(stage + (r0 + rr) * LD + cc);
-      if (mr < M && n < N) store_through(C + ((size_t)mr * N + n), v);
     }
   }
 }
@@ -333,44 +341,34 @@ __device__ __forceinline__ void finish_row_sums(const float2* __restrict__ part,
   }
 }
 
-// The same tile requested through inline assembly, exactly MI*NI*4 load instructions whatever M and N
+// The residual tile requested through inline assembly, exactly ResidTile::P load instructions whatever M and N
 // (addresses clamped into the matrix; positions outside it are ignored by the epilogue): the K loop counts
-// outstanding memory instructions by hand and must know this number.
+// outstanding memory instructions by hand and must know this number.  rrow[p]: the residual row of store pass p
+// of this lane (clamped, and already translated through resid_rows where the residual is the padded input).
 template <int MI, int NI>
-__device__ __forceinline__ void request_resid(const half_t* __restrict__ resid, const int (&rrow)[MI], int N, int n_base,
-                                              int hf, half4_t (&rres)[MI][NI][4]) {
-  // rrow[i]: the residual row of accumulator row block i of this lane (clamped into the matrix, and already
-  // translated through resid_rows where the residual is the padded input tensor)
+__device__ __forceinline__ void request_resid(const half_t* __restrict__ resid, const int (&rrow)[ResidTile<MI, NI>::P],
+                                              int N, int n_base, int lane, ResidTile<MI, NI>& rres) {
+  const int n = min(n_base + (lane % ResidTile<MI, NI>::LPR) * 8, N - 8);
 #pragma unroll
-  for (int i = 0; i < MI; ++i)
-#pragma unroll
-    for (int j = 0; j < NI; ++j)
-#pragma unroll
-      for (int g = 0; g < 4; ++g) {
-        const int n = min(n_base + j * 32 + 8 * g + 4 * hf, N - 4);
-        const half_t* src = resid + (size_t)rrow[i] * N + n;
-        half4_t t;
-        asm volatile("global_load_dwordx2 %0, %1, off" : "=v"(t) : "v"(src) : "memory");
-        rres[i][j][g] = t;
-      }
+  for (int p = 0; p < ResidTile<MI, NI>::P; ++p) {
+    const half_t* src = resid + (size_t)rrow[p] * N + n;
+    uint4_t t;
+    asm volatile("global_load_dwordx4 %0, %1, off" : "=v"(t) : "v"(src) : "memory");
+    rres.r[p] = t;
+  }
 }
 
-// The residual tile of EPI_RESID in accumulator layout (zero outside the matrix).
+// The same tile with ordinary loads (fallback kernel).
 template <int MI, int NI>
 __device__ __forceinline__ void load_resid(const half_t* __restrict__ resid, const int32_t* __restrict__ rows, int M,
-                                           int N, int m_base, int n_base, int l32, int hf, half4_t (&rres)[MI][NI][4]) {
-  const half4_t zero = {(half_t)0.f, (half_t)0.f, (half_t)0.f, (half_t)0.f};
+                                           int N, int m_base, int n_base, int lane, ResidTile<MI, NI>& rres) {
+  constexpr int LPR = ResidTile<MI, NI>::LPR, RPP = ResidTile<MI, NI>::RPP;
+  const int n = min(n_base + (lane % LPR) * 8, N - 8);
 #pragma unroll
-  for (int i = 0; i < MI; ++i)
-#pragma unroll
-    for (int j = 0; j < NI; ++j)
-#pragma unroll
-      for (int g = 0; g < 4; ++g) {
-        const int m = m_base + i * 32 + l32, n = n_base + j * 32 + 8 * g + 4 * hf;
-        rres[i][j][g] = (m < M && n < N)
-                            ? *reinterpret_cast<const half4_t*>(resid + (size_t)(rows ? rows[m] : m) * N + n)
-                            : zero;
-      }
+  for (int p = 0; p < ResidTile<MI, NI>::P; ++p) {
+    const int m = min(m_base + p * RPP + lane / LPR, M - 1);
+    rres.r[p] = *reinterpret_cast<const uint4_t*>(resid + (size_t)(rows ? rows[m] : m) * N + n);
+  }
 }
 
 // ---------------------------------------------------------------------------
@@ -431,7 +429,7 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_pipe_kernel(
   // load whose latency then hides behind the K loop).  The folded forms hold more per-column operands than
   // there are registers to park them across the K loop; they load them right before the epilogue.  Their
   // residual tile and partial row sums are requested in the last steady round (see below).
-  half4_t rres[MI][NI][4];  // dead (and removed by the compiler) in the other epilogue forms
+  ResidTile<MI, NI> rres;  // dead (and removed by the compiler) in the other epilogue forms
   EpiVecs<NI> vec;
   __shared__ float2 red[EPI == EPI_RESID ? WGN * BM : 1];
   float2 psum[MI][kMaxHalfParts];
@@ -441,7 +439,7 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_pipe_kernel(
   const float2* const stat_src = EPI == EPI_FOLD ? ep.ln_part : (EPI == EPI_RESID ? ep.resid_part : nullptr);
   const float2* const stat_part = stat_src ? stat_src : reinterpret_cast<const float2*>(W);
   const int stat_np = stat_src ? (EPI == EPI_FOLD ? ep.ln_np : ep.resid_np) : 0;
-  constexpr int kLateLoads = (EPI == EPI_RESID ? MI * NI * 4 : 0) + (kStats ? MI * kMaxHalfParts : 0);
+  constexpr int kLateLoads = (EPI == EPI_RESID ? ResidTile<MI, NI>::P : 0) + (kStats ? MI * kMaxHalfParts : 0);
   static_assert((NS - 2) * TOT + kLateLoads < 64, "vmcnt range");
 
   // DMA source pointers.  Instruction q of this wave fills LDS rows [r0, r0+8) of the slab; lane i
@@ -462,16 +460,16 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_pipe_kernel(
     const int c = (lane % CPR) ^ ((r >> 1) & (CPR - 1));
     gb[q] = W + (size_t)min(n0 + r, N - 1) * K + k_off + c * 8;
   }
-  // Residual rows of this lane's accumulator rows (EPI_RESID): resolved here, with the operand row indices and
+  // Residual rows of this lane's store passes (EPI_RESID): resolved here, with the operand row indices and
   // before the first DMA, so that the late residual requests need no dependent index load.
-  int rrow[MI];
+  int rrow[ResidTile<MI, NI>::P];
 #pragma unroll
-  for (int i = 0; i < MI; ++i) {
-    const int m = min(m0 + wm * WM + i * 32 + l32, M - 1);
-    rrow[i] = (EPI == EPI_RESID && ep.resid_rows) ? ep.resid_rows[m] : m;
+  for (int p = 0; p < ResidTile<MI, NI>::P; ++p) {
+    const int m = min(m0 + wm * WM + p * ResidTile<MI, NI>::RPP + lane / ResidTile<MI, NI>::LPR, M - 1);
+    rrow[p] = (EPI == EPI_RESID && ep.resid_rows) ? ep.resid_rows[m] : m;
     // collected here: the wait for this load must not end up in the K loop, where the compiler cannot see
     // the DMA instructions in flight and would wait for all of them
-    if constexpr (EPI == EPI_RESID) asm volatile("" : "+v"(rrow[i]));
+    if constexpr (EPI == EPI_RESID) asm volatile("" : "+v"(rrow[p]));
   }
   const uint32_t lds_a = lds_addr(sA) + wave * LA * RPI * BK * 2;  // bytes
   const uint32_t lds_b = lds_addr(sB) + wave * LB * RPI * BK * 2;
@@ -509,7 +507,7 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_pipe_kernel(
   // These loads sit between the DMA of the first NS-1 slabs and of the later ones in the in-order queue the
   // hand-written waits count: a wait for slab k then also waits for as many of the younger entries as there
   // are loads here -- more than needed, never less, and only for the first slabs.
-  if constexpr (EPI == EPI_PLAIN) load_epi_vecs<NI, EPI>(ep, bias, N, n0 + wn * WN, hf, vec);
+  if constexpr (EPI == EPI_PLAIN) load_epi_vecs<NI, EPI>(ep, bias, N, n0 + wn * WN, lane, vec);
 
   // operand read offsets (halves): row*BK + ((2ks+hf) ^ swz(row))*8 ; swz depends on l32 only
   const int swz = (l32 >> 1) & (CPR - 1);
@@ -592,7 +590,7 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_pipe_kernel(
 #pragma unroll
   for (int i = 0; i < MI; ++i) { mu[i] = 0.f; rstd[i] = 1.f; }
   auto late_requests = [&]() {
-    if constexpr (EPI == EPI_RESID) request_resid<MI, NI>(ep.resid, rrow, N, n0 + wn * WN, hf, rres);
+    if constexpr (EPI == EPI_RESID) request_resid<MI, NI>(ep.resid, rrow, N, n0 + wn * WN, lane, rres);
     if constexpr (kStats) request_row_sums<MI>(stat_part, stat_np, M, m0 + wm * WM, l32, hf, psum);
   };
   auto late_collect = [&]() {
@@ -600,11 +598,7 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_pipe_kernel(
       wait_vmcnt<0>();
       if constexpr (EPI == EPI_RESID) {
 #pragma unroll
-        for (int i = 0; i < MI; ++i)
-#pragma unroll
-          for (int j = 0; j < NI; ++j)
-#pragma unroll
-            for (int g = 0; g < 4; ++g) asm volatile("" : "+v"(rres[i][j][g]));  // ordered after the wait
+        for (int p = 0; p < ResidTile<MI, NI>::P; ++p) asm volatile("" : "+v"(rres.r[p]));  // ordered after the wait
       }
       finish_row_sums<MI>(stat_part, stat_np, M, m0 + wm * WM, l32, hf, ep.inv_h, ep.eps, psum, mu, rstd);
     }
@@ -638,7 +632,7 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_pipe_kernel(
 #pragma unroll
     for (int i = 0; i < MI; ++i) { mu[i] = 0.f; rstd[i] = 1.f; }
   }
-  if constexpr (EPI == EPI_FOLD || EPI == EPI_RESID) load_epi_vecs<NI, EPI>(ep, bias, N, n0 + wn * WN, hf, vec);
+  if constexpr (EPI == EPI_FOLD || EPI == EPI_RESID) load_epi_vecs<NI, EPI>(ep, bias, N, n0 + wn * WN, lane, vec);
   if constexpr (EPI == EPI_PARTIAL) {
     __builtin_amdgcn_s_barrier();  // every wave is done reading the last slab: LDS becomes staging space
     store_partial<MI, NI>(acc, ep.partial + (size_t)split * M * N, M, N, m0 + wm * WM, n0 + wn * WN, lane,
@@ -697,7 +691,7 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_simple_kernel(const half_t*
   }
   __syncthreads();  // operand tiles are dead: reuse them as per-wave staging space (32 x 40 halves each)
   float mu[1] = {0.f}, rstd[1] = {1.f};
-  half4_t rres[1][1][4];
+  ResidTile<1, 1> rres;
   __shared__ float2 red[EPI == EPI_RESID ? 2 * BM : 1];
   const float2* const stat_part = EPI == EPI_FOLD ? ep.ln_part : (EPI == EPI_RESID ? ep.resid_part : nullptr);
   const int stat_np = EPI == EPI_FOLD ? ep.ln_np : ep.resid_np;
@@ -707,9 +701,9 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_simple_kernel(const half_t*
     wait_vmcnt<0>();
     finish_row_sums<1>(stat_part, stat_np, M, m0 + wm * 32, l32, hf, ep.inv_h, ep.eps, psum, mu, rstd);
   }
-  if constexpr (EPI == EPI_RESID) load_resid<1, 1>(ep.resid, ep.resid_rows, M, N, m0 + wm * 32, n0 + wn * 32, l32, hf, rres);
+  if constexpr (EPI == EPI_RESID) load_resid<1, 1>(ep.resid, ep.resid_rows, M, N, m0 + wm * 32, n0 + wn * 32, lane, rres);
   EpiVecs<1> vec;
-  load_epi_vecs<1, EPI>(ep, ep.bias, N, n0 + wn * 32, hf, vec);
+  load_epi_vecs<1, EPI>(ep, ep.bias, N, n0 + wn * 32, lane, vec);
   store_tile<1, 1, 2, ACT, EPI>(acc, ep, vec, mu, rstd, rres, tn, wn, wm * 32, red, BM, C, M, N, m0 + wm * 32, n0 + wn * 32,
                                 lane, (wave < 2 ? sA : sB) + (wave & 1) * 32 * 40);
 }
@@ -746,7 +740,10 @@ static bt_status launch_pipe(const half_t* A, const half_t* W, half_t* C, int M,
     }                                                                           \
   } while (0)
   if (epi == EPI_RESID) {
-    // only for shapes with one 32x32 block per wavefront (the residual tile lives in registers)
+    // only for shapes with one 32x32 block per wavefront: the residual tile and the partial row sums wait in
+    // registers across the last slabs, and the two largest shapes have none to spare (they would spill, which
+    // the hand-collected loads do not survive).  128x128 fits (192 registers) but gains nothing where it could
+    // be chosen: folded and plain layers are level from 2 700 to 5 400 tokens of width 768 with it.
     if constexpr ((BM / WGM) * (BN / WGN) == 32 * 32) BT_LAUNCH(BT_ACT_NONE, EPI_RESID);
     else return BT_ERR_UNSUPPORTED;
   } else if (epi == EPI_FOLD) {
@@ -792,7 +789,7 @@ static bt_status launch_simple(const half_t* A, const half_t* W, half_t* C, int 
 // BM+BN, and the grid runs in ceil(tiles / 256) rounds of one tile per compute unit.  slab_us and
 // epi_us (epilogue + pipeline fill) were measured per shape on MI355X; GELU adds to the epilogue.
 // Returns the index into kGemmTiles.  K % 64 == 0.
-struct GemmTile { int bm, bn; float slab_us, epi_us; bool one_block_per_wave; };
+struct GemmTile { int bm, bn; float slab_us, epi_us; bool resid_form; };
 static const GemmTile kGemmTiles[6] = {{256, 128, 0.607f, 2.2f, false}, {192, 128, 0.482f, 1.5f, false},
                                        {128, 128, 0.384f, 1.5f, false}, {128, 64, 0.298f, 0.78f, true},
                                        {64, 128, 0.287f, 0.84f, true},  {64, 64, 0.183f, 0.4f, true}};
@@ -801,9 +798,7 @@ static int gemm_tile_choice(int M, int N, int K, bt_act act, int epi) {
   float best_us = 0.f;
   for (int c = 0; c < 6; ++c) {
     const GemmTile& t = kGemmTiles[c];
-    // EPI_RESID keeps a residual tile per lane across the last slabs: only the shapes with one 32x32
-    // block per wavefront have the registers for it
-    if (epi == EPI_RESID && !t.one_block_per_wave) continue;
+    if (epi == EPI_RESID && !t.resid_form) continue;  // see launch_pipe
     const long long tiles = (long long)((M + t.bm - 1) / t.bm) * ((N + t.bn - 1) / t.bn);
     const long long rounds = (tiles + 255) / 256;
     const float act_us = act != BT_ACT_NONE ? 9e-5f * t.bm * t.bn : 0.f;

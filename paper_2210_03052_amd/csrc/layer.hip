@@ -226,8 +226,8 @@ static bt_status stack_fwd_folded(const bt_layer* layers, int n_layers, const fl
 // Whether the folded pipeline is the faster one for T tokens (hidden width H, FFN width F).  Its residual
 // epilogue exists for the small tile shapes only (64 x 128 for the H-wide products); as long as those tiles fit
 // one round of the 256 compute units the two launches saved per layer win, beyond that the small tiles run in
-// several rounds and the plain 7-launch layer with its larger tiles is faster (measured: -2.3 ... -3 % at
-// 2 308 tokens of width 768, +19 % at 9 894).  With so few tokens that the plain layer splits K of its
+// several rounds and the plain 7-launch layer with its larger tiles is faster (measured: -4 % from 1 280 to
+// 2 560 tokens of width 768, -3 % at 2 048 tokens of width 1024; +7 ... +18 % beyond 5 400 tokens).  With so few tokens that the plain layer splits K of its
 // H-wide products, the plain layer wins again (the folded epilogue has no split-K form: +1.5 % at 186 tokens).
 static bool folded_pays(int T, int H, int F) {
   if ((long long)((T + 63) / 64) * ((H + 127) / 128) > 256) return false;
