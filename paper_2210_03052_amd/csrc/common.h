@@ -83,11 +83,40 @@ __device__ __forceinline__ void store_through(float* gptr, const float4_t& v) {
                ::"v"((float __attribute__((address_space(1)))*)gptr), "v"(v) : "memory");
 }
 
-// Butterfly reductions over the 64 lanes of a wavefront.
+// Cross-lane moves inside a row of 16 lanes through the data-parallel-primitive operand path (no LDS trip,
+// unlike ds_bpermute, which is what __shfl compiles to).  CTRL: 0xB1 = lane ^ 1, 0x4E = lane ^ 2 (quad
+// permutations), 0x141 = 7 - lane within 8 (half mirror), 0x140 = 15 - lane within 16 (mirror).
+template <int CTRL>
+__device__ __forceinline__ int dpp_move(int v) {
+  return __builtin_amdgcn_update_dpp(v, v, CTRL, 0xf, 0xf, false);
+}
+template <int CTRL>
+__device__ __forceinline__ float dpp_move(float v) {
+  return __builtin_bit_cast(float, dpp_move<CTRL>(__builtin_bit_cast(int, v)));
+}
+
+// Sum / maximum over the 64 lanes of a wavefront, the same value in every lane: four steps inside each row
+// of 16 lanes (after the two quad steps every lane of a quad holds the quad's value, so the mirrors combine
+// whole quads), then the four row results are read as scalars and combined in a fixed order.
 __device__ __forceinline__ float wave_sum(float v) {
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, kWave);
-  return v;
+  v += dpp_move<0xB1>(v);
+  v += dpp_move<0x4E>(v);
+  v += dpp_move<0x141>(v);
+  v += dpp_move<0x140>(v);
+  const int b = __builtin_bit_cast(int, v);
+  const float r0 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(b, 0));
+  const float r1 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(b, 16));
+  const float r2 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(b, 32));
+  const float r3 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(b, 48));
+  return (r0 + r1) + (r2 + r3);
+}
+__device__ __forceinline__ int wave_max(int v) {
+  v = max(v, dpp_move<0xB1>(v));
+  v = max(v, dpp_move<0x4E>(v));
+  v = max(v, dpp_move<0x141>(v));
+  v = max(v, dpp_move<0x140>(v));
+  return max(max(__builtin_amdgcn_readlane(v, 0), __builtin_amdgcn_readlane(v, 16)),
+             max(__builtin_amdgcn_readlane(v, 32), __builtin_amdgcn_readlane(v, 48)));
 }
 
 }  // namespace bt

@@ -219,10 +219,18 @@ __device__ __forceinline__ void store_tile(const float16_t (&acc)[MI][NI], const
           u8[e] = (half_t)(v * (float)vec.og8[e]);
         }
         out4 = __builtin_bit_cast(uint4_t, u8);
-#pragma unroll
-        for (int o = 1; o < LPR; o <<= 1) {  // the LPR lanes of a row are neighbours
-          s0 += __shfl_xor(s0, o, kWave);
-          s1 += __shfl_xor(s1, o, kWave);
+        // the LPR (4, 8 or 16) lanes of a row are neighbours inside one row of 16 lanes
+        s0 += dpp_move<0xB1>(s0);
+        s1 += dpp_move<0xB1>(s1);
+        s0 += dpp_move<0x4E>(s0);
+        s1 += dpp_move<0x4E>(s1);
+        if constexpr (LPR >= 8) {
+          s0 += dpp_move<0x141>(s0);
+          s1 += dpp_move<0x141>(s1);
+        }
+        if constexpr (LPR >= 16) {
+          s0 += dpp_move<0x140>(s0);
+          s1 += dpp_move<0x140>(s1);
         }
         if ((lane % LPR) == 0) red[wn * tile_rows + row_in_tile + r0 + rr] = make_float2(s0, s1);
       }

@@ -207,10 +207,7 @@ __device__ __forceinline__ bool locate_tile(const int32_t* __restrict__ cu, int 
     const int start = lane < B ? cu[lane] : 0;
     const int len = lane < B ? cu[lane + 1] - start : 0;
     const int nt = (len + BQ - 1) / BQ;
-    int vmax = nt;  // largest tile count present: where the walk over the groups starts
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) vmax = max(vmax, __shfl_xor(vmax, o, kWave));
-    vmax = __builtin_amdgcn_readfirstlane(vmax);
+    const int vmax = wave_max(nt);  // largest tile count present: where the walk over the groups starts
     const unsigned long long below = (1ull << lane) - 1ull;
     int running = 0;
     for (int v = vmax; v >= 1; --v) {
@@ -220,9 +217,9 @@ __device__ __forceinline__ bool locate_tile(const int32_t* __restrict__ cu, int 
         const int idx = qtile - running;
         const int j = idx / v;  // j-th sequence of the group, its q-tile idx % v
         const unsigned long long me = __ballot(nt == v && __popcll(grp & below) == j);
-        const int src = __ffsll((long long)me) - 1;
-        tok0 = __builtin_amdgcn_readfirstlane(__shfl(start, src, kWave));
-        L = __builtin_amdgcn_readfirstlane(__shfl(len, src, kWave));
+        const int src = __ffsll((long long)me) - 1;  // wave-uniform
+        tok0 = __builtin_amdgcn_readlane(start, src);
+        L = __builtin_amdgcn_readlane(len, src);
         qt = idx - j * v;
         return true;
       }
@@ -245,13 +242,13 @@ __device__ __forceinline__ bool locate_tile(const int32_t* __restrict__ cu, int 
     const int excl = running + incl - nt;
     const unsigned long long hit = __ballot(qtile >= excl && qtile < excl + nt);
     if (hit) {
-      const int src = __ffsll((long long)hit) - 1;
-      tok0 = __builtin_amdgcn_readfirstlane(__shfl(start, src, kWave));
-      L = __builtin_amdgcn_readfirstlane(__shfl(len, src, kWave));
-      qt = __builtin_amdgcn_readfirstlane(qtile - __shfl(excl, src, kWave));
+      const int src = __ffsll((long long)hit) - 1;  // wave-uniform
+      tok0 = __builtin_amdgcn_readlane(start, src);
+      L = __builtin_amdgcn_readlane(len, src);
+      qt = qtile - __builtin_amdgcn_readlane(excl, src);
       return true;
     }
-    running += __shfl(incl, kWave - 1, kWave);
+    running += __builtin_amdgcn_readlane(incl, kWave - 1);
   }
   return false;
 }
