@@ -120,7 +120,7 @@ bt_status bt_unpack(const bt_half* d_packed, const int32_t* d_token_idx, int T, 
  * with d_k = d_q + heads*head_dim, d_v = d_q + 2*heads*head_dim reads the fused
  * [T, q|k|v] buffer GEMM #0 writes; row_stride = heads*head_dim reads three
  * separate tensors.  row_stride % 8 == 0.
- * d_bq/d_bk/d_bv: optional fp16 [heads*head_dim] biases (NULL = none).  Alg. 1 adds them while
+ * d_bq/d_bk/d_bv: optional fp16 [heads*head_dim] biases (NULL = none; 16-byte aligned).  Alg. 1 adds them while
  * the operands are loaded; here b_q is added to the Q registers (fp32 add, fp16 result), b_k is
  * ignored because (q+b_q).b_k is constant along a softmax row and cancels exactly, and b_v is added
  * to the output because the probabilities of a row sum to one -- the same function, fewer roundings.

@@ -736,12 +736,18 @@ static bt_status launch_pipe(const half_t* A, const half_t* W, half_t* C, int M,
 #define BT_LAUNCH_S(ACT, EPI, SHAPE) \
   gemm_pipe_kernel<BM, BN, WGM, WGN, NS, ACT, EPI, SHAPE><<<grid, block, 0, st>>>(A, W, ep.a_rows, ep.bias, M, N, K, tiles_n, tiles_m, group_m, C, ep)
   // the shape class is spelled out only where two products of a layer can meet in one instantiation
-  // (no activation, plain epilogue); everything else is told apart by ACT / EPI already
+  // (no activation); the FFN-up product is told apart by its activation already
 #define BT_LAUNCH(ACT, EPI)                                                     \
   do {                                                                          \
     if constexpr ((ACT) == BT_ACT_NONE && (EPI) == EPI_PLAIN) {                 \
       if (N >= 2 * K) BT_LAUNCH_S(ACT, EPI, 0);                                 \
       else if (K >= 2 * N) BT_LAUNCH_S(ACT, EPI, 2);                            \
+      else BT_LAUNCH_S(ACT, EPI, 1);                                            \
+    } else if constexpr ((ACT) == BT_ACT_NONE && (EPI) == EPI_FOLD) {           \
+      if (N >= 2 * K) BT_LAUNCH_S(ACT, EPI, 0);                                 \
+      else BT_LAUNCH_S(ACT, EPI, 1);                                            \
+    } else if constexpr ((EPI) == EPI_RESID) {                                  \
+      if (K >= 2 * N) BT_LAUNCH_S(ACT, EPI, 2);                                 \
       else BT_LAUNCH_S(ACT, EPI, 1);                                            \
     } else {                                                                    \
       BT_LAUNCH_S(ACT, EPI, 1);                                                 \

@@ -99,6 +99,15 @@ __device__ __forceinline__ void mask_ragged(float16_t (&s)[2], int k0, int L, in
     }
 }
 
+// x of lane l and of lane l ^ 32 as (value of the lower half, value of the upper half), the same pair in both
+// lanes: the cross-half lane swap of gfx950, a VALU operation (no trip through the LDS queue).
+__device__ __forceinline__ void both_halves(float x, float& lo, float& hi) {
+  const unsigned u = __builtin_bit_cast(unsigned, x);
+  const auto sw = __builtin_amdgcn_permlane32_swap(u, u, false, false);  // {lo,lo} and {hi,hi} of the halves
+  lo = __builtin_bit_cast(float, (unsigned)sw[0]);
+  hi = __builtin_bit_cast(float, (unsigned)sw[1]);
+}
+
 // m_run is kept in the scaled log2 domain and is only raised when the tile maximum exceeds it by
 // more than 8 (a factor 256: probabilities stay <= 256, exact in fp16/fp32 terms), so the rescale
 // of the accumulators is skipped for most tiles; any reference maximum gives the same softmax.
@@ -118,10 +127,9 @@ __device__ __forceinline__ void softmax_max(const float16_t (&s)[2], float scale
   }
   float mx = fmaxf(fmaxf(fmaxf(c[0], c[1]), c[2]), c[3]);
   {
-    const unsigned u = __builtin_bit_cast(unsigned, mx);
-    const auto sw = __builtin_amdgcn_permlane32_swap(u, u, false, false);  // {lo,lo} and {hi,hi} of the halves
-    const unsigned lo = sw[0], hi = sw[1];
-    mx = fmaxf(__builtin_bit_cast(float, lo), __builtin_bit_cast(float, hi));
+    float lo, hi;
+    both_halves(mx, lo, hi);
+    mx = fmaxf(lo, hi);
   }
   const float mx_s = mx * scale_log2e;            // finite: every tile holds at least one valid key
   const bool raise = mx_s > m_run + 8.0f;         // same in both halves of a query column
@@ -334,10 +342,13 @@ __global__ __launch_bounds__(NW * 64) void varlen_mha_kernel(
     if (s < ntiles) issue_tile(s, s);
 
   if (bq) {
+    half8_t b8[4];
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) b8[ks] = *reinterpret_cast<const half8_t*>(bq + hofs + ks * 16 + hf * 8);
 #pragma unroll
     for (int ks = 0; ks < 4; ++ks)
 #pragma unroll
-      for (int e = 0; e < 8; ++e) qf[ks][e] = (half_t)((float)qf[ks][e] + (float)bq[hofs + ks * 16 + hf * 8 + e]);
+      for (int e = 0; e < 8; ++e) qf[ks][e] = (half_t)((float)qf[ks][e] + (float)b8[ks][e]);
   }
   // The Q loads must be complete BEFORE the tile loop.  Left to the compiler, their s_waitcnt vmcnt(3..0)
   // land at the first use inside the loop body and are executed by every iteration, where the only
@@ -381,20 +392,29 @@ __global__ __launch_bounds__(NW * 64) void varlen_mha_kernel(
   half_t* ostage = ((wave & 2) ? sV : sK) + (wave & 1) * (32 * OLD);
   static_assert(2 * 32 * OLD <= NS * TILE, "two staged blocks fit one operand ring");
   if (wave_active) {
-    const float l_tot = l_run + __shfl_xor(l_run, 32, kWave);
-    const float inv = 1.0f / l_tot;
+    float l_lo, l_hi;
+    both_halves(l_run, l_lo, l_hi);
+    const float inv = 1.0f / (l_lo + l_hi);
+    // the value bias, all eight pieces requested together (one round trip, and only when there is a bias)
+    half4_t bias4[2][4];
+    if (bv) {
+#pragma unroll
+      for (int db = 0; db < 2; ++db)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) bias4[db][g] = *reinterpret_cast<const half4_t*>(bv + hofs + db * 32 + 8 * g + 4 * hf);
+    } else {
+#pragma unroll
+      for (int db = 0; db < 2; ++db)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) bias4[db][g] = half4_t{(half_t)0.f, (half_t)0.f, (half_t)0.f, (half_t)0.f};
+    }
 #pragma unroll
     for (int db = 0; db < 2; ++db)
 #pragma unroll
       for (int g = 0; g < 4; ++g) {
-        float bias4[4] = {0.f, 0.f, 0.f, 0.f};
-        if (bv) {
-#pragma unroll
-          for (int t = 0; t < 4; ++t) bias4[t] = (float)bv[hofs + db * 32 + 8 * g + 4 * hf + t];
-        }
         half4_t o;
 #pragma unroll
-        for (int t = 0; t < 4; ++t) o[t] = (half_t)(o_acc[db][4 * g + t] * inv + bias4[t]);
+        for (int t = 0; t < 4; ++t) o[t] = (half_t)(o_acc[db][4 * g + t] * inv + (float)bias4[db][g][t]);
         *reinterpret_cast<half4_t*>(ostage + l32 * OLD + db * 32 + 8 * g + 4 * hf) = o;
       }
     // same wavefront reads what it wrote: LDS operations of a wave complete in order
@@ -474,10 +494,13 @@ __global__ __launch_bounds__(NK * 64) void varlen_mha_splitkey_kernel(
     if (s < my_tiles) issue_tile(wave + s * NK, s);
 
   if (bq) {
+    half8_t b8[4];
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) b8[ks] = *reinterpret_cast<const half8_t*>(bq + hofs + ks * 16 + hf * 8);
 #pragma unroll
     for (int ks = 0; ks < 4; ++ks)
 #pragma unroll
-      for (int e = 0; e < 8; ++e) qf[ks][e] = (half_t)((float)qf[ks][e] + (float)bq[hofs + ks * 16 + hf * 8 + e]);
+      for (int e = 0; e < 8; ++e) qf[ks][e] = (half_t)((float)qf[ks][e] + (float)b8[ks][e]);
   }
   // The Q loads must be complete BEFORE the tile loop.  Left to the compiler, their s_waitcnt vmcnt(3..0)
   // land at the first use inside the loop body and are executed by every iteration, where the only
@@ -525,7 +548,9 @@ __global__ __launch_bounds__(NK * 64) void varlen_mha_splitkey_kernel(
   for (int db = 0; db < 2; ++db)
 #pragma unroll
     for (int r = 0; r < 16; ++r) po[(db * 32 + 8 * (r >> 2) + 4 * hf + (r & 3)) * 32 + l32] = o_acc[db][r];
-  const float l_tot = l_run + __shfl_xor(l_run, 32, kWave);
+  float l_lo, l_hi;
+  both_halves(l_run, l_lo, l_hi);
+  const float l_tot = l_lo + l_hi;
   if (hf == 0) {
     pm[l32] = m_run;
     pl[l32] = l_tot;
@@ -560,15 +585,19 @@ __global__ __launch_bounds__(NK * 64) void varlen_mha_splitkey_kernel(
   }
   if (q_row < L) {
     half_t* op = out + (size_t)(tok0 + q_row) * (heads * kD) + hofs + d0;
+    half8_t b8[DL / 8];  // the value bias, requested in one go
+#pragma unroll
+    for (int c = 0; c < DL / 8; ++c) {
+      if (bv) b8[c] = *reinterpret_cast<const half8_t*>(bv + hofs + d0 + c * 8);
+      else
+#pragma unroll
+        for (int e = 0; e < 8; ++e) b8[c][e] = (half_t)0.f;
+    }
 #pragma unroll
     for (int c = 0; c < DL / 8; ++c) {
       half8_t h8;
 #pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        float v = o[c * 8 + e] * inv;
-        if (bv) v += (float)bv[hofs + d0 + c * 8 + e];
-        h8[e] = (half_t)v;
-      }
+      for (int e = 0; e < 8; ++e) h8[e] = (half_t)(o[c * 8 + e] * inv + (float)b8[c][e]);
       *reinterpret_cast<half8_t*>(op + c * 8) = h8;
     }
   }
@@ -641,6 +670,7 @@ extern "C" bt_status bt_varlen_mha(const bt_half* d_q, const bt_half* d_k, const
   if (!d_q || !d_k || !d_v || !d_cu_seqlens || !d_out) return BT_ERR_INVALID_ARG;
   if (!bt::aligned16(d_q) || !bt::aligned16(d_k) || !bt::aligned16(d_v) || !bt::aligned16(d_out))
     return BT_ERR_INVALID_ARG;
+  if ((d_bq && !bt::aligned16(d_bq)) || (d_bv && !bt::aligned16(d_bv))) return BT_ERR_INVALID_ARG;  // vector loads
   return bt::mha_dispatch(d_q, d_k, d_v, row_stride, d_bq, d_bk, d_bv, d_cu_seqlens, B, T, max_len, heads, scale,
                           d_out, static_cast<hipStream_t>(stream));
 }

@@ -56,10 +56,12 @@ def role_of(name: str, grid: int = 0):
         label = f"gemm_pipe<{bm}x{bn},{wgm}x{wgn} waves,{ns} stages,act={act},epi={epi},shape={shape}>"
         if epi == 3:
             return ("gemm3_ffn_down" if shape == 2 else "gemm1_proj"), label
+        if epi == 1:   # LayerNorm of the input folded into the epilogue (5-launch pipeline)
+            return ("gemm2_bias_gelu_folded" if act != 0 else ("gemm0_qkv_folded" if shape == 0 else "gemm_folded")), label
         if act != 0:
             return "gemm2_bias_gelu", label
-        if epi == 2:
-            return ("gemm3_ffn_down" if shape == 2 else "gemm1_proj"), label
+        if epi == 2:   # bias + residual + row sums in the epilogue (5-launch pipeline)
+            return ("gemm3_ffn_down_resid" if shape == 2 else "gemm1_proj_resid"), label
         return {0: "gemm0_qkv_bias", 1: "gemm1_proj", 2: "gemm3_ffn_down"}.get(shape, "gemm"), label
     if "gemm_simple_kernel" in name:
         return "gemm_fallback", "gemm_simple"
@@ -205,6 +207,11 @@ def main():
     work = {k["kernel"]: k for k in bench.get("kernels", [])}
     if "bias_residual_ln0" in work:
         work["bias_residual_ln"] = work["bias_residual_ln0"]
+    # the folded pipeline's GEMMs do the same products as the plain ones
+    for folded, plain in (("gemm0_qkv_folded", "gemm0_qkv_bias"), ("gemm2_bias_gelu_folded", "gemm2_bias_gelu"),
+                          ("gemm1_proj_resid", "gemm1_proj"), ("gemm3_ffn_down_resid", "gemm3_ffn_down")):
+        if plain in work:
+            work[folded] = work[plain]
 
     md = [f"# rocprofv3 summary: bench.py, workload `{args.workload}`", ""]
     if bench.get("config"):

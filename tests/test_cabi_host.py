@@ -69,6 +69,10 @@ def test_argument_errors_before_launch(lib):
                              None) == 2                          # max_len beyond BT_MAX_SEQ
     assert lib.bt_varlen_mha(one, one, one, 2304, None, None, None, one, 2, 10, 8, 12, 64, ctypes.c_float(-1.0),
                              one, None, 0, None) == 1
+    assert lib.bt_varlen_mha(one, one, one, 2304, None, None, odd, one, 2, 10, 8, 12, 64, f, one, None, 0,
+                             None) == 1                          # misaligned value bias
+    assert lib.bt_varlen_mha(one, one, one, 2304, odd, None, None, one, 2, 10, 8, 12, 64, f, one, None, 0,
+                             None) == 1                          # misaligned query bias
     # gemm / layernorm
     assert lib.bt_gemm_bias_act(one, one, None, 4, 12, 64, 0, one, None) == 1   # N % 8
     assert lib.bt_gemm_bias_act(one, one, None, 4, 16, 60, 0, one, None) == 1   # K % 8

@@ -15,6 +15,10 @@ def test_kernel_names_map_to_layer_steps():
     assert PS.role_of(g.format(256, 128, 4, 2, 3, 1, 0, 1))[0] == "gemm2_bias_gelu"
     assert PS.role_of(g.format(64, 128, 2, 4, 4, 0, 0, 2))[0] == "gemm3_ffn_down"
     assert PS.role_of(g.format(64, 64, 2, 2, 4, 0, 3, 2))[0] == "gemm3_ffn_down"      # split over K, deep
+    assert PS.role_of(g.format(192, 128, 2, 4, 3, 0, 1, 0))[0] == "gemm0_qkv_folded"   # folded pipeline
+    assert PS.role_of(g.format(256, 128, 4, 2, 3, 1, 1, 1))[0] == "gemm2_bias_gelu_folded"
+    assert PS.role_of(g.format(64, 128, 2, 4, 4, 0, 2, 1))[0] == "gemm1_proj_resid"
+    assert PS.role_of(g.format(64, 128, 2, 4, 4, 0, 2, 2))[0] == "gemm3_ffn_down_resid"
     assert PS.role_of(g.format(64, 64, 2, 2, 4, 0, 3, 1))[0] == "gemm1_proj"          # split over K, square
     assert PS.role_of("_ZN2bt17varlen_mha_kernelILi4ELi2EEEvPKiiifPKDF16_S4_S4_lPDF16_S4_S4_") == \
         ("varlen_mha", "varlen_mha<4,2>")
