@@ -13,10 +13,17 @@ namespace bt {
 // hint (measured +9 % on a 1.2 GB pass); at cache-resident sizes the next kernel wants the rows cached.
 template <int CPL, bool PART, bool STREAM>
 __global__ __launch_bounds__(256) void bias_residual_ln_kernel(
-    // what the loads at the top need first: it fits the 14 dwords preloaded into SGPRs at wave launch
-    const half_t* x, const half_t* residual, const half_t* __restrict__ bias, int T, int H, int nsplit, float eps,
-    const float* __restrict__ xpart, const int32_t* __restrict__ res_rows, const half_t* __restrict__ gamma,
-    const half_t* __restrict__ beta, half_t* y, const int32_t* __restrict__ out_idx, int out_rows) {
+    // Everything the kernel touches before its first batch of row loads is in flight comes first and fills exactly
+    // the 14 dwords that are preloaded into SGPRs at wave launch: the output index (decides the first branch), the
+    // four tensors of that batch, the residual's row index and the two sizes.  The rest arrives by scalar loads
+    // whose latency then hides behind the row loads (with gamma, beta and the output index behind such loads the
+    // kernel began with two exposed round trips to the kernel-argument buffer).
+    // xin: x (fp16 [T,H]), or with PART the fp32 K slices [nsplit][T][H] of x.
+    const void* __restrict__ xin, const half_t* residual, const half_t* __restrict__ gamma,
+    const half_t* __restrict__ beta, const int32_t* __restrict__ out_idx, const int32_t* __restrict__ res_rows, int T,
+    int H, const half_t* __restrict__ bias, half_t* y, int nsplit, float eps, int out_rows) {
+  const half_t* x = static_cast<const half_t*>(xin);
+  const float* xpart = static_cast<const float*>(xin);
   // res_rows: the residual of packed row i is row res_rows[i] of `residual` (pack fused into the read).
   // out_idx: y is the padded tensor [out_rows, H]; this wave owns padded row r, which is packed row
   //   `lo` if out_idx[lo] == r (out_idx is increasing: uniform binary search) and a zero row otherwise
@@ -47,43 +54,84 @@ __global__ __launch_bounds__(256) void bias_residual_ln_kernel(
   const size_t base = (size_t)row * H;
   const size_t rbase = res_rows ? (size_t)res_rows[row] * H : base;
 
+  // Every load of the row is issued before the first value is used, as straight-line code: chunk indices past the
+  // row are clamped (the lane's copy is ignored later) and a missing bias reads gamma with weight 0, so no branch
+  // splits the loads into batches that would each wait for the previous one -- the kernel is one memory round trip,
+  // not one per chunk and per operand.
   float v[CPL][8];
-  half8_t gm[CPL], bt[CPL];  // gamma and beta are requested with the row, not after the two reductions
+  half8_t gm[CPL], bt[CPL], rs[CPL], bs[CPL];  // gamma and beta are requested with the row, not after the reductions
+  int cc[CPL];
+#pragma unroll
+  for (int i = 0; i < CPL; ++i) cc[i] = min(lane + i * kWave, chunks - 1) * 8;
+#pragma unroll
+  for (int i = 0; i < CPL; ++i) {
+    rs[i] = STREAM ? __builtin_nontemporal_load(reinterpret_cast<const half8_t*>(residual + rbase + cc[i]))
+                   : *reinterpret_cast<const half8_t*>(residual + rbase + cc[i]);
+    gm[i] = *reinterpret_cast<const half8_t*>(gamma + cc[i]);
+    bt[i] = *reinterpret_cast<const half8_t*>(beta + cc[i]);
+  }
+  half8_t xs[PART ? 1 : CPL];
+  if constexpr (!PART) {
+#pragma unroll
+    for (int i = 0; i < CPL; ++i)
+      xs[i] = STREAM ? __builtin_nontemporal_load(reinterpret_cast<const half8_t*>(x + base + cc[i]))
+                     : *reinterpret_cast<const half8_t*>(x + base + cc[i]);
+  }
+  // the bias pointer is not among the preloaded kernel arguments: its loads go last, so that the scalar load of the
+  // pointer completes behind the row loads already in flight
+  __builtin_amdgcn_sched_barrier(0);
+  const half_t* const bsrc = bias ? bias : gamma;
+  const float bw = bias ? 1.f : 0.f;
+#pragma unroll
+  for (int i = 0; i < CPL; ++i) bs[i] = *reinterpret_cast<const half8_t*>(bsrc + cc[i]);
+  if constexpr (PART) {
+    // K slices of the product, four at a time where the registers allow (slice indices past nsplit are clamped
+    // and their values dropped): at the usual widths the up to eight slices cost two round trips, not one each
+    constexpr int G = CPL <= 2 ? 4 : (CPL <= 4 ? 2 : 1);
+#pragma unroll
+    for (int i = 0; i < CPL; ++i)
+#pragma unroll
+      for (int e = 0; e < 8; ++e) v[i][e] = 0.f;
+    for (int s0 = 0; s0 < nsplit; s0 += G) {
+      float4_t lo[G][CPL], hi[G][CPL];
+#pragma unroll
+      for (int k = 0; k < G; ++k)
+#pragma unroll
+        for (int i = 0; i < CPL; ++i) {
+          const float* src = xpart + (size_t)min(s0 + k, nsplit - 1) * T * H + base + cc[i];
+          lo[k][i] = *reinterpret_cast<const float4_t*>(src);
+          hi[k][i] = *reinterpret_cast<const float4_t*>(src + 4);
+        }
+#pragma unroll
+      for (int k = 0; k < G; ++k) {  // in slice order
+        const bool live = s0 + k < nsplit;
+#pragma unroll
+        for (int i = 0; i < CPL; ++i)
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            v[i][e] += live ? lo[k][i][e] : 0.f;
+            v[i][4 + e] += live ? hi[k][i][e] : 0.f;
+          }
+      }
+    }
+  } else {
+#pragma unroll
+    for (int i = 0; i < CPL; ++i)
+#pragma unroll
+      for (int e = 0; e < 8; ++e) v[i][e] = (float)xs[i][e];
+  }
+  // pinned here (after every load of the row has been issued): left alone, the compiler moves the gamma / beta loads down to the stores, a round trip of their own
+#pragma unroll
+  for (int i = 0; i < CPL; ++i) asm volatile("" : "+v"(gm[i]), "+v"(bt[i]), "+v"(bs[i]));
   float sum = 0.f;
 #pragma unroll
   for (int i = 0; i < CPL; ++i) {
-    const int c = lane + i * kWave;
-    if (c < chunks) {
-      gm[i] = *reinterpret_cast<const half8_t*>(gamma + c * 8);
-      bt[i] = *reinterpret_cast<const half8_t*>(beta + c * 8);
-      const half8_t r = STREAM ? __builtin_nontemporal_load(reinterpret_cast<const half8_t*>(residual + rbase + c * 8))
-                               : *reinterpret_cast<const half8_t*>(residual + rbase + c * 8);
-      if constexpr (PART) {
-        float acc8[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-        for (int sl = 0; sl < nsplit; ++sl) {
-          const float* src = xpart + (size_t)sl * T * H + base + c * 8;
-          const float4_t lo = *reinterpret_cast<const float4_t*>(src), hi = *reinterpret_cast<const float4_t*>(src + 4);
+    const bool mine = lane + i * kWave < chunks;
 #pragma unroll
-          for (int e = 0; e < 4; ++e) { acc8[e] += lo[e]; acc8[4 + e] += hi[e]; }
-        }
-#pragma unroll
-        for (int e = 0; e < 8; ++e) v[i][e] = acc8[e] + (float)r[e];
-      } else {
-        const half8_t a = STREAM ? __builtin_nontemporal_load(reinterpret_cast<const half8_t*>(x + base + c * 8))
-                                 : *reinterpret_cast<const half8_t*>(x + base + c * 8);
-#pragma unroll
-        for (int e = 0; e < 8; ++e) v[i][e] = (float)a[e] + (float)r[e];
-      }
-      if (bias) {
-        const half8_t b = *reinterpret_cast<const half8_t*>(bias + c * 8);
-#pragma unroll
-        for (int e = 0; e < 8; ++e) v[i][e] += (float)b[e];
-      }
-#pragma unroll
-      for (int e = 0; e < 8; ++e) sum += v[i][e];
-    } else {
-#pragma unroll
-      for (int e = 0; e < 8; ++e) v[i][e] = 0.f;
+    for (int e = 0; e < 8; ++e) {
+      const float t = (v[i][e] + (float)rs[i][e]) + bw * (float)bs[i][e];
+      v[i][e] = mine ? t : 0.f;
+      sum += v[i][e];
     }
   }
   const float inv_h = 1.0f / (float)H;
@@ -91,12 +139,11 @@ __global__ __launch_bounds__(256) void bias_residual_ln_kernel(
   float sq = 0.f;
 #pragma unroll
   for (int i = 0; i < CPL; ++i) {
-    if (lane + i * kWave < chunks) {
+    const bool mine = lane + i * kWave < chunks;
 #pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        const float d = v[i][e] - mean;
-        sq += d * d;
-      }
+    for (int e = 0; e < 8; ++e) {
+      const float d = mine ? v[i][e] - mean : 0.f;
+      sq += d * d;
     }
   }
   const float rstd = rsqrtf(wave_sum(sq) * inv_h + eps);
@@ -234,9 +281,9 @@ bt_status layernorm_dispatch(const bt_half* x, const float* xpart, int nsplit, c
   const bool stream = (size_t)T * H * 6 > ((size_t)256 << 20);  // three tensors larger than the 256 MB Infinity Cache
 #define BT_LN(CPL)                                                                                             \
   do {                                                                                                         \
-    if (xpart) bias_residual_ln_kernel<CPL, true, false><<<grid, block, 0, st>>>(px, pr, pb, T, H, nsplit, eps, xpart, res_rows, pg, pe, py, out_idx, out_rows); \
-    else if (stream) bias_residual_ln_kernel<CPL, false, true><<<grid, block, 0, st>>>(px, pr, pb, T, H, nsplit, eps, xpart, res_rows, pg, pe, py, out_idx, out_rows); \
-    else bias_residual_ln_kernel<CPL, false, false><<<grid, block, 0, st>>>(px, pr, pb, T, H, nsplit, eps, xpart, res_rows, pg, pe, py, out_idx, out_rows); \
+    if (xpart) bias_residual_ln_kernel<CPL, true, false><<<grid, block, 0, st>>>(xpart, pr, pg, pe, out_idx, res_rows, T, H, pb, py, nsplit, eps, out_rows); \
+    else if (stream) bias_residual_ln_kernel<CPL, false, true><<<grid, block, 0, st>>>(px, pr, pg, pe, out_idx, res_rows, T, H, pb, py, nsplit, eps, out_rows); \
+    else bias_residual_ln_kernel<CPL, false, false><<<grid, block, 0, st>>>(px, pr, pg, pe, out_idx, res_rows, T, H, pb, py, nsplit, eps, out_rows); \
   } while (0)
   if (chunks <= 64) BT_LN(1);
   else if (chunks <= 128) BT_LN(2);
