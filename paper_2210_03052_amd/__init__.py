@@ -11,6 +11,7 @@ from __future__ import annotations
 import ctypes
 import os
 import threading as _threading
+import weakref as _weakref
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_PKG, "libbt.so")
@@ -131,7 +132,10 @@ def _pinned_total():
     longest sequence) there and the host polls it."""
     t = getattr(_tls, "total", None)
     if t is None:
-        t = _tls.total = _torch().empty(2, dtype=_torch().int32, pin_memory=True)
+        t = _torch().empty(2, dtype=_torch().int32, pin_memory=True)
+        # (tensor, its address as the C pointer, a numpy view for cheap reads): the reads sit between the device
+        # writing the count and the first launch that needs it, where every host microsecond is device idle time
+        t = _tls.total = (t, _c.cast(t.data_ptr(), _c.POINTER(_c.c_int32)), t.numpy())
     return t
 
 
@@ -154,20 +158,20 @@ def build_offsets(mask=None, lengths=None, S=None, pinned=True, with_max=False):
         B, dev = lengths.shape[0], lengths.device
     cu = torch.empty(B + 2, dtype=torch.int32, device=dev)
     tok = torch.empty(max(1, B * S), dtype=torch.int32, device=dev)
+    cu_view = cu[: B + 1]  # made before the call: it does not depend on the count the host waits for
     name = "bt_build_offsets_stats" if with_max else "bt_build_offsets"
     if pinned:
-        slot = _pinned_total()
-        _call(name, _ptr(mask), _ptr(lengths), B, int(S), _ptr(cu), _ptr(tok),
-              _c.cast(slot.data_ptr(), _c.POINTER(_c.c_int32)), _stream())
-        T, mx = int(slot[0]), int(slot[1])
+        _, slot_ptr, slot_np = _pinned_total()
+        _call(name, _ptr(mask), _ptr(lengths), B, int(S), _ptr(cu), _ptr(tok), slot_ptr, _stream())
+        T, mx = int(slot_np[0]), int(slot_np[1])
     else:
         res = (_c.c_int32 * 2)(-1, -1)
         _call(name, _ptr(mask), _ptr(lengths), B, int(S), _ptr(cu), _ptr(tok),
               _c.cast(res, _c.POINTER(_c.c_int32)), _stream())
         T, mx = int(res[0]), int(res[1])
     if with_max:
-        return cu[: B + 1], tok[:T], T, mx
-    return cu[: B + 1], tok[:T], T
+        return cu_view, tok[:T], T, mx
+    return cu_view, tok[:T], T
 
 
 def pack(padded, token_idx, out=None):
@@ -363,12 +367,29 @@ def encoder_layer_fwd_static(layer: Layer, x, cu_seqlens, max_len, out):
     return out
 
 
+_layer_arrays = {}
+
+
+def _layer_array(layers):
+    """The C array of layer descriptors for a list of Layer objects, built once per distinct list.  The key is the
+    identity of the Layer objects (immutable once built); weak references tell a recycled id from the original
+    and keep the cache from holding device memory alive."""
+    key = tuple(map(id, layers))
+    hit = _layer_arrays.get(key)
+    if hit is None or any(r() is not l for r, l in zip(hit[1], layers)):
+        if len(_layer_arrays) > 64:
+            _layer_arrays.clear()
+        hit = _layer_arrays[key] = ((bt_layer * len(layers))(*[l.desc for l in layers]),
+                                    tuple(_weakref.ref(l) for l in layers))
+    return hit[0]
+
+
 def encoder_prepare(layers):
     """bt_encoder_prepare: the fold vectors (fp32, device) that move every LayerNorm of the stack
     into GEMM epilogues.  Depends on the parameters only: compute once, pass to encoder_fwd."""
     torch = _torch()
     lib = load_library()
-    arr = (bt_layer * len(layers))(*[l.desc for l in layers])
+    arr = _layer_array(layers)
     n = int(lib.bt_encoder_fold_bytes(arr, len(layers)))
     fold = torch.empty(n // 4, dtype=torch.float32, device=layers[0].tensors["w_o"].device)
     _call("bt_encoder_prepare", arr, len(layers), _ptr(fold), n, _stream())
@@ -388,7 +409,7 @@ def encoder_fwd(layers, x, cu_seqlens, max_len, out=None, ws=None, fold=None):
         out = torch.empty_like(x)
     if ws is None:
         ws, _ = _workspace(layers[0], T, B, max_len, x.device)
-    arr = (bt_layer * len(layers))(*[l.desc for l in layers])
+    arr = _layer_array(layers)
     _call("bt_encoder_fwd", arr, len(layers), _ptr(fold), _ptr(x), _ptr(cu_seqlens), B, T, int(max_len), _ptr(out),
           _ptr(ws), ws.numel(), _stream())
     return out
@@ -407,7 +428,7 @@ def encoder_fwd_padded(layers, x_padded, token_idx, cu_seqlens, out=None, ws=Non
         out = torch.empty_like(x_padded)
     if ws is None:
         ws, _ = _workspace(layers[0], max(T, 1), B, S, x_padded.device)
-    arr = (bt_layer * len(layers))(*[l.desc for l in layers])
+    arr = _layer_array(layers)
     if fold is not None:
         _chk(fold, torch.float32, "fold", 1)
     _call("bt_encoder_fwd_padded", arr, len(layers), _ptr(fold), _ptr(x_padded), _ptr(token_idx), _ptr(cu_seqlens),
