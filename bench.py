@@ -302,13 +302,16 @@ def timed_steps(torch, step, steps, warmup):
     for _ in range(warmup):
         step(lambda: None)
     torch.cuda.synchronize()
-    stamps = []
+    stamps, returned = [], []
     mark = lambda: stamps.append(time.perf_counter())
     t0 = time.perf_counter()
     for _ in range(steps):
         step(mark)
+        returned.append(time.perf_counter())
     torch.cuda.synchronize()
     t1 = time.perf_counter()
+    # host time from the mark (the token count is known) to the step's return (every launch enqueued)
+    timed_steps.host_enqueue_s = sorted(r - m for m, r in zip(stamps, returned))[len(returned) // 2] if stamps else None
     stamps.append(t1)
     per = [b - a for a, b in zip(stamps[:-1], stamps[1:])]
     return t1 - t0, per
@@ -667,6 +670,7 @@ def main():
     torch.cuda.synchronize()
     dt, per = timed_steps(torch, step, args.steps, args.warmup)
     stats = step_stats(wl.B, dt, per)
+    host_enqueue_s = timed_steps.host_enqueue_s
     flops_step = nl * (24.0 * T * H * H + 4.0 * sum_l2 * H)
 
     out = {
@@ -681,6 +685,9 @@ def main():
                    "step": step_name, "layernorm_fold_vectors_given": fold is not None,
                    "device_settle_steps_before_warmup": n_settle},
         "useful_tflops_per_s": round(flops_step / (stats["ms_per_step"] * 1e-3) / 1e12, 2),
+        # median host time from "the token count is known" to "every launch of the step is enqueued": when this
+        # approaches ms_per_step the machine's host, not its GPU, paces the step
+        "host_enqueue_ms_per_step": None if host_enqueue_s is None else round(host_enqueue_s * 1e3, 4),
     }
 
     # ---------------- the same step with the fold vectors handed over (extra point; see --fold)
