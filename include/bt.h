@@ -292,6 +292,23 @@ bt_status bt_encoder_fwd_padded(const bt_layer* layers, int n_layers, const floa
                                 const int32_t* d_cu_seqlens, int B, int T, int S, bt_half* d_y_padded, void* d_ws,
                                 size_t ws_bytes, bt_stream stream);
 
+/*
+ * bt_build_offsets followed by bt_encoder_fwd_padded in one call (Sec. III-D, Fig. 2 (c): the prefix sum of the mask
+ * and the packed layers it feeds).  Same kernels, same results, same arguments with the same meaning as in the two
+ * calls: d_mask / d_lengths (exactly one non-NULL), d_cu_seqlens [B+1] and d_token_idx [B*S] are written as by
+ * bt_build_offsets, *h_total receives the token count (host memory; pinned and device-mapped memory avoids a stream
+ * synchronisation), d_y_padded as by bt_encoder_fwd_padded.  What the single call saves is host time: the count that
+ * the host waits for goes into the launches of the layers without returning to the caller first, and while the
+ * host holds that count without having launched, the device has nothing to do (about 10 us per batch through a
+ * scripting-language binding).  The workspace must be large enough for every count: at least
+ * bt_layer_workspace_bytes(layers, B*S, B, S).  Argument errors are reported before anything runs.  Like
+ * bt_build_offsets this call waits on the host and is refused (BT_ERR_UNSUPPORTED) on a capturing stream.
+ */
+bt_status bt_encoder_fwd_masked(const bt_layer* layers, int n_layers, const float* d_fold,
+                                const bt_half* d_x_padded, const int32_t* d_mask, const int32_t* d_lengths, int B,
+                                int S, int32_t* d_cu_seqlens, int32_t* d_token_idx, int32_t* h_total,
+                                bt_half* d_y_padded, void* d_ws, size_t ws_bytes, bt_stream stream);
+
 #ifdef __cplusplus
 }
 #endif

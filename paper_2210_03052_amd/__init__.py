@@ -73,6 +73,9 @@ _SIGNATURES = {
     "bt_encoder_fwd_padded": (_c.c_int, [_c.POINTER(bt_layer), _c.c_int, _c.c_void_p, _c.c_void_p, _c.c_void_p,
                                          _c.c_void_p, _c.c_int, _c.c_int, _c.c_int, _c.c_void_p, _c.c_void_p,
                                          _c.c_size_t, _c.c_void_p]),
+    "bt_encoder_fwd_masked": (_c.c_int, [_c.POINTER(bt_layer), _c.c_int, _c.c_void_p, _c.c_void_p, _c.c_void_p,
+                                         _c.c_void_p, _c.c_int, _c.c_int, _c.c_void_p, _c.c_void_p,
+                                         _c.POINTER(_c.c_int32), _c.c_void_p, _c.c_void_p, _c.c_size_t, _c.c_void_p]),
 }
 EXPORTED = tuple(_SIGNATURES)
 
@@ -434,3 +437,39 @@ def encoder_fwd_padded(layers, x_padded, token_idx, cu_seqlens, out=None, ws=Non
     _call("bt_encoder_fwd_padded", arr, len(layers), _ptr(fold), _ptr(x_padded), _ptr(token_idx), _ptr(cu_seqlens),
           B, T, S, _ptr(out), _ptr(ws), ws.numel(), _stream())
     return out
+
+
+def encoder_fwd_masked(layers, x_padded, mask=None, lengths=None, out=None, ws=None, fold=None):
+    """bt_encoder_fwd_masked: build_offsets + encoder_fwd_padded in one call of the library -- the token count goes
+    from the prefix-sum kernel into the launches of the layers without passing through Python.
+    x_padded fp16 [B,S,H]; exactly one of mask int32 [B,S] / lengths int32 [B].  `ws` must hold B*S tokens
+    (layer_workspace_bytes(layers[0], B*S, B, S)).  Returns (out [B,S,H], cu_seqlens [B+1], token_idx [T], T)."""
+    torch = _torch()
+    _chk(x_padded, torch.float16, "x_padded", 3)
+    if (mask is None) == (lengths is None):
+        raise ValueError("give exactly one of mask / lengths")
+    B, S, _ = x_padded.shape
+    if mask is not None:
+        _chk(mask, torch.int32, "mask", 2)
+        if tuple(mask.shape) != (B, S):
+            raise ValueError("mask must be [B,S]")
+    else:
+        _chk(lengths, torch.int32, "lengths", 1)
+        if lengths.shape[0] != B:
+            raise ValueError("lengths must be [B]")
+    if fold is not None:
+        _chk(fold, torch.float32, "fold", 1)
+    dev = x_padded.device
+    if out is None:
+        out = torch.empty_like(x_padded)
+    if ws is None:
+        ws, _ = _workspace(layers[0], max(B * S, 1), B, S, dev)
+    cu = torch.empty(B + 2, dtype=torch.int32, device=dev)
+    tok = torch.empty(max(1, B * S), dtype=torch.int32, device=dev)
+    cu_view = cu[: B + 1]
+    _, slot_ptr, slot_np = _pinned_total()
+    _call("bt_encoder_fwd_masked", _layer_array(layers), len(layers), _ptr(fold), _ptr(x_padded), _ptr(mask),
+          _ptr(lengths), B, S, _ptr(cu), _ptr(tok), slot_ptr, _ptr(out), _ptr(ws), ws.numel(), _stream())
+    T = int(slot_np[0])
+    return out, cu_view, tok[:T], T
+

@@ -411,3 +411,28 @@ extern "C" bt_status bt_encoder_fwd_padded(const bt_layer* layers, int n_layers,
   }
   return BT_OK;
 }
+
+// bt_build_offsets followed by bt_encoder_fwd_padded in one call: the token count the first call waits for
+// goes straight into the launches of the second, with no host code of the caller in between (while the host
+// holds the count and has not launched yet, the device is idle).
+extern "C" bt_status bt_encoder_fwd_masked(const bt_layer* layers, int n_layers, const float* d_fold,
+                                           const bt_half* d_x_padded, const int32_t* d_mask,
+                                           const int32_t* d_lengths, int B, int S, int32_t* d_cu_seqlens,
+                                           int32_t* d_token_idx, int32_t* h_total, bt_half* d_y_padded, void* d_ws,
+                                           size_t ws_bytes, bt_stream stream) {
+  // everything that can be refused is refused before the prefix-sum kernel runs
+  bt_status s = check_stack(layers, n_layers);
+  if (s != BT_OK) return s;
+  if (d_fold && (reinterpret_cast<uintptr_t>(d_fold) & 15u)) return BT_ERR_INVALID_ARG;
+  if (B > 0 && S > 0) {
+    if (!d_x_padded || !d_y_padded || d_x_padded == d_y_padded || !aligned16(d_x_padded) || !aligned16(d_y_padded))
+      return BT_ERR_INVALID_ARG;
+    if ((int64_t)B * S >= (int64_t)INT32_MAX) return BT_ERR_UNSUPPORTED;
+    if (!d_ws || (reinterpret_cast<uintptr_t>(d_ws) & 255u)) return BT_ERR_WORKSPACE;
+    if (ws_bytes < carve(d_ws, B * S, layers[0].H, layers[0].F).bytes) return BT_ERR_WORKSPACE;  // any count fits
+  }
+  if ((s = bt_build_offsets(d_mask, d_lengths, B, S, d_cu_seqlens, d_token_idx, h_total, stream)) != BT_OK) return s;
+  return bt_encoder_fwd_padded(layers, n_layers, d_fold, d_x_padded, d_token_idx, d_cu_seqlens, B, h_total[0], S,
+                               d_y_padded, d_ws, ws_bytes, stream);
+}
+

@@ -200,7 +200,7 @@ def sweep_summary(path_json: str, out: str) -> None:
           f"Lengths are drawn `{d['length_law']}`, the end-to-end protocol of Sec. IV-E, seeded. \"all tokens valid\" runs the",
           "same kernels on the same batch with every sequence at full length, i.e. what a padded pipeline computes;",
           "the ratio is the gain from removing padding (Sec. III-D; the paper reports +24 % per layer at mean 0.6 max on A100).",
-          "Each figure is the whole step (`bt_build_offsets` + `bt_encoder_fwd_padded`: 12 layers with pack / unpack fused into the",
+          "Each figure is the whole step (`bt_encoder_fwd_masked` = `bt_build_offsets` + `bt_encoder_fwd_padded`: 12 layers with pack / unpack fused into the",
           "first / last kernels), 50 timed iterations.", "",
           "| batch | max_seq | valid tokens | ms packed | ms all tokens valid | gain |", "|---|---|---|---|---|---|"]
     for r in rows:

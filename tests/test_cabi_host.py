@@ -126,6 +126,16 @@ def test_layer_checks(lib):
     assert pad(ws_=None) == 3 and pad(nb=n - 1) == 3
     assert lib.bt_encoder_fwd_padded((bt.bt_layer * 1)(good), 1, ctypes.c_void_p(4), x, cu, cu, 4, 100, 64, y, ws, n,
                                      None) == 1                 # misaligned fold vectors
+    # build_offsets + padded forward in one call: every refusal comes before the prefix-sum kernel would run
+    n_all = lib.bt_layer_workspace_bytes(ctypes.byref(good), 4 * 64, 4, 64)
+    tot = (ctypes.c_int32 * 2)()
+    masked = lambda x_=x, y_=y, ws_=ws, nb=n_all, L=good, fold=None: lib.bt_encoder_fwd_masked(
+        (bt.bt_layer * 1)(L), 1, fold, x_, None, cu, 4, 64, cu, cu, tot, y_, ws_, nb, None)
+    assert masked(nb=n) == 3                                   # workspace for 100 tokens, but B*S = 256 may come
+    assert masked(ws_=None) == 3
+    assert masked(x_=None) == 1 and masked(y_=x) == 1
+    assert masked(fold=ctypes.c_void_p(4)) == 1                # misaligned fold vectors
+    assert masked(L=bt.bt_layer(768, 12, 32, 3072, 1e-12, 0, *[one] * 12)) == 2  # head_dim
     same = (bt.bt_layer * 2)(good, good)
     fb = lib.bt_encoder_fold_bytes(same, 2)
     assert fb == 2 * (6 * 768 + 2 * 3072) * 4

@@ -471,9 +471,10 @@ def test_stack_bert_base_b16_s256(bt):
     err = max(np.abs(full[cuh[b]: cuh[b + 1]].astype(np.float64) - ref[b]).max() for b in seqs)
     assert err <= TOL_12, err
     # the step bench.py times: offsets, then the stack on padded tensors (pack / unpack inside the first / last
-    # kernels), all 12 layers -- against the oracle on every sequence, pads zero
-    _, tok, _ = bt.build_offsets(lengths=dev(L), S=wl.S)
-    ypad = host(bt.encoder_fwd_padded(layers, dev(I.pad_rows(x, L, wl.S)), tok, cu)).astype(np.float64)
+    # kernels), all 12 layers, as one call of the library -- against the oracle on every sequence, pads zero
+    ypad_d, _, _, t_step = bt.encoder_fwd_masked(layers, dev(I.pad_rows(x, L, wl.S)), lengths=dev(L))
+    assert t_step == int(L.sum())
+    ypad = host(ypad_d).astype(np.float64)
     for b in seqs:
         assert np.abs(ypad[b, : L[b]] - ref[b]).max() <= TOL_12
         assert not ypad[b, L[b]:].any()
@@ -574,6 +575,31 @@ def test_encoder_fwd_padded_equals_pack_fwd_unpack(bt, name, n_layers, stress, f
     assert torch.equal(got, want) and torch.equal(xpad, keep)
     mask = O.lengths_to_mask(L, wl.S).astype(bool)
     assert float(got[torch.from_numpy(~mask).to("cuda:0")].abs().sum()) == 0.0
+
+
+@pytest.mark.parametrize("folded", [False, True])
+@pytest.mark.parametrize("use_mask", [False, True])
+def test_encoder_fwd_masked_equals_the_two_calls(bt, use_mask, folded):
+    """build_offsets + encoder_fwd_padded as one call of the library: same offsets, same count, same bits, from a
+    mask or from lengths, plain and folded, including an empty sequence and an all-padding batch."""
+    import torch
+    wl = I.WORKLOADS["bert_base_b16_s256"]
+    L = I.draw_lengths(wl)
+    L[3] = 0
+    T = int(L.sum())
+    xpad = dev(I.pad_rows(I.make_hidden_packed(wl, T), L, wl.S, fill=5.0))
+    layers = [bt.Layer(I.make_layer_params(wl, i)) for i in range(2)]
+    fold = bt.encoder_prepare(layers) if folded else None
+    mask = dev(O.lengths_to_mask(L, wl.S).astype(np.int32)) if use_mask else None
+    lengths = None if use_mask else dev(L)
+    cu, tok, t = bt.build_offsets(mask=mask, lengths=lengths, S=wl.S)
+    want = bt.encoder_fwd_padded(layers, xpad, tok, cu, fold=fold)
+    got, cu2, tok2, t2 = bt.encoder_fwd_masked(layers, xpad, mask=mask, lengths=lengths, fold=fold)
+    assert t2 == t == T and torch.equal(cu2, cu) and torch.equal(tok2, tok) and torch.equal(got, want)
+    # nothing valid at all: the output is all zeros and the count is 0
+    zero = dev(np.zeros(wl.B, np.int32))
+    got0, _, tok0, t0 = bt.encoder_fwd_masked(layers, xpad, lengths=zero, out=torch.full_like(xpad, 3.0), fold=fold)
+    assert t0 == 0 and tok0.numel() == 0 and float(got0.abs().sum()) == 0.0
 
 
 def test_encoder_fwd_graph_replay_equals_eager(bt):
