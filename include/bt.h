@@ -301,7 +301,9 @@ bt_status bt_encoder_fwd_padded(const bt_layer* layers, int n_layers, const floa
  * the host waits for goes into the launches of the layers without returning to the caller first, and while the
  * host holds that count without having launched, the device has nothing to do (about 10 us per batch through a
  * scripting-language binding).  The workspace must be large enough for every count: at least
- * bt_layer_workspace_bytes(layers, B*S, B, S).  Argument errors are reported before anything runs.  Like
+ * bt_layer_workspace_bytes(layers, B*S, B, S).  Errors the host can see are reported before anything runs; a
+ * length outside [0, S] is found by the prefix-sum kernel and reported as by bt_build_offsets, and then no layer
+ * is launched.  Like
  * bt_build_offsets this call waits on the host and is refused (BT_ERR_UNSUPPORTED) on a capturing stream.
  */
 bt_status bt_encoder_fwd_masked(const bt_layer* layers, int n_layers, const float* d_fold,

@@ -600,6 +600,13 @@ def test_encoder_fwd_masked_equals_the_two_calls(bt, use_mask, folded):
     zero = dev(np.zeros(wl.B, np.int32))
     got0, _, tok0, t0 = bt.encoder_fwd_masked(layers, xpad, lengths=zero, out=torch.full_like(xpad, 3.0), fold=fold)
     assert t0 == 0 and tok0.numel() == 0 and float(got0.abs().sum()) == 0.0
+    # a length beyond S is found by the prefix-sum kernel: the call reports it and launches no layer
+    bad = dev(np.array([wl.S + 1] + [1] * (wl.B - 1), np.int32))
+    untouched = torch.full_like(xpad, 3.0)
+    with pytest.raises(bt.BtError):
+        bt.encoder_fwd_masked(layers, xpad, lengths=bad, out=untouched, fold=fold)
+    torch.cuda.synchronize()
+    assert float((untouched - 3.0).abs().sum()) == 0.0
 
 
 def test_encoder_fwd_graph_replay_equals_eager(bt):
