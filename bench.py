@@ -621,6 +621,9 @@ def main():
                 rounds = -(-tiles // 256)
                 kernels[-1].update({"tile": f"{bm}x{bn}", "tiles": tiles, "rounds_of_256_cus": rounds,
                                     "tile_quantisation_ceiling": round(M_ * N_ / (tiles * bm * bn) * tiles / (rounds * 256), 4)})
+                split_rows = bt.gemm_row_split(M_, N_, K_, act_)
+                if split_rows:   # run as two launches over row ranges; the figures above describe one launch
+                    kernels[-1]["rows_of_first_launch"] = split_rows
         dom = max(kernels, key=lambda k: k["us"] * k["launches_per_step"])
         out["roofline"] = {"kernel": dom["kernel"], "bound": dom["bound"], "achieved": dom["achieved"],
                            "peak": dom["peak"], "unit": dom["unit"], "frac": dom["frac"],

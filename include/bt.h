@@ -157,6 +157,16 @@ bt_status bt_gemm_bias_act(const bt_half* d_A, const bt_half* d_W, const bt_half
 bt_status bt_gemm_tile_shape(int M, int N, int K, bt_act act, int* bm, int* bn);
 
 /*
+ * Whether bt_gemm_bias_act runs an M x N x K product as two launches over row ranges (host only, nothing is
+ * launched).  A tile grid that needs slightly more than a whole number of rounds of the 256 compute units pays a
+ * whole round for its last few tiles; rows are independent, so the library then runs the rows that fill whole
+ * rounds first and the remaining rows with the tile shape that suits them (Sec. III-C2 product, same function;
+ * a row's value can differ in the last fp16 digit from the single launch where the two launches use different
+ * tile shapes).  *rows_first = number of leading rows of the first launch, 0 = a single launch.  For reports.
+ */
+bt_status bt_gemm_row_split(int M, int N, int K, bt_act act, int* rows_first);
+
+/*
  * Fused add-bias + residual + LayerNorm, Sec. III-C1:
  *   y[i,:] = LN(x[i,:] + bias + residual[i,:]) * gamma + beta,   one pass over memory.
  * x, residual, y fp16 [T,H]; bias, gamma, beta fp16 [H]; bias may be NULL.

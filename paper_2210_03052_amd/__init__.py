@@ -70,6 +70,7 @@ _SIGNATURES = {
     "bt_encoder_fwd": (_c.c_int, [_c.POINTER(bt_layer), _c.c_int, _c.c_void_p, _c.c_void_p, _c.c_void_p, _c.c_int,
                                   _c.c_int, _c.c_int, _c.c_void_p, _c.c_void_p, _c.c_size_t, _c.c_void_p]),
     "bt_gemm_tile_shape": (_c.c_int, [_c.c_int, _c.c_int, _c.c_int, _c.c_int, _c.POINTER(_c.c_int), _c.POINTER(_c.c_int)]),
+    "bt_gemm_row_split": (_c.c_int, [_c.c_int, _c.c_int, _c.c_int, _c.c_int, _c.POINTER(_c.c_int)]),
     "bt_encoder_fwd_padded": (_c.c_int, [_c.POINTER(bt_layer), _c.c_int, _c.c_void_p, _c.c_void_p, _c.c_void_p,
                                          _c.c_void_p, _c.c_int, _c.c_int, _c.c_int, _c.c_void_p, _c.c_void_p,
                                          _c.c_size_t, _c.c_void_p]),
@@ -256,6 +257,13 @@ def gemm_bias_act(a, w, bias=None, act=ACT_NONE, out=None):
         out = torch.empty((M, N), dtype=torch.float16, device=a.device)
     _call("bt_gemm_bias_act", _ptr(a), _ptr(w), _ptr(bias), M, N, K, int(act), _ptr(out), _stream())
     return out
+
+
+def gemm_row_split(M, N, K, act=ACT_NONE):
+    """bt_gemm_row_split: number of leading rows bt_gemm_bias_act gives a launch of their own (0 = one launch)."""
+    rows = _c.c_int(0)
+    _call("bt_gemm_row_split", int(M), int(N), int(K), int(act), _c.byref(rows))
+    return rows.value
 
 
 def gemm_tile_shape(M, N, K, act=ACT_NONE):

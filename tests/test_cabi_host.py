@@ -214,3 +214,19 @@ def test_gemm_tile_shape_query_is_host_only():
     for bad in ((10, 7, 64), (10, 8, 60), (-1, 8, 64)):
         with pytest.raises(bt.BtError):
             bt.gemm_tile_shape(*bad)
+
+
+def test_gemm_row_split_query_is_host_only():
+    """bt_gemm_row_split: products whose tile grid fills its rounds run as one launch (the four products of the
+    headline layer, the long and the large workload's FFN-down); a grid a little past a whole number of rounds
+    gives its leading rows -- whole tile rows, whole rounds -- a launch of their own."""
+    for shape in ((2308, 2304, 768), (2308, 768, 768), (2308, 768, 3072), (9894, 768, 3072), (4648, 1024, 4096)):
+        assert bt.gemm_row_split(*shape) == 0
+    assert bt.gemm_row_split(2308, 3072, 768, bt.ACT_GELU_ERF) == 0
+    r = bt.gemm_row_split(2752, 3072, 768, bt.ACT_GELU_ERF)        # 11 x 24 tiles of 256 x 128: 8 past one round
+    assert r == 2560                                                # 10 tile rows x 24 = 240 tiles, one round
+    r = bt.gemm_row_split(6400, 4096, 1024, bt.ACT_GELU_ERF)
+    assert 0 < r < 6400 and r % 64 == 0
+    assert bt.gemm_row_split(100, 768, 72) == 0                     # fallback kernel: never split
+    with pytest.raises(bt.BtError):
+        bt.gemm_row_split(10, 7, 64)

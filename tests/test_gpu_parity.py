@@ -182,7 +182,8 @@ def test_gemm_slab_schedule_all_residues(bt, M, N):
     (1, 8, 8, 0, False), (5, 16, 40, 0, True), (77, 72, 200, 1, True), (150, 2304, 768, 0, True),
     (129, 768, 3072, 0, False), (300, 3072, 768, 1, True), (2456, 768, 768, 0, True), (2456, 3072, 768, 2, True),
     (1000, 1024, 4096, 0, True), (4710, 4096, 1024, 1, True), (2308, 2304, 768, 0, True), (4648, 1024, 4096, 0, False),
-    (2305, 2312, 832, 1, True), (2699, 768, 3072, 0, True), (2764, 1024, 1024, 1, True)])
+    (2305, 2312, 832, 1, True), (2699, 768, 3072, 0, True), (2764, 1024, 1024, 1, True),
+    (2752, 3072, 768, 1, True), (6300, 4096, 1024, 1, True), (8200, 2304, 768, 0, True)])   # run as two row ranges
 def test_gemm_bias_act(bt, M, N, K, act, bias):
     rng = np.random.default_rng(M + N + K)
     a = rng.normal(0, 1, (M, K)).astype(np.float16)
@@ -607,6 +608,34 @@ def test_encoder_fwd_masked_equals_the_two_calls(bt, use_mask, folded):
         bt.encoder_fwd_masked(layers, xpad, lengths=bad, out=untouched, fold=fold)
     torch.cuda.synchronize()
     assert float((untouched - 3.0).abs().sum()) == 0.0
+
+
+def test_padded_stack_where_the_first_gemm_runs_as_two_row_ranges(bt):
+    """8 200 tokens at width 768: the QKV product's tile grid is a little past two rounds, so it runs as two
+    launches over row ranges -- with the pack fused into its operand load the second launch must continue in
+    the row index, not in the matrix.  Same bits as pack + forward + unpack, and within the layer tolerance
+    of the oracle on two sequences."""
+    import torch
+    wl = I.WORKLOADS["bert_base_b16_s1024"]
+    assert bt.gemm_row_split(8200, 3 * wl.H, wl.H) > 0
+    L = (512 + np.arange(wl.B) * 7 % 97 - 48).astype(np.int32)          # ragged lengths around 512
+    L[-1] += 8200 - int(L.sum())
+    assert 0 < L.min() and L.max() <= wl.S and int(L.sum()) == 8200
+    x = I.make_hidden_packed(wl, 8200)
+    xpad = dev(I.pad_rows(x, L, wl.S, fill=9.0))
+    params = I.make_layer_params(wl, 0)
+    layers = [bt.Layer(params)]
+    cu, tok, t = bt.build_offsets(lengths=dev(L), S=wl.S)
+    want = bt.unpack(bt.encoder_fwd(layers, bt.pack(xpad, tok), cu, wl.S), tok, wl.B, wl.S)
+    got = bt.encoder_fwd_padded(layers, xpad, tok, cu)
+    assert torch.equal(got, want)
+    ow = O.LayerWeights(**params)
+    cuh = np.concatenate([[0], np.cumsum(L)])
+    gh = host(got).astype(np.float64)
+    for b in (0, wl.B - 1):                                   # first and last sequence: both row ranges
+        xb = x[cuh[b]: cuh[b + 1]].astype(np.float64)[None]
+        ref = O.encoder_layer(xb, np.ones((1, L[b]), np.int32), ow)[0]
+        assert np.abs(gh[b, : L[b]] - ref).max() <= TOL_LAYER
 
 
 def test_encoder_fwd_graph_replay_equals_eager(bt):
