@@ -301,12 +301,30 @@ def main():
         md += ["## Kernel trace (`--kernel-trace --stats`)", "",
                "| step | kernel | calls | avg us | min us | max us | useful work / avg time | of peak |", "|---|---|---|---|---|---|---|---|"]
         tot = sum(sum(v) for v in dur.values())
+        # A product that the library runs as two launches over row ranges shows up as two GEMM kernels of one
+        # step with the same number of calls: the step's work belongs to the two together, not to either.
+        by_role = collections.defaultdict(list)
+        for label in dur:
+            by_role[roles[label]].append(label)
+        halves = {}
+        for role, labels in by_role.items():
+            if role.startswith("gemm") and len(labels) > 1:
+                top = max(labels, key=lambda l: len(dur[l]))
+                pair = [l for l in labels if abs(len(dur[l]) - len(dur[top])) <= 0.02 * len(dur[top])]
+                if len(pair) == 2:
+                    both = sum(sum(dur[l]) / len(dur[l]) for l in pair)
+                    for l in pair:
+                        halves[l] = both
         for label, v in sorted(dur.items(), key=lambda kv: -sum(kv[1])):
             role = roles[label]
             avg = sum(v) / len(v)
             w = work.get(role)
             rate = frac = ""
-            if w and role not in ("bias_residual_ln_streaming", "pack_streaming"):
+            if label in halves and w:
+                r_ = w["work_per_launch"] / halves[label] / 1e6
+                rate = f"two row ranges, {halves[label]:.2f} us together: {r_:.0f} TFLOP/s"
+                frac = f"{r_ / w['peak']:.3f}"
+            elif w and role not in ("bias_residual_ln_streaming", "pack_streaming"):
                 if w["bound"] == "mfma":
                     r_ = w["work_per_launch"] / avg / 1e6
                     rate, frac = f"{r_:.0f} TFLOP/s", f"{r_ / w['peak']:.3f}"
@@ -334,6 +352,19 @@ def main():
                 dv["useful_share_of_executed"] = dv["useful_gflop"] / dv["executed_gflop"]
             if dv:
                 derived.append((roles[label], label, dv))
+        # a product run as two launches over row ranges: its useful FLOPs are to be set against the two together
+        pairs = collections.defaultdict(list)
+        for role, label, dv in derived:
+            if role.startswith("gemm") and "useful_gflop" in dv:
+                pairs[role].append((label, dv))
+        for role, items in pairs.items():
+            top = max(n[l] for l, _ in items)
+            both = [(l, dv) for l, dv in items if abs(n[l] - top) <= 0.02 * top]
+            if len(both) == 2:
+                executed = sum(dv["executed_gflop"] for _, dv in both)
+                for _, dv in both:
+                    dv["executed_gflop_of_both_row_ranges"] = executed
+                    dv["useful_share_of_executed"] = dv["useful_gflop"] / executed
         if derived:
             md += ["", "Derived:", ""]
             for role, label, dv in derived:
